@@ -1,0 +1,168 @@
+/* plora.h - C ABI of the paged multi-LoRA library for MI355X (gfx950).
+ *
+ * The library computes the heterogeneous-rank multi-LoRA delta of Predictive-LoRA: for every
+ * token t of a batch whose adapter is i,
+ *        y[t,:] += scale_i * (x[t,:] * A_i^T) * B_i
+ * (Sec. II-A, Eq. 1: W = W0 + B A; stored orientation below), where A_i and B_i live in a pool
+ * of fixed-size GPU pages and are gathered through a per-adapter page table (Sec. III-C "Page
+ * Structure", "Page Table"; Sec. IV "Memory Manager").  Around the two kernels sit the page
+ * allocator that places and evicts adapters (Sec. III-C; Sec. III-B "Eviction Policy",
+ * mechanism only) and the pinned-host -> GPU copy that fills the pages (Sec. III-B "Prefetch
+ * Scheduling").
+ *
+ * Conventions
+ *  - Every call returns a plora_status; a failed call leaves the pool unchanged.
+ *  - "host" / "device" is stated for every pointer.  Streams are hipStream_t values passed as
+ *    plain pointers (plora_stream); NULL is the null stream.
+ *  - A *slot* is one linear map d_in -> d_out that every adapter of the pool covers.  An adapter of
+ *    rank r is one contiguous blob of  S = r * elt * sum_slots(d_in + d_out)  bytes, slot after
+ *    slot, each slot as [A_s | B_s] with A_s = r rows of d_in elements and B_s = r rows of d_out
+ *    elements (both rank-major, no padding).  A_s is the paper's A; B_s is the paper's B transposed.
+ *  - The blob occupies ceil(S / page_bytes) pages: the lowest-numbered free pages, in ascending
+ *    order (first fit).  Virtual byte o of the blob lives at slab + pt[o / P] * P + o % P.
+ *  - Not thread safe: one host thread drives a pool.
+ */
+#ifndef PLORA_H
+#define PLORA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct plora_pool plora_pool;   /* opaque, owned by the library */
+typedef struct plora_batch plora_batch; /* opaque, owned by the pool that made it */
+typedef void* plora_stream;             /* a hipStream_t */
+
+typedef enum {
+  PLORA_OK = 0,
+  PLORA_ERR_INVAL = -1,    /* bad argument, alignment, rank, id or size */
+  PLORA_ERR_NOMEM = -2,    /* fewer free pages than needed; nothing was allocated */
+  PLORA_ERR_EXISTS = -3,   /* id already resident (or still loading) */
+  PLORA_ERR_NOTFOUND = -4, /* id not resident */
+  PLORA_ERR_BUSY = -5,     /* evict of an adapter whose load has not completed or that an open batch uses */
+  PLORA_ERR_HIP = -6       /* a HIP runtime call failed; see plora_last_hip */
+} plora_status;
+
+typedef enum { PLORA_F16 = 0, PLORA_BF16 = 1, PLORA_F32 = 2 } plora_dtype;
+
+typedef struct {
+  int32_t n_slots;      /* >= 1 */
+  const int32_t* d_in;  /* host, n_slots entries, each > 0 and a multiple of 8 */
+  const int32_t* d_out; /* host, n_slots entries, each > 0 and a multiple of 8 */
+  int32_t dtype;        /* plora_dtype of weights, x and y */
+  int32_t max_adapters; /* adapter ids are 0 .. max_adapters-1 */
+  int32_t max_rank;     /* 1 <= rank <= max_rank <= 512; also the row stride of v */
+} plora_layout;
+
+/* plora_pool_create flags */
+#define PLORA_POOL_PLACEMENT_ONLY 1u /* allocator and batch translation only: no device memory, no
+                                        copies; shrink / expand return PLORA_ERR_INVAL.  For capacity
+                                        planning and host-side tests on a machine without a GPU. */
+
+typedef struct {
+  uint64_t page_bytes, n_pages, used_pages, free_pages;
+  uint64_t resident_adapters;
+  uint64_t resident_bytes;      /* sum of S over resident adapters */
+  uint64_t internal_frag_bytes; /* used_pages * page_bytes - resident_bytes */
+  uint64_t loads, evictions, nomem_failures;
+  uint64_t h2d_bytes;  /* bytes handed to the copy engine by plora_load_adapter */
+  uint64_t h2d_copies; /* number of copy calls (one per run of physically consecutive pages) */
+  double h2d_ms;       /* summed first-copy-start -> last-copy-end time of completed loads */
+} plora_stats;
+
+/* Pool of n_pages pages of page_bytes each (Sec. III-C "Page Structure"; the paper's default page is
+ * 2 MB).  page_bytes: power of two >= 4096.  slab_or_null: device pointer to at least
+ * n_pages * page_bytes bytes, 256-byte aligned, that stays valid until plora_pool_destroy (the
+ * caller keeps ownership), or NULL to let the pool allocate and own the slab.  The layout arrays are
+ * copied.  INVAL for bad sizes or a layout whose rows would need more page-table window than the
+ * kernels stage (16 * max(d_in) * elt / page_bytes + 2 > 1024). */
+int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* layout, void* slab_or_null,
+                      uint32_t flags, plora_pool** out);
+
+/* Frees everything the pool owns.  Synchronises the device first.  BUSY if a batch is still open. */
+int plora_pool_destroy(plora_pool* pool);
+
+/* Bytes of a rank-`rank` adapter blob for this pool's layout (0 if rank is out of range). */
+uint64_t plora_adapter_bytes(const plora_pool* pool, int32_t rank);
+
+/* Place adapter `id` and start filling its pages (Sec. III-B: load from host memory to GPU;
+ * Sec. III-C: ceil(S/P) pages).  pinned_host_ptr: host, page-locked, S bytes, must stay valid and
+ * unchanged until the adapter is ready.  The copies are issued on copy_stream, one per run of
+ * physically consecutive pages, after that stream has been made to wait for every batch that last
+ * read the pages being reused.  page_table_out / n_pages_out (either may be NULL): the adapter's
+ * page table, a host pointer into pool-owned memory that stays valid until plora_evict(id).
+ * Returns at once; the adapter becomes usable by batches immediately (they wait on its ready event).
+ * INVAL (bad id / rank / pointer not page-locked), EXISTS, NOMEM (nothing allocated). */
+int plora_load_adapter(plora_pool* pool, int32_t id, int32_t rank, float scale, const void* pinned_host_ptr,
+                       plora_stream copy_stream, const int32_t** page_table_out, uint32_t* n_pages_out);
+
+/* 1 if the adapter's copies have completed, 0 if still in flight, or a negative plora_status. */
+int plora_adapter_ready(plora_pool* pool, int32_t id);
+
+/* Makes `stream` wait (device side) until the adapter's copies have completed. */
+int plora_wait_adapter(plora_pool* pool, int32_t id, plora_stream stream);
+
+/* Return the adapter's pages to the free set (Sec. III-B "Eviction Policy": the mechanism).  The
+ * pages are allocatable at once.  NOTFOUND; BUSY if the load has not completed or an open batch
+ * names the adapter. */
+int plora_evict(plora_pool* pool, int32_t id);
+
+/* Once-per-batch translation (Sec. III-C "Page Table").  tok2adapter_host: host, n_tokens entries;
+ * -1 = token without adapter (its y row is left untouched).  Groups tokens by adapter with a stable
+ * counting sort (ascending adapter id), resolves each group's rank, scale and page table, builds the
+ * work lists of the kernels and sends all of it to the device with one copy on `stream`; `stream`
+ * is also made to wait for the adapters' copies.  The adapters named are pinned against eviction
+ * until plora_batch_end.  n_tokens may be 0.  NOTFOUND if a token names a non-resident adapter,
+ * INVAL for ids outside [-1, max_adapters). */
+int plora_batch_begin(plora_pool* pool, const int32_t* tok2adapter_host, int32_t n_tokens, plora_stream stream,
+                      plora_batch** out);
+
+/* The translation's result, for inspection: perm (token indices sorted by adapter, n_perm entries),
+ * seg_adapter (n_seg distinct ids, ascending), seg_start (n_seg + 1 offsets into perm).  Host
+ * pointers owned by the batch, valid until plora_batch_end.  Any out pointer may be NULL. */
+int plora_batch_info(const plora_batch* batch, int32_t* n_seg, int32_t* n_perm, const int32_t** perm,
+                     const int32_t** seg_adapter, const int32_t** seg_start);
+
+/* Shrink, slots slot0 .. slot0+n_slots-1, one launch sequence for all of them:
+ *   v[s][t, j] = sum_k x[s][t,k] * A_i[j,k]   (j < r_i, i = adapter of t; fp32 accumulation)
+ *   v[s][t, j] = 0                            (r_i <= j < max_rank, or t has no adapter)
+ * x: host array of n_slots device pointers, x[q] -> n_tokens x d_in[slot0+q] elements, row-major,
+ * 16-byte aligned.  v: host array of n_slots device pointers, v[q] -> n_tokens x max_rank floats,
+ * 16-byte aligned.  Runs on `stream` (normally the stream given to plora_batch_begin; another stream
+ * must be ordered after it by the caller). */
+int plora_shrink(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const void* const* x,
+                 float* const* v, plora_stream stream);
+
+/* Expand, same slot range:
+ *   y[s][t, n] = round_to_elt( y[s][t,n] + scale_i * sum_j v[s][t,j] * B_i[j,n] )   (fp32 accumulation,
+ * one rounding to nearest even).  y: host array of n_slots device pointers, y[q] -> n_tokens x
+ * d_out[slot0+q] elements, row-major, 16-byte aligned, updated in place. */
+int plora_expand(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const float* const* v,
+                 void* const* y, plora_stream stream);
+
+/* Ends the batch: records its completion on its stream, unpins its adapters and recycles the batch
+ * object.  Kernels already enqueued keep running; pages freed afterwards are not overwritten before
+ * they finish. */
+int plora_batch_end(plora_pool* pool, plora_batch* batch);
+
+/* Counters of the pool (Sec. V-A lists memory utilisation and fragmentation as metrics). */
+int plora_pool_stats(plora_pool* pool, plora_stats* out);
+
+/* Tunables.  key: "mfma_min_tokens" (adapter groups with at least this many tokens use the
+ * matrix-core path; 0 disables it), "shrink_rows_per_item", "expand_cols_per_item".  INVAL for an
+ * unknown key or a value out of range.  Takes effect for batches begun afterwards. */
+int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
+
+/* The last hipError_t seen by a call that returned PLORA_ERR_HIP (0 if none). */
+int plora_last_hip(void);
+
+/* Library version, major * 100 + minor. */
+int plora_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PLORA_H */

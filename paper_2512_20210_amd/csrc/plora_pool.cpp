@@ -1,0 +1,568 @@
+// Host side of the paged multi-LoRA library: page pool, first-fit allocator, page tables, the
+// pinned-host -> GPU copy path and the once-per-batch translation.  See include/plora.h for the
+// contract of every entry point (and the passages of the paper each one follows).
+#include "../../include/plora.h"
+#include "plora_internal.h"
+
+#include <algorithm>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace plora;
+
+static thread_local int g_last_hip = 0;
+
+#define HIP_TRY(expr)                                   \
+  do {                                                  \
+    hipError_t e_ = (expr);                             \
+    if (e_ != hipSuccess) {                             \
+      g_last_hip = (int)e_;                             \
+      (void)hipGetLastError();                          \
+      return PLORA_ERR_HIP;                             \
+    }                                                   \
+  } while (0)
+
+namespace {
+
+struct Event {  // shared completion marker of a batch
+  hipEvent_t ev = nullptr;
+  ~Event() { if (ev) (void)hipEventDestroy(ev); }
+};
+
+struct Adapter {
+  bool present = false;
+  int32_t rank = 0;
+  float scale = 0.f;
+  uint64_t bytes = 0;
+  std::vector<int32_t> pt;
+  hipEvent_t ev_start = nullptr, ev_ready = nullptr;  // created on first use, reused
+  bool copy_pending = false;                          // ready event not yet observed complete
+  int pins = 0;
+  std::shared_ptr<Event> last_use;
+};
+
+}  // namespace
+
+struct plora_batch {
+  plora_pool* pool = nullptr;
+  bool open = false;
+  hipStream_t stream = nullptr;
+  int32_t n_tokens = 0, n_seg = 0, n_perm = 0;
+  // host copies for plora_batch_info
+  std::vector<int32_t> perm, seg_adapter, seg_start;
+  // staging (pinned) and device image
+  uint8_t* h_img = nullptr;
+  uint8_t* d_img = nullptr;
+  size_t cap = 0;
+  // offsets inside the image
+  size_t off_segs = 0, off_perm = 0, off_pt = 0, off_items[4] = {0, 0, 0, 0};
+  int32_t n_items[4] = {0, 0, 0, 0};  // shrink valu, shrink mfma, expand valu, expand mfma
+  std::vector<int32_t> adapters;      // pinned adapters
+  std::shared_ptr<Event> done;        // recorded by plora_batch_end; the images are reusable once it has passed
+};
+
+struct plora_pool {
+  size_t P = 0;
+  int log2P = 0;
+  uint32_t n_pages = 0;
+  bool placement_only = false;
+  int dtype = 0, elt = 2, max_adapters = 0, max_rank = 0, n_slots = 0;
+  std::vector<SlotRec> slots;
+  int64_t C = 0;
+  int max_d_out = 0;
+  uint8_t* slab = nullptr;
+  bool own_slab = false;
+  SlotRec* d_slots = nullptr;
+  std::vector<uint64_t> free_bits;  // bit set = page free
+  uint32_t n_free = 0;
+  uint32_t hint_word = 0;  // no free bit below this word
+  std::vector<Adapter> ad;
+  std::vector<std::shared_ptr<Event>> reuse_wait;  // batches that last read pages since freed
+  std::vector<plora_batch*> batches;               // all batch objects ever made (recycled)
+  int open_batches = 0;
+  std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
+  // tunables
+  int mfma_min_tokens = 8;
+  // statistics
+  uint64_t resident_adapters = 0, resident_bytes = 0, loads = 0, evictions = 0, nomem = 0;
+  uint64_t h2d_bytes = 0, h2d_copies = 0;
+  double h2d_ms = 0.0;
+};
+
+namespace {
+
+// Harvest the copy time of a finished load.  Returns 1 ready, 0 pending, <0 error.
+int poll_ready(plora_pool* p, Adapter& a) {
+  if (!a.copy_pending) return 1;
+  hipError_t e = hipEventQuery(a.ev_ready);
+  if (e == hipErrorNotReady) { (void)hipGetLastError(); return 0; }
+  if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return PLORA_ERR_HIP; }
+  float ms = 0.f;
+  if (hipEventElapsedTime(&ms, a.ev_start, a.ev_ready) == hipSuccess) p->h2d_ms += ms;
+  else (void)hipGetLastError();
+  a.copy_pending = false;
+  return 1;
+}
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+
+int plora_version(void) { return 100; }
+int plora_last_hip(void) { return g_last_hip; }
+
+int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* lay, void* slab_or_null, uint32_t flags,
+                      plora_pool** out) {
+  if (!out || !lay || !lay->d_in || !lay->d_out) return PLORA_ERR_INVAL;
+  if (page_bytes < 4096 || page_bytes > ((size_t)1 << 30) || (page_bytes & (page_bytes - 1))) return PLORA_ERR_INVAL;
+  if (n_pages == 0 || n_pages > 0x7fffffffu) return PLORA_ERR_INVAL;
+  if (lay->n_slots < 1 || lay->dtype < 0 || lay->dtype > 2 || lay->max_adapters < 1) return PLORA_ERR_INVAL;
+  if (lay->max_rank < 1 || lay->max_rank > kMaxRank) return PLORA_ERR_INVAL;
+  if (flags & ~PLORA_POOL_PLACEMENT_ONLY) return PLORA_ERR_INVAL;
+  if (slab_or_null && ((uintptr_t)slab_or_null & 255)) return PLORA_ERR_INVAL;
+  const int elt = lay->dtype == PLORA_F32 ? 4 : 2;
+  int64_t c = 0;
+  int max_in = 0, max_out = 0;
+  std::vector<SlotRec> slots;
+  for (int s = 0; s < lay->n_slots; ++s) {
+    const int32_t di = lay->d_in[s], dn = lay->d_out[s];
+    if (di <= 0 || dn <= 0 || di % 8 || dn % 8) return PLORA_ERR_INVAL;
+    slots.push_back(SlotRec{di, dn, c});
+    c += (int64_t)di + dn;
+    max_in = std::max(max_in, di);
+    max_out = std::max(max_out, dn);
+  }
+  if ((uint64_t)kMfmaRows * (uint64_t)max_in * elt / page_bytes + 2 > (uint64_t)kPtWindow) return PLORA_ERR_INVAL;
+
+  plora_pool* p = new (std::nothrow) plora_pool;
+  if (!p) return PLORA_ERR_NOMEM;
+  p->P = page_bytes;
+  while (((size_t)1 << p->log2P) < page_bytes) p->log2P++;
+  p->n_pages = n_pages;
+  p->placement_only = (flags & PLORA_POOL_PLACEMENT_ONLY) != 0;
+  p->dtype = lay->dtype; p->elt = elt; p->max_adapters = lay->max_adapters; p->max_rank = lay->max_rank;
+  p->n_slots = lay->n_slots; p->slots = slots; p->C = c; p->max_d_out = max_out;
+  p->free_bits.assign(((size_t)n_pages + 63) / 64, ~(uint64_t)0);
+  if (n_pages & 63) p->free_bits.back() = (((uint64_t)1 << (n_pages & 63)) - 1);
+  p->n_free = n_pages;
+  p->ad.resize(lay->max_adapters);
+  p->count.assign(lay->max_adapters, 0);
+  p->cursor.assign(lay->max_adapters, 0);
+  if (!p->placement_only) {
+    hipError_t e = hipSuccess;
+    if (slab_or_null) p->slab = (uint8_t*)slab_or_null;
+    else { e = hipMalloc((void**)&p->slab, (size_t)n_pages * page_bytes); p->own_slab = (e == hipSuccess); }
+    if (e == hipSuccess) e = hipMalloc((void**)&p->d_slots, sizeof(SlotRec) * slots.size());
+    if (e == hipSuccess) e = hipMemcpy(p->d_slots, slots.data(), sizeof(SlotRec) * slots.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+      g_last_hip = (int)e; (void)hipGetLastError();
+      if (p->own_slab) (void)hipFree(p->slab);
+      if (p->d_slots) (void)hipFree(p->d_slots);
+      delete p;
+      return PLORA_ERR_HIP;
+    }
+  }
+  *out = p;
+  return PLORA_OK;
+}
+
+int plora_pool_destroy(plora_pool* p) {
+  if (!p) return PLORA_ERR_INVAL;
+  if (p->open_batches) return PLORA_ERR_BUSY;
+  if (!p->placement_only) {
+    (void)hipDeviceSynchronize();
+    for (auto& a : p->ad) {
+      if (a.ev_start) (void)hipEventDestroy(a.ev_start);
+      if (a.ev_ready) (void)hipEventDestroy(a.ev_ready);
+    }
+    if (p->own_slab) (void)hipFree(p->slab);
+    if (p->d_slots) (void)hipFree(p->d_slots);
+  }
+  for (plora_batch* b : p->batches) {
+    if (b->h_img) { if (p->placement_only) ::operator delete(b->h_img); else (void)hipHostFree(b->h_img); }
+    if (b->d_img) (void)hipFree(b->d_img);
+    delete b;
+  }
+  delete p;
+  return PLORA_OK;
+}
+
+uint64_t plora_adapter_bytes(const plora_pool* p, int32_t rank) {
+  if (!p || rank < 1 || rank > p->max_rank) return 0;
+  return (uint64_t)rank * p->elt * (uint64_t)p->C;
+}
+
+int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, const void* host, plora_stream cs,
+                       const int32_t** pt_out, uint32_t* n_out) {
+  if (!p || id < 0 || id >= p->max_adapters || rank < 1 || rank > p->max_rank) return PLORA_ERR_INVAL;
+  if (!p->placement_only && !host) return PLORA_ERR_INVAL;
+  Adapter& a = p->ad[id];
+  if (a.present) return PLORA_ERR_EXISTS;
+  const uint64_t S = (uint64_t)rank * p->elt * (uint64_t)p->C;
+  const uint64_t m = (S + p->P - 1) / p->P;
+  if (m > p->n_free) { p->nomem++; return PLORA_ERR_NOMEM; }
+  hipStream_t st = (hipStream_t)cs;
+  if (!p->placement_only) {
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, host);
+    if (e != hipSuccess || at.type != hipMemoryTypeHost) { (void)hipGetLastError(); return PLORA_ERR_INVAL; }
+    if (!a.ev_start) {
+      HIP_TRY(hipEventCreate(&a.ev_start));
+      HIP_TRY(hipEventCreate(&a.ev_ready));
+    }
+    // copies into reused pages must not overtake kernels of batches that read them
+    for (auto& w : p->reuse_wait) HIP_TRY(hipStreamWaitEvent(st, w->ev, 0));
+    p->reuse_wait.clear();
+  }
+  // first fit: the m lowest-numbered free pages, ascending
+  a.pt.clear();
+  a.pt.reserve(m);
+  uint32_t w = p->hint_word;
+  while (a.pt.size() < m) {
+    uint64_t bits = p->free_bits[w];
+    while (bits && a.pt.size() < m) {
+      const int b = __builtin_ctzll(bits);
+      bits &= bits - 1;
+      a.pt.push_back((int32_t)(w * 64 + b));
+    }
+    p->free_bits[w] = bits;  // taken bits cleared; if we stopped early, the rest stay set
+    if (a.pt.size() < m) ++w;
+  }
+  // restore bits of word w that were cleared in `bits` but not taken: none (we clear only taken ones)
+  while (p->hint_word < p->free_bits.size() && p->free_bits[p->hint_word] == 0) p->hint_word++;
+  p->n_free -= (uint32_t)m;
+
+  if (!p->placement_only) {
+    hipError_t e = hipEventRecord(a.ev_start, st);
+    uint64_t l = 0;
+    while (e == hipSuccess && l < m) {  // one copy per run of consecutive physical pages
+      uint64_t h = l + 1;
+      while (h < m && a.pt[h] == a.pt[h - 1] + 1) ++h;
+      const uint64_t lo = l * p->P, hi = std::min<uint64_t>(h * p->P, S);
+      e = hipMemcpyAsync(p->slab + (uint64_t)a.pt[l] * p->P, (const uint8_t*)host + lo, hi - lo, hipMemcpyHostToDevice, st);
+      p->h2d_copies++;
+      l = h;
+    }
+    if (e == hipSuccess) e = hipEventRecord(a.ev_ready, st);
+    if (e != hipSuccess) {  // undo the placement
+      g_last_hip = (int)e; (void)hipGetLastError();
+      for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
+      p->n_free += (uint32_t)m;
+      p->hint_word = std::min<uint32_t>(p->hint_word, a.pt.empty() ? p->hint_word : (uint32_t)a.pt[0] >> 6);
+      a.pt.clear();
+      return PLORA_ERR_HIP;
+    }
+    a.copy_pending = true;
+    p->h2d_bytes += S;
+  }
+  a.present = true; a.rank = rank; a.scale = scale; a.bytes = S; a.pins = 0; a.last_use.reset();
+  p->loads++; p->resident_adapters++; p->resident_bytes += S;
+  if (pt_out) *pt_out = a.pt.data();
+  if (n_out) *n_out = (uint32_t)m;
+  return PLORA_OK;
+}
+
+int plora_adapter_ready(plora_pool* p, int32_t id) {
+  if (!p || id < 0 || id >= p->max_adapters) return PLORA_ERR_INVAL;
+  Adapter& a = p->ad[id];
+  if (!a.present) return PLORA_ERR_NOTFOUND;
+  if (p->placement_only) return 1;
+  return poll_ready(p, a);
+}
+
+int plora_wait_adapter(plora_pool* p, int32_t id, plora_stream s) {
+  if (!p || id < 0 || id >= p->max_adapters) return PLORA_ERR_INVAL;
+  Adapter& a = p->ad[id];
+  if (!a.present) return PLORA_ERR_NOTFOUND;
+  if (p->placement_only || !a.copy_pending) return PLORA_OK;
+  HIP_TRY(hipStreamWaitEvent((hipStream_t)s, a.ev_ready, 0));
+  return PLORA_OK;
+}
+
+int plora_evict(plora_pool* p, int32_t id) {
+  if (!p || id < 0 || id >= p->max_adapters) return PLORA_ERR_INVAL;
+  Adapter& a = p->ad[id];
+  if (!a.present) return PLORA_ERR_NOTFOUND;
+  if (a.pins > 0) return PLORA_ERR_BUSY;
+  if (!p->placement_only) {
+    const int rdy = poll_ready(p, a);
+    if (rdy < 0) return rdy;
+    if (rdy == 0) return PLORA_ERR_BUSY;
+    if (a.last_use) {
+      hipError_t e = hipEventQuery(a.last_use->ev);
+      if (e == hipErrorNotReady) {
+        (void)hipGetLastError();
+        if (std::find(p->reuse_wait.begin(), p->reuse_wait.end(), a.last_use) == p->reuse_wait.end())
+          p->reuse_wait.push_back(a.last_use);
+      } else if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return PLORA_ERR_HIP; }
+    }
+  }
+  for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
+  p->n_free += (uint32_t)a.pt.size();
+  if (!a.pt.empty()) p->hint_word = std::min<uint32_t>(p->hint_word, (uint32_t)a.pt[0] >> 6);
+  p->resident_adapters--; p->resident_bytes -= a.bytes; p->evictions++;
+  a.pt.clear(); a.pt.shrink_to_fit();
+  a.present = false; a.rank = 0; a.scale = 0.f; a.bytes = 0; a.last_use.reset();
+  return PLORA_OK;
+}
+
+int plora_pool_stats(plora_pool* p, plora_stats* o) {
+  if (!p || !o) return PLORA_ERR_INVAL;
+  if (!p->placement_only)
+    for (auto& a : p->ad)
+      if (a.present && a.copy_pending) (void)poll_ready(p, a);
+  o->page_bytes = p->P; o->n_pages = p->n_pages; o->free_pages = p->n_free; o->used_pages = p->n_pages - p->n_free;
+  o->resident_adapters = p->resident_adapters; o->resident_bytes = p->resident_bytes;
+  o->internal_frag_bytes = o->used_pages * p->P - p->resident_bytes;
+  o->loads = p->loads; o->evictions = p->evictions; o->nomem_failures = p->nomem;
+  o->h2d_bytes = p->h2d_bytes; o->h2d_copies = p->h2d_copies; o->h2d_ms = p->h2d_ms;
+  return PLORA_OK;
+}
+
+int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
+  if (!p || !key) return PLORA_ERR_INVAL;
+  const std::string k(key);
+  if (k == "mfma_min_tokens") {
+    if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    p->mfma_min_tokens = (int)value;
+    return PLORA_OK;
+  }
+  return PLORA_ERR_INVAL;
+}
+
+// ---------------------------------------------------------------------------------------------
+// batch translation
+// ---------------------------------------------------------------------------------------------
+int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream s, plora_batch** out) {
+  if (!p || !out || T < 0 || (T > 0 && !t2a)) return PLORA_ERR_INVAL;
+  // pass 1: validate and count (nothing is modified on failure except the scratch counters)
+  int rc = PLORA_OK;
+  int32_t n_none = 0;
+  std::vector<int32_t> touched;
+  for (int32_t t = 0; t < T; ++t) {
+    const int32_t i = t2a[t];
+    if (i == -1) { n_none++; continue; }
+    if (i < 0 || i >= p->max_adapters) { rc = PLORA_ERR_INVAL; break; }
+    if (!p->ad[i].present) { rc = PLORA_ERR_NOTFOUND; break; }
+    if (p->count[i]++ == 0) touched.push_back(i);
+  }
+  if (rc != PLORA_OK) {
+    for (int32_t i : touched) p->count[i] = 0;
+    return rc;
+  }
+  std::sort(touched.begin(), touched.end());
+  const int32_t n_seg = (int32_t)touched.size();
+  const int32_t n_perm = T - n_none;
+
+  plora_batch* b = nullptr;
+  for (plora_batch* c : p->batches) {
+    if (c->open) continue;
+    if (c->done) {  // its last copy and kernels may still be in flight
+      const hipError_t e = hipEventQuery(c->done->ev);
+      if (e != hipSuccess) { (void)hipGetLastError(); continue; }
+      c->done.reset();
+    }
+    b = c;
+    break;
+  }
+  if (!b) {
+    b = new (std::nothrow) plora_batch;
+    if (!b) { for (int32_t i : touched) p->count[i] = 0; return PLORA_ERR_NOMEM; }
+    b->pool = p;
+    p->batches.push_back(b);
+  }
+  b->stream = (hipStream_t)s;
+  b->n_tokens = T; b->n_seg = n_seg; b->n_perm = n_perm;
+  b->perm.assign(T, 0);
+  b->seg_adapter.assign(touched.begin(), touched.end());
+  b->seg_start.assign(n_seg + 1, 0);
+  int32_t run = 0;
+  for (int32_t u = 0; u < n_seg; ++u) {
+    const int32_t i = touched[u];
+    b->seg_start[u] = run; p->cursor[i] = run; run += p->count[i];
+  }
+  b->seg_start[n_seg] = run;
+  int32_t none_cur = n_perm;  // tokens without adapter go behind the sorted ones (device side only)
+  for (int32_t t = 0; t < T; ++t) {
+    const int32_t i = t2a[t];
+    if (i == -1) b->perm[none_cur++] = t; else b->perm[p->cursor[i]++] = t;
+  }
+
+  // segments (+ one rank-0 pseudo segment for tokens without adapter) and work items
+  const bool mfma_ok = p->dtype != PLORA_F32 && p->mfma_min_tokens > 0;
+  std::vector<SegRec> segs;
+  std::vector<ItemRec> items[4];
+  size_t n_pt_total = 0;
+  for (int32_t u = 0; u < n_seg; ++u) {
+    const Adapter& a = p->ad[touched[u]];
+    const int32_t n = p->count[touched[u]];
+    SegRec sg{b->seg_start[u], n, a.rank, (int32_t)n_pt_total, a.scale, touched[u], (int32_t)a.pt.size(), 0};
+    segs.push_back(sg);
+    n_pt_total += a.pt.size();
+    if (mfma_ok && n >= p->mfma_min_tokens) {
+      for (int32_t t0 = 0; t0 < n; t0 += kMfmaTok) {
+        const int32_t nt = std::min(kMfmaTok, n - t0);
+        for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows) items[1].push_back(ItemRec{u, t0, nt, j0});
+        items[3].push_back(ItemRec{u, t0, nt, 0});
+      }
+    } else {
+      for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
+        const int32_t nt = std::min(kValuTok, n - t0);
+        for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows) items[0].push_back(ItemRec{u, t0, nt, j0});
+        items[2].push_back(ItemRec{u, t0, nt, 0});
+      }
+    }
+  }
+  if (n_none > 0) {
+    segs.push_back(SegRec{n_perm, n_none, 0, 0, 0.f, -1, 0, 0});
+    for (int32_t t0 = 0; t0 < n_none; t0 += kValuTok)
+      items[0].push_back(ItemRec{n_seg, t0, std::min(kValuTok, n_none - t0), 0});
+  }
+  for (int32_t i : touched) p->count[i] = 0;
+
+  // image layout
+  size_t off = 0;
+  b->off_segs = off; off = align_up(off + segs.size() * sizeof(SegRec), 256);
+  b->off_perm = off; off = align_up(off + (size_t)T * 4, 256);
+  b->off_pt = off; off = align_up(off + (n_pt_total + 1) * 4, 256);
+  for (int k = 0; k < 4; ++k) {
+    b->off_items[k] = off; b->n_items[k] = (int32_t)items[k].size();
+    off = align_up(off + items[k].size() * sizeof(ItemRec), 256);
+  }
+  const size_t need = std::max<size_t>(off, 256);
+  if (need > b->cap) {
+    const size_t cap = align_up(need + need / 2, 4096);
+    if (p->placement_only) {
+      if (b->h_img) ::operator delete(b->h_img);
+      b->h_img = (uint8_t*)::operator new(cap, std::nothrow);
+      if (!b->h_img) { b->cap = 0; return PLORA_ERR_NOMEM; }
+    } else {
+      if (b->h_img) { (void)hipHostFree(b->h_img); b->h_img = nullptr; }
+      if (b->d_img) { (void)hipFree(b->d_img); b->d_img = nullptr; }
+      b->cap = 0;
+      HIP_TRY(hipHostMalloc((void**)&b->h_img, cap, hipHostMallocDefault));
+      HIP_TRY(hipMalloc((void**)&b->d_img, cap));
+    }
+    b->cap = cap;
+  }
+  if (!segs.empty()) std::memcpy(b->h_img + b->off_segs, segs.data(), segs.size() * sizeof(SegRec));
+  if (T) std::memcpy(b->h_img + b->off_perm, b->perm.data(), (size_t)T * 4);
+  {
+    int32_t* dst = (int32_t*)(b->h_img + b->off_pt);
+    for (int32_t u = 0; u < n_seg; ++u) {
+      const Adapter& a = p->ad[touched[u]];
+      std::memcpy(dst, a.pt.data(), a.pt.size() * 4);
+      dst += a.pt.size();
+    }
+    *dst = 0;
+  }
+  for (int k = 0; k < 4; ++k)
+    if (!items[k].empty()) std::memcpy(b->h_img + b->off_items[k], items[k].data(), items[k].size() * sizeof(ItemRec));
+  b->perm.resize(n_perm);
+
+  if (!p->placement_only) {
+    HIP_TRY(hipMemcpyAsync(b->d_img, b->h_img, need, hipMemcpyHostToDevice, b->stream));
+    for (int32_t i : touched) {
+      Adapter& a = p->ad[i];
+      if (a.copy_pending && poll_ready(p, a) == 0) HIP_TRY(hipStreamWaitEvent(b->stream, a.ev_ready, 0));
+    }
+  }
+  b->adapters.assign(touched.begin(), touched.end());
+  for (int32_t i : touched) p->ad[i].pins++;
+  b->open = true;
+  p->open_batches++;
+  *out = b;
+  return PLORA_OK;
+}
+
+int plora_batch_info(const plora_batch* b, int32_t* n_seg, int32_t* n_perm, const int32_t** perm,
+                     const int32_t** seg_adapter, const int32_t** seg_start) {
+  if (!b || !b->open) return PLORA_ERR_INVAL;
+  if (n_seg) *n_seg = b->n_seg;
+  if (n_perm) *n_perm = b->n_perm;
+  if (perm) *perm = b->perm.data();
+  if (seg_adapter) *seg_adapter = b->seg_adapter.data();
+  if (seg_start) *seg_start = b->seg_start.data();
+  return PLORA_OK;
+}
+
+static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* in,
+                     void* const* outp, plora_stream s, bool is_shrink) {
+  if (!p || !b || !b->open || b->pool != p || p->placement_only) return PLORA_ERR_INVAL;
+  if (slot0 < 0 || n_slots < 0 || slot0 + n_slots > p->n_slots) return PLORA_ERR_INVAL;
+  if (n_slots == 0 || b->n_tokens == 0) return PLORA_OK;
+  if (!in || !outp) return PLORA_ERR_INVAL;
+  for (int q = 0; q < n_slots; ++q)
+    if (!in[q] || !outp[q] || ((uintptr_t)in[q] & 15) || ((uintptr_t)outp[q] & 15)) return PLORA_ERR_INVAL;
+  LaunchArgs a;
+  a.slab = p->slab;
+  a.segs = (const SegRec*)(b->d_img + b->off_segs);
+  a.perm = (const int32_t*)(b->d_img + b->off_perm);
+  a.pt = (const int32_t*)(b->d_img + b->off_pt);
+  a.slots = p->d_slots;
+  a.log2_page = p->log2P;
+  a.v_stride = p->max_rank;
+  a.pad = 0;
+  const int vec = 16 / p->elt;
+  for (int q0 = 0; q0 < n_slots; q0 += kMaxSlotsPerLaunch) {
+    const int nq = std::min(kMaxSlotsPerLaunch, n_slots - q0);
+    SlotPtrs ptrs;
+    int max_out = 0;
+    for (int q = 0; q < nq; ++q) {
+      ptrs.a[q] = in[q0 + q];
+      ptrs.b[q] = outp[q0 + q];
+      max_out = std::max(max_out, (int)p->slots[slot0 + q0 + q].d_out);
+    }
+    a.slot0 = slot0 + q0;
+    for (int kind = 1; kind >= 0; --kind) {  // matrix-core items (the long ones) first
+      const int li = (is_shrink ? 0 : 2) + kind;
+      a.items = (const ItemRec*)(b->d_img + b->off_items[li]);
+      a.n_items = b->n_items[li];
+      hipError_t e;
+      if (is_shrink) e = launch_shrink(p->dtype, kind, a, ptrs, nq, (hipStream_t)s);
+      else {
+        const int cols = kind ? kMfmaCols : kWave * vec;
+        e = launch_expand(p->dtype, kind, a, ptrs, nq, (max_out + cols - 1) / cols, (hipStream_t)s);
+      }
+      HIP_TRY(e);
+    }
+  }
+  return PLORA_OK;
+}
+
+int plora_shrink(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* x, float* const* v,
+                 plora_stream s) {
+  return run_slots(p, b, slot0, n_slots, x, (void* const*)v, s, true);
+}
+
+int plora_expand(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const float* const* v, void* const* y,
+                 plora_stream s) {
+  return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);
+}
+
+int plora_batch_end(plora_pool* p, plora_batch* b) {
+  if (!p || !b || !b->open || b->pool != p) return PLORA_ERR_INVAL;
+  std::shared_ptr<Event> done;
+  if (!p->placement_only) {
+    done = std::make_shared<Event>();
+    HIP_TRY(hipEventCreateWithFlags(&done->ev, hipEventDisableTiming));
+    HIP_TRY(hipEventRecord(done->ev, b->stream));
+  }
+  for (int32_t i : b->adapters) {
+    Adapter& a = p->ad[i];
+    a.pins--;
+    if (done) a.last_use = done;
+  }
+  b->adapters.clear();
+  b->done = done;
+  b->open = false;
+  p->open_batches--;
+  return PLORA_OK;
+}
+
+}  // extern "C"

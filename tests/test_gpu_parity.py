@@ -1,0 +1,115 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element."""
+import numpy as np
+import pytest
+
+from workload import (CONFIGS, DT_BF16, DT_F16, DT_F32, Layout, config_layout, draw_tok2adapter)
+from helpers import Case
+
+pytestmark = pytest.mark.gpu
+
+
+def test_cfg0_small_workload(oracle_mod):
+    """1024->1024 fp16, 16 tokens, ranks (8,16,8,16), scale 2, 16 KiB pages, 64 pages."""
+    cfg = CONFIGS["cfg0"]
+    lay = config_layout(cfg)
+    case = Case(oracle_mod, lay, cfg["ranks"], [cfg["scale"]] * 4, cfg["page_bytes"], cfg["n_pages"], cfg["seed"])
+    rng = np.random.default_rng(cfg["seed"])
+    t2a = draw_tok2adapter(rng, cfg["tokens"], np.arange(4), s=None)
+    print("cfg0 t2a", t2a.tolist(), flush=True)
+    for mfma in (0, 1, 4):
+        case.gpool.set_option("mfma_min_tokens", mfma)
+        out = case.run(t2a, seed=1)
+        print("mfma_min", mfma, "err_v %.3g err_y %.3g" % (out[0]["err_v"], out[0]["err_y"]), flush=True)
+        out = case.run(t2a, seed=2, y0_zero=True)
+    st = case.gpool.stats()
+    assert st["used_pages"] == 12
+    case.close()
+
+
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F16, DT_F32])
+@pytest.mark.parametrize("mfma", [0, 1, 3])
+def test_ragged_multi_slot(oracle_mod, dtype, mfma):
+    """Several tiles and ragged tails everywhere: d not a multiple of the wave width, ranks 1..40
+    (not multiples of 8), rows straddling 4 KiB pages, tokens without adapter, scattered pages."""
+    lay = Layout((1000, 520, 72), (264, 1304, 8), dtype)
+    ranks = [1, 3, 8, 17, 40, 5, 33, 16]
+    scales = [16.0 / r for r in ranks]
+    case = Case(oracle_mod, lay, ranks, scales, 4096, 1024, seed=77, load_order=[4, 0, 6, 2, 1, 7, 3, 5],
+                mfma_min_tokens=mfma)
+    # scatter: evict two adapters and reload them so that their pages interleave
+    case.evict(0)
+    case.evict(6)
+    case.load(6)
+    case.load(0)
+    rng = np.random.default_rng(5)
+    for T in (1, 7, 90, 300):
+        t2a = draw_tok2adapter(rng, T, np.arange(len(ranks)), s=1.0, none_frac=0.15)
+        print("ragged dtype", dtype, "mfma", mfma, "T", T, flush=True)
+        out = case.run(t2a, seed=T)
+        print("   err_v", ["%.2g" % o["err_v"] for o in out], "err_y", ["%.2g" % o["err_y"] for o in out], flush=True)
+    case.close()
+
+
+def test_empty_and_no_adapter_batches(oracle_mod):
+    lay = Layout((64,), (64,), DT_BF16)
+    case = Case(oracle_mod, lay, [4], [1.0], 4096, 4, seed=1)
+    case.run(np.zeros(0, np.int32))
+    case.run(np.full(9, -1, np.int32))
+    case.close()
+
+
+def test_evict_reload_bit_identical_on_gpu(oracle_mod):
+    lay = Layout((512, 256), (256, 768), DT_BF16)
+    ranks = [8, 16, 24, 64]
+    case = Case(oracle_mod, lay, ranks, [2.0, 1.0, 0.5, 0.25], 4096, 256, seed=9, mfma_min_tokens=6)
+    rng = np.random.default_rng(3)
+    t2a = draw_tok2adapter(rng, 64, np.arange(4), s=1.0)
+    a = case.run(t2a, seed=4)
+    case.evict(0)
+    case.evict(2)
+    case.load(2)
+    case.load(0)
+    b = case.run(t2a, seed=4)
+    for ra, rb in zip(a, b):
+        assert (ra["v_got"].view(np.uint32) == rb["v_got"].view(np.uint32)).all()
+        assert (ra["y_got"] == rb["y_got"]).all()
+    case.close()
+
+
+def test_error_paths_on_gpu(oracle_mod):
+    import torch
+    import paper_2512_20210_amd as P
+    lay = Layout((64,), (64,), DT_BF16)
+    case = Case(oracle_mod, lay, [4, 8], [1.0, 1.0], 4096, 2, seed=1, max_adapters=4, load_order=[0])
+    g = case.gpool
+    # not enough pages: nothing allocated
+    rc, _ = P.plora_load_adapter(g.h, 1, 8, 1.0, case.pinned[1].data_ptr(), None)
+    assert rc == P.PLORA_OK  # 8*128*2 = 2 KiB -> 1 page
+    rc, _ = P.plora_load_adapter(g.h, 2, 8, 1.0, case.pinned[1].data_ptr(), None)
+    assert rc == P.PLORA_ERR_NOMEM and g.stats()["free_pages"] == 0
+    rc, _ = P.plora_load_adapter(g.h, 1, 8, 1.0, case.pinned[1].data_ptr(), None)
+    assert rc == P.PLORA_ERR_EXISTS
+    unpinned = torch.zeros(4096, dtype=torch.int16)
+    assert P.plora_evict(g.h, 1) == P.PLORA_OK or P.plora_evict(g.h, 1) == P.PLORA_ERR_BUSY
+    torch.cuda.synchronize()
+    if P.plora_adapter_ready(g.h, 1) != P.PLORA_ERR_NOTFOUND:
+        assert P.plora_evict(g.h, 1) == P.PLORA_OK
+    rc, _ = P.plora_load_adapter(g.h, 1, 8, 1.0, unpinned.data_ptr(), None)
+    assert rc == P.PLORA_ERR_INVAL and g.stats()["free_pages"] == 1
+    rc, b = P.plora_batch_begin(g.h, np.array([0, 3], np.int32), None)
+    assert rc == P.PLORA_ERR_NOTFOUND
+    rc, b = P.plora_batch_begin(g.h, np.array([0, 7], np.int32), None)
+    assert rc == P.PLORA_ERR_INVAL
+    rc, b = P.plora_batch_begin(g.h, np.array([0, 0], np.int32), None)
+    assert rc == P.PLORA_OK
+    assert P.plora_evict(g.h, 0) == P.PLORA_ERR_BUSY       # pinned by the open batch
+    assert P.plora_pool_destroy(g.h) == P.PLORA_ERR_BUSY
+    x = torch.zeros(2, 64, dtype=torch.int16, device="cuda")
+    v = torch.zeros(2, 8, dtype=torch.float32, device="cuda")
+    assert P.plora_shrink(g.h, b, 0, 2, [x.data_ptr()] * 2, [v.data_ptr()] * 2, None) == P.PLORA_ERR_INVAL  # slot range
+    assert P.plora_shrink(g.h, b, 0, 1, [x.data_ptr() + 2], [v.data_ptr()], None) == P.PLORA_ERR_INVAL      # alignment
+    assert P.plora_batch_end(g.h, b) == P.PLORA_OK
+    torch.cuda.synchronize()
+    assert P.plora_evict(g.h, 0) == P.PLORA_OK
+    assert P.plora_evict(g.h, 0) == P.PLORA_ERR_NOTFOUND
+    case.close()
