@@ -1,0 +1,302 @@
+#!/usr/bin/env python3
+"""Benchmark of the paged multi-LoRA hot path on one MI355X.
+
+One *step* = one decode batch through the whole path: batch translation (token -> adapter groups,
+page tables to the device), shrink over all slots, expand over all slots, batch end.  Inputs
+(adapter pool, activations) are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Default workload: cfg1 = Llama-7B-shaped q,k,v,o projections (4096->4096) x 32 layers = 128 slots,
+bf16, 256 decode tokens, 64 resident adapters with ranks uniform in {8,16,32,64}, Zipf(1.0)
+token->adapter, 64 KiB pages.  All inputs are seeded and synthetic.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+from workload import (CONFIGS, RAW_DTYPE, config_layout, draw_ranks, draw_tok2adapter, make_adapters,  # noqa: E402
+                      prefill_requests, to_elt)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
+KCLASS = ["shrink_valu", "shrink_mfma", "expand_valu", "expand_mfma", "shrink_fused", "expand_fused"]
+
+
+def workload_params(name):
+    """Ranks, scales and pool size of a named workload (all drawn from its seed)."""
+    cfg = CONFIGS[name]
+    lay = config_layout(cfg)
+    rng = np.random.default_rng(cfg["seed"])
+    n_ad = cfg.get("n_adapters") or cfg["population"]
+    ranks = np.asarray(cfg["ranks"], np.int32) if cfg["ranks"] else draw_ranks(rng, n_ad, cfg["rank_choices"])
+    scales = [float(cfg["scale"])] * n_ad if cfg["scale"] else [16.0 / int(r) for r in ranks]
+    P = cfg["page_bytes"]
+    n_pages = cfg["n_pages"] or int(sum(-(-lay.adapter_bytes(int(r)) // P) for r in ranks))
+    return cfg, lay, ranks, scales, P, n_pages
+
+
+def draw_batch(cfg, rng, n_adapters):
+    if "requests" in cfg:
+        return prefill_requests(rng, cfg["requests"], cfg["len_lo"], cfg["len_hi"], np.arange(n_adapters), cfg["zipf"])[0]
+    return draw_tok2adapter(rng, cfg["tokens"], np.arange(n_adapters), cfg["zipf"])
+
+
+def algorithmic_bytes(lay, ranks, t2a, slots):
+    """Bytes the method itself must move for one batch over `slots` (each needed weight byte once per
+    batch, x read once, y read + written once, v written + read once, page-table entries and the
+    token permutation once per slot).  Returns per-slot-summed dicts for shrink and expand."""
+    elt = lay.elt
+    has = t2a >= 0
+    Tn = int(has.sum())
+    uniq = np.unique(t2a[has])
+    sum_r_u = int(sum(int(ranks[u]) for u in uniq))
+    sum_r_t = int(sum(int(ranks[i]) for i in t2a[has]))
+    shrink = expand = 0
+    flops = 0
+    for s in slots:
+        di, do = lay.d_in[s], lay.d_out[s]
+        meta = 4 * Tn
+        shrink += sum_r_u * di * elt + Tn * di * elt + sum_r_t * 4 + meta
+        expand += sum_r_u * do * elt + 2 * Tn * do * elt + sum_r_t * 4 + meta
+        flops += 2 * sum_r_t * (di + do)
+    return dict(shrink=shrink, expand=expand, total=shrink + expand, flops=flops, n_unique=len(uniq), tokens=Tn)
+
+
+class GpuWorkload:
+    """Pool with all adapters resident + per-slot activation buffers on the device."""
+
+    def __init__(self, name, workers=16, verbose=False):
+        import torch
+        import paper_2512_20210_amd as P
+        self.torch, self.P, self.name = torch, P, name
+        self.cfg, self.lay, self.ranks, self.scales, self.page_bytes, self.n_pages = workload_params(name)
+        lay, cfg = self.lay, self.cfg
+        self.n_ad = len(self.ranks)
+        self.max_rank = cfg["max_rank"]
+        self.mfma_min = 8  # the library's default for "mfma_min_tokens"
+        t0 = time.perf_counter()
+        self.pinned = [torch.empty(lay.adapter_elems(int(r)), dtype=torch.int16 if lay.elt == 2 else torch.float32,
+                                   pin_memory=True) for r in self.ranks]
+        views = [t.numpy().view(RAW_DTYPE[lay.dtype]) for t in self.pinned]
+        self.blobs = make_adapters(cfg["seed"] + 1000, lay, self.ranks, outs=views, workers=workers)
+        self.t_gen = time.perf_counter() - t0
+        self.pool = P.PagedLoraPool(self.page_bytes, self.n_pages, lay.d_in, lay.d_out, lay.dtype, self.n_ad, self.max_rank)
+        self.copy_stream = torch.cuda.Stream()
+        self.stream = torch.cuda.current_stream().cuda_stream
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.tables = [self.pool.load(i, int(self.ranks[i]), self.scales[i], self.pinned[i], self.copy_stream.cuda_stream)
+                       for i in range(self.n_ad)]
+        self.copy_stream.synchronize()
+        self.t_load = time.perf_counter() - t0
+        self.stats_after_load = self.pool.stats()
+        if verbose:
+            st = self.stats_after_load
+            print("[bench] %s: %d adapters, %.2f GB in %d pages of %d KiB; generated in %.1fs; H2D %.2f GB/s wall "
+                  "(%d copies, %.1f GB/s by events)" % (
+                      name, self.n_ad, st["resident_bytes"] / 1e9, st["used_pages"], self.page_bytes // 1024, self.t_gen,
+                      st["h2d_bytes"] / 1e9 / self.t_load, st["h2d_copies"],
+                      st["h2d_bytes"] / 1e6 / max(st["h2d_ms"], 1e-9)), file=sys.stderr, flush=True)
+
+    def alloc_activations(self, T, seed, zero_y=False):
+        """x ~ N(0,1), y0 ~ N(0,1) per slot on the device (raw element tensors), v buffers."""
+        torch, lay = self.torch, self.lay
+        rng = np.random.default_rng(seed)
+        dt = torch.int16 if lay.elt == 2 else torch.float32
+        self.T = T
+        self.x, self.y, self.v = [], [], []
+        # one draw per distinct width, re-used with a per-slot roll so that slots differ
+        base = {}
+        for s in range(lay.n_slots):
+            for d in (lay.d_in[s], lay.d_out[s]):
+                if d not in base:
+                    base[d] = to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype)
+        self.x_host_base, self.y_host_base = base, base
+        for s in range(lay.n_slots):
+            xs = np.roll(base[lay.d_in[s]], s, axis=0)
+            ys = np.roll(base[lay.d_out[s]], -s - 1, axis=0)
+            self.x.append(torch.from_numpy(np.ascontiguousarray(xs).view(np.int16) if lay.elt == 2 else xs).to("cuda"))
+            y = torch.from_numpy(np.ascontiguousarray(ys).view(np.int16) if lay.elt == 2 else ys).to("cuda")
+            if zero_y:
+                y.zero_()
+            self.y.append(y)
+            self.v.append(torch.empty((T, self.max_rank), dtype=torch.float32, device="cuda"))
+        torch.cuda.synchronize()
+
+    def set_mfma_min(self, n):
+        self.pool.set_option("mfma_min_tokens", n)
+        self.mfma_min = n
+
+    def host_x(self, s):
+        return np.roll(self.x_host_base[self.lay.d_in[s]], s, axis=0)
+
+    def host_y0(self, s):
+        return np.roll(self.y_host_base[self.lay.d_out[s]], -s - 1, axis=0)
+
+    def step(self, t2a, slots_per_call):
+        pool, n = self.pool, self.lay.n_slots
+        if len(t2a) > self.T:  # the library cannot see buffer sizes: never launch past the activations
+            raise ValueError("batch of %d tokens but activation buffers hold %d" % (len(t2a), self.T))
+        b = pool.batch_begin(t2a, self.stream)
+        for s0 in range(0, n, slots_per_call):
+            s1 = min(n, s0 + slots_per_call)
+            pool.shrink(b, s0, self.x[s0:s1], self.v[s0:s1], self.stream)
+            pool.expand(b, s0, self.v[s0:s1], self.y[s0:s1], self.stream)
+        pool.batch_end(b)
+
+    def close(self):
+        self.torch.cuda.synchronize()
+        self.pool.close()
+
+
+def cpu_baseline(w, t2a, budget_s=15.0):
+    """The oracle as it stands (fp32 accumulators, OpenMP over tokens on all host threads), timed on a
+    bounded sample: whole slots of the same batch, as many as fit the time budget."""
+    import oracle
+    oracle.build(force=False)
+    from oracle.pool import max_threads
+    lay = w.lay
+    threads = max_threads()
+    op = oracle.OraclePool(w.page_bytes, w.n_pages, lay.d_in, lay.d_out, lay.dtype, w.n_ad, w.max_rank)
+    for i in range(w.n_ad):
+        op.load(i, int(w.ranks[i]), w.scales[i], w.blobs[i])
+    done, t_total, bytes_total = 0, 0.0, 0
+    for s in range(lay.n_slots):
+        x, y = w.host_x(s), w.host_y0(s).copy()
+        t0 = time.perf_counter()
+        v = op.shrink(s, x, t2a, threads=threads)
+        op.expand(s, v, t2a, y, threads=threads)
+        t_total += time.perf_counter() - t0
+        bytes_total += algorithmic_bytes(lay, w.ranks, t2a, [s])["total"]
+        done += 1
+        if t_total > budget_s or (done >= 2 and t_total / done * (done + 1) > budget_s * 1.5):
+            break
+    op.close()
+    per_slot = t_total / done
+    return dict(value=bytes_total / t_total / 1e9, unit="GB/s", cores=threads, kind="oracle",
+                sample="%d of %d slots of one %d-token batch, shrink+expand, fp32 accumulators, OpenMP over tokens; "
+                       "%.2f s per slot => %.1f tokens/s for the whole step" % (
+                           done, lay.n_slots, len(t2a), per_slot, len(t2a) / (per_slot * lay.n_slots)),
+                tokens_per_s=len(t2a) / (per_slot * lay.n_slots), seconds=t_total)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
+    ap.add_argument("--mfma-min-tokens", type=int, default=-1)
+    ap.add_argument("--fused", type=int, default=-1, help="1 = one launch per call over the mixed item list")
+    ap.add_argument("--xcd-remap", type=int, default=-1)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--same-batch", action="store_true", help="reuse one token->adapter draw for every step")
+    ap.add_argument("--verbose", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); the path has no multi-GPU part", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    w = GpuWorkload(args.workload, verbose=args.verbose)
+    cfg, lay = w.cfg, w.lay
+    if args.mfma_min_tokens >= 0:
+        w.set_mfma_min(args.mfma_min_tokens)
+    if args.fused >= 0:
+        w.pool.set_option("fused", args.fused)
+    if args.xcd_remap >= 0:
+        w.pool.set_option("xcd_remap", args.xcd_remap)
+    rng = np.random.default_rng(cfg["seed"] + 7)
+    n_draws = 1 if args.same_batch else args.steps + args.warmup
+    batches = [draw_batch(cfg, rng, w.n_ad) for _ in range(n_draws)]
+    T = max(len(b) for b in batches)
+    w.alloc_activations(T, cfg["seed"] + 9)
+    spc = args.slots_per_call or lay.n_slots
+    all_slots = list(range(lay.n_slots))
+
+    for i in range(args.warmup):
+        w.step(batches[i % n_draws], spc)
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        w.pool.profile(True)
+    timed = [batches[(args.warmup + i) % n_draws] for i in range(args.steps)]
+    t0 = time.perf_counter()
+    for t2a in timed:
+        w.step(t2a, spc)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    elapsed = t1 - t0
+    kms, kn = ([0.0] * 6, [0] * 6)
+    if not args.no_kernel_events:
+        w.pool.profile(False)
+        kms, kn = w.pool.profile_read()
+
+    ab = [algorithmic_bytes(lay, w.ranks, t2a, all_slots) for t2a in timed]
+    bytes_total = sum(a["total"] for a in ab)
+    tokens_total = sum(len(t2a) for t2a in timed)
+    gbs = bytes_total / elapsed / 1e9
+
+    # dominant kernel: the class with the largest summed duration; its algorithmic bytes per launch
+    # are the weights of its adapter groups plus the activations of their tokens (split by path)
+    roof = None
+    if not args.no_kernel_events and sum(kn):
+        dom = int(np.argmax(kms))
+        is_shrink = dom in (0, 1, 4)
+        mfma_min = w.mfma_min
+        kb = 0
+        for t2a in timed:
+            has = t2a >= 0
+            ids, counts = np.unique(t2a[has], return_counts=True)
+            on_mfma = (counts >= mfma_min) if (mfma_min > 0 and lay.dtype != 2) else np.zeros(len(ids), bool)
+            sel = np.ones(len(ids), bool) if dom >= 4 else (on_mfma if dom % 2 == 1 else ~on_mfma)
+            sum_r_u = int(sum(int(w.ranks[u]) for u in ids[sel]))
+            ntok = int(counts[sel].sum())
+            sum_r_t = int(sum(int(w.ranks[u]) * int(c) for u, c in zip(ids[sel], counts[sel])))
+            for s in all_slots:
+                d = lay.d_in[s] if is_shrink else lay.d_out[s]
+                kb += sum_r_u * d * lay.elt + (1 if is_shrink else 2) * ntok * d * lay.elt + sum_r_t * 4 + 4 * ntok
+        avg_ms = kms[dom] / kn[dom]
+        per_launch = kb / kn[dom]
+        ach = per_launch / (avg_ms * 1e-3) / 1e9
+        roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=None, avg_launch_ms=round(avg_ms, 5),
+                    launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
+                    all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(6) if kn[k]})
+
+    out = {
+        "metric": METRIC, "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(elapsed / args.steps * 1e3, 4), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": {0: "f16", 1: "bf16", 2: "f32"}[lay.dtype],
+        "data": "synthetic",
+        "config": {"workload": args.workload, "slots": lay.n_slots, "tokens": int(T), "adapters": int(w.n_ad),
+                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc),
+                   "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1)},
+        "tokens_per_s": round(tokens_total / elapsed, 1),
+        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
+        "algorithmic_bytes_per_step": int(bytes_total / args.steps),
+        "gflop_per_step": round(sum(a["flops"] for a in ab) / args.steps / 1e9, 2),
+        "h2d_prefetch_gbs": round(w.stats_after_load["h2d_bytes"] / 1e9 / w.t_load, 2),
+        "pool_page_util": round(w.stats_after_load["used_pages"] / w.stats_after_load["n_pages"], 4),
+        "roofline": roof,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, timed[0])
+    w.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -15,7 +15,7 @@ __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS",
            "plora_pool_create", "plora_pool_destroy", "plora_adapter_bytes", "plora_load_adapter",
            "plora_adapter_ready", "plora_wait_adapter", "plora_evict", "plora_batch_begin", "plora_batch_info",
            "plora_shrink", "plora_expand", "plora_batch_end", "plora_pool_stats", "plora_pool_set_option",
-           "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH"]
+           "plora_profile", "plora_profile_read", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH"]
 
 PLORA_OK, PLORA_ERR_INVAL, PLORA_ERR_NOMEM, PLORA_ERR_EXISTS = 0, -1, -2, -3
 PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP = -4, -5, -6
@@ -23,7 +23,7 @@ PLORA_F16, PLORA_BF16, PLORA_F32 = 0, 1, 2
 PLORA_POOL_PLACEMENT_ONLY = 1
 _STATUS = {0: "OK", -1: "INVAL", -2: "NOMEM", -3: "EXISTS", -4: "NOTFOUND", -5: "BUSY", -6: "HIP"}
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libplora.so")
+LIB_PATH = os.environ.get("PLORA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libplora.so")
 if not os.path.exists(LIB_PATH):
     raise ImportError("libplora.so is not built: run `python -m paper_2512_20210_amd.build` "
                       "(or __graft_entry__.build()); there is no fallback implementation")
@@ -58,6 +58,8 @@ lib.plora_expand.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp]
 lib.plora_batch_end.argtypes = [_vp, _vp]
 lib.plora_pool_stats.argtypes = [_vp, C.POINTER(_Stats)]
 lib.plora_pool_set_option.argtypes = [_vp, C.c_char_p, C.c_int64]
+lib.plora_profile.argtypes = [_vp, C.c_int]
+lib.plora_profile_read.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
 lib.plora_last_hip.argtypes = []
 lib.plora_version.argtypes = []
 
@@ -151,6 +153,19 @@ def plora_pool_set_option(pool, key, value):
     return lib.plora_pool_set_option(pool, key.encode(), int(value))
 
 
+def plora_profile(pool, enable):
+    return lib.plora_profile(pool, int(enable))
+
+
+def plora_profile_read(pool):
+    """-> (status, ms[6], launches[6]) for shrink-valu, shrink-mfma, expand-valu, expand-mfma,
+    shrink-fused, expand-fused."""
+    ms = (C.c_double * 6)()
+    n = (C.c_uint64 * 6)()
+    rc = lib.plora_profile_read(pool, ms, n)
+    return rc, list(ms), list(n)
+
+
 def plora_last_hip():
     return lib.plora_last_hip()
 
@@ -238,6 +253,14 @@ class PagedLoraPool:
         rc, st = plora_pool_stats(self.h)
         _check("plora_pool_stats", rc)
         return st
+
+    def profile(self, enable):
+        _check("plora_profile", plora_profile(self.h, enable))
+
+    def profile_read(self):
+        rc, ms, n = plora_profile_read(self.h)
+        _check("plora_profile_read", rc)
+        return ms, n
 
     def set_option(self, key, value):
         _check("plora_pool_set_option", plora_pool_set_option(self.h, key, value))

@@ -5,35 +5,50 @@
 
 namespace plora {
 
-constexpr int kWave = 64;              // one work item = one wavefront = one workgroup
+constexpr int kWave = 64;               // one work item = one wavefront = one workgroup
 constexpr int kMaxSlotsPerLaunch = 128; // pointer pairs carried in the kernel arguments
-constexpr int kShrinkRows = 8;         // rows of A per vector-ALU shrink item
-constexpr int kValuTok = 4;            // tokens per vector-ALU item
-constexpr int kMfmaTok = 64;           // tokens per matrix-core item (4 tiles of 16)
-constexpr int kMfmaRows = 16;          // rows of A per matrix-core shrink item (one 16-wide tile)
-constexpr int kMfmaCols = 128;         // columns of B per matrix-core expand item
-constexpr int kPtWindow = 1024;        // page-table entries a shrink item may stage in LDS
-constexpr int kMaxRank = 512;          // rows of B an expand item may stage page pairs for
+#ifndef PLORA_SHRINK_ROWS
+#define PLORA_SHRINK_ROWS 8
+#endif
+#ifndef PLORA_VALU_TOK
+#define PLORA_VALU_TOK 4
+#endif
+#ifndef PLORA_EXPAND_U
+#define PLORA_EXPAND_U 8
+#endif
+constexpr int kShrinkRows = PLORA_SHRINK_ROWS;  // rows of A per vector-ALU shrink item
+constexpr int kValuTok = PLORA_VALU_TOK;        // tokens per vector-ALU item (1, 2 or 4)
+constexpr int kExpandU = PLORA_EXPAND_U;        // rows of B in flight per vector-ALU expand iteration
+#ifndef PLORA_MFMA_TOK_S
+#define PLORA_MFMA_TOK_S 32
+#endif
+#ifndef PLORA_MFMA_TOK_E
+#define PLORA_MFMA_TOK_E 16
+#endif
+constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item (16 or 32)
+constexpr int kMfmaTokE = PLORA_MFMA_TOK_E;     // tokens per matrix-core expand item (16 or 32)
+#ifndef PLORA_MFMA_ROWS
+#define PLORA_MFMA_ROWS 64
+#endif
+constexpr int kMfmaRows = PLORA_MFMA_ROWS;      // rows of A per matrix-core shrink item (16, 32 or 64)
+constexpr int kMfmaCols = 128;          // columns of B per matrix-core expand pass
+constexpr int kPtWindow = 1024;         // page-table entries a shrink item may stage in LDS
+constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for
+constexpr int kXcds = 8;                // consecutive workgroups go to consecutive XCDs
 
-// One group of tokens that share an adapter (a "segment" of the sorted batch).
-struct SegRec {
-  int32_t tok_start;  // first entry of the group in perm
-  int32_t n_tok;
-  int32_t rank;
-  int32_t pt_off;     // first entry of the adapter's page table in the batch's table array
-  float scale;
-  int32_t adapter;
-  int32_t n_pt;
-  int32_t pad;
-};
-
-// One wavefront's worth of work.
+// One wavefront's worth of work, self-contained so that a wavefront needs a single 32-byte read
+// before it can start fetching page-table entries, activations and weights.
 struct ItemRec {
-  int32_t seg;
-  int32_t tok0;   // first token of the item inside its group
-  int32_t ntok;   // tokens of the item (<= kValuTok or <= kMfmaTok)
-  int32_t j0;     // shrink: first row of A;  expand: unused
+  int16_t kind;    // -1 = padding (nothing to do), 0 = vector-ALU item, 1 = matrix-core item
+  int16_t ntok;    // tokens of the item
+  int16_t rank;    // rank of the adapter (0 = tokens without adapter: shrink only clears v)
+  int16_t j0;      // shrink: first row of A;  expand: unused
+  float scale;
+  int32_t pt_off;  // first entry of the adapter's page table in the batch's table array
+  int32_t tok[4];  // vector-ALU item (kValuTok <= 4): the token indices (unused entries repeat the last one);
+                   // matrix-core item: tok[0] = index of the item's first token in perm
 };
+static_assert(sizeof(ItemRec) == 32, "ItemRec must stay 32 bytes");
 
 struct SlotRec {
   int32_t d_in, d_out;
@@ -47,21 +62,25 @@ struct SlotPtrs {
 
 struct LaunchArgs {
   const uint8_t* slab;
-  const SegRec* segs;
   const int32_t* perm;
   const int32_t* pt;
   const ItemRec* items;
   const SlotRec* slots;   // indexed by absolute slot number
+  int64_t elems_per_rank; // sum over all slots of (d_in + d_out)
   int32_t n_items;
   int32_t slot0;
   int32_t log2_page;
   int32_t v_stride;       // = max_rank
+  int32_t slot_fastest;   // 1: grid = (slots, items, chunks); 0: grid = (items, chunks, slots)
   int32_t pad;
 };
 
-// Launchers (plora_kernels.hip).  kind: 0 = vector-ALU items, 1 = matrix-core items.
-// Shrink grid: (n_items, 1, n_slots).  Expand grid: (n_items, max_chunks, n_slots) where a chunk is
-// 64 * 16 bytes of a row of B for vector-ALU items and kMfmaCols columns for matrix-core items.
+// Launchers (plora_kernels.hip).  kind: 0 = list holds vector-ALU items only, 1 = matrix-core items
+// only, 2 = mixed.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
+// a.slot_fastest is set: consecutive workgroups go to consecutive XCDs, so with a slot count that
+// is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
+// slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row
+// of B (shrink: chunks = 1).
 hipError_t launch_shrink(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, hipStream_t st);
 hipError_t launch_expand(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks,
                          hipStream_t st);

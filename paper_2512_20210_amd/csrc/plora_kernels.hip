@@ -8,17 +8,23 @@
 //   shrink, vector-ALU item : up to 8 rows of A x up to 4 tokens.  Lanes stride along d_in with
 //                             16-byte loads, accumulate in fp32 and finish with a wavefront
 //                             reduction.
-//   shrink, matrix-core item: 16 rows of A x up to 64 tokens, v_mfma_f32_16x16x32 (bf16 / f16).
+//   shrink, matrix-core item: 32 rows of A x up to 64 tokens, v_mfma_f32_16x16x32 (bf16 / f16).
 //   expand, vector-ALU item : all rows of B x 64 lanes x 16 bytes of columns x up to 4 tokens;
 //                             no reduction, read-modify-write of y.
-//   expand, matrix-core item: all rows of B x 128 columns x up to 64 tokens; v is split into a
-//                             high and a low half so that fp32 v loses nothing that matters.
+//   expand, matrix-core item: all rows of B x 512 columns (4 passes of 128) x up to 32 tokens; v is
+//                             split into a high and a low half so that fp32 v loses nothing that
+//                             matters.
 //
 // Address translation: virtual byte o of an adapter is at slab + pt[o >> log2P] * P + (o & (P-1)).
 // A 16-byte vector never straddles a page (all offsets are multiples of 16).  Each item stages the
 // page-table entries it can touch in LDS first, so the translation in the inner loop is an LDS
 // read, and the reduction order depends on virtual offsets only (evicting and reloading an adapter
 // onto other pages gives bit-identical results).
+//
+// Latency: an item's record is self-contained (one 32-byte read), everything that depends only on
+// it (page-table entries, x / v / y rows) is requested at once, and the inner loops over whole
+// 64-lane chunks carry no predicates, so that all loads of an iteration are in flight together; a
+// ragged last chunk goes through a predicated copy of the same code.
 #include "plora_internal.h"
 
 namespace plora {
@@ -32,6 +38,20 @@ template <int DT> struct Elt { static constexpr int B = 2, VEC = 8; };
 template <> struct Elt<2> { static constexpr int B = 4, VEC = 4; };
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// Weights are read once per batch: a streaming (non-temporal) load keeps them from pushing the
+// re-used x / y / v rows and page-table entries out of L2.
+#ifndef PLORA_NT_WEIGHTS
+#define PLORA_NT_WEIGHTS 1
+#endif
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 ldw16(const void* p) {
+#if PLORA_NT_WEIGHTS
+  const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+  return make_uint4(q.x, q.y, q.z, q.w);
+#else
+  return *reinterpret_cast<const uint4*>(p);
+#endif
+}
 __device__ __forceinline__ void st16(void* p, uint4 q) { *reinterpret_cast<uint4*>(p) = q; }
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
@@ -95,19 +115,67 @@ __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 // ------------------------------------------------------------------------------------------
 // shrink, vector-ALU item
 // ------------------------------------------------------------------------------------------
+template <int DT, int NT, bool TAIL>
+__device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uint8_t* __restrict__ x, const int64_t* tok,
+                                                  const int32_t* lds_pt, uint32_t win0, uint64_t base, uint64_t rowb,
+                                                  int nrows, int d_in, int k0, float (*acc)[NT]) {
+  constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
+  const int lp = a.log2_page;
+  const uint64_t pmask = ((uint64_t)1 << lp) - 1;
+  const int k = k0 + (int)threadIdx.x * VEC;
+  const bool ok = !TAIL || k < d_in;
+  const int kk = ok ? k : 0;
+  uint4 xq[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) xq[i] = ld16(x + ((uint64_t)tok[i] * d_in + kk) * EB);
+  uint4 wq[kShrinkRows];
+#pragma unroll
+  for (int jj = 0; jj < kShrinkRows; ++jj) {
+    const int jr = imin(jj, nrows - 1);
+    const uint64_t voff = base + (uint64_t)jr * rowb + (uint64_t)kk * EB;
+    const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(voff >> lp) - win0];
+    wq[jj] = ldw16(a.slab + (pg << lp) + (voff & pmask));
+  }
+  float xf[NT][VEC];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) {
+    if (TAIL && !ok) xq[i] = make_uint4(0, 0, 0, 0);
+    unpack<DT>(xq[i], xf[i]);
+  }
+#pragma unroll
+  for (int jj = 0; jj < kShrinkRows; ++jj) {
+    float wf[VEC];
+    unpack<DT>(wq[jj], wf);
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+#pragma unroll
+      for (int e = 0; e < VEC; ++e) acc[jj][i] = __builtin_fmaf(wf[e], xf[i][e], acc[jj][i]);
+  }
+}
+
 template <int DT, int NT>
-__device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const SegRec sg, const ItemRec it, const SlotRec sl,
+__device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
   const int lane = threadIdx.x;
-  const int r = sg.rank;
+  const int r = it.rank;
   const int d_in = sl.d_in;
   const int vs = a.v_stride;
   int64_t tok[NT];
 #pragma unroll
-  for (int i = 0; i < NT; ++i) tok[i] = a.perm[sg.tok_start + it.tok0 + imin(i, it.ntok - 1)];
+  for (int i = 0; i < NT; ++i) tok[i] = it.tok[i];
 
+  const int nrows = imin(kShrinkRows, r - it.j0);
+  const uint64_t rowb = (uint64_t)d_in * EB;
+  const uint64_t base = (uint64_t)r * EB * (uint64_t)sl.cum + (uint64_t)it.j0 * rowb;
+  const int lp = a.log2_page;
+  const uint32_t win0 = (uint32_t)(base >> lp);
+  if (r > 0) {
+    const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
+    const int32_t* ptg = a.pt + it.pt_off + win0;
+    for (uint32_t i = lane; i < win_n; i += kWave) lds_pt[i] = ptg[i];
+  }
   if (it.j0 == 0) {  // the first row block of a token group also clears the unused tail of v
 #pragma unroll
     for (int i = 0; i < NT; ++i)
@@ -115,16 +183,6 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const SegR
         for (int j = r + lane; j < vs; j += kWave) v[tok[i] * vs + j] = 0.f;
   }
   if (r == 0) return;
-
-  const int nrows = imin(kShrinkRows, r - it.j0);
-  const uint64_t rowb = (uint64_t)d_in * EB;
-  const uint64_t base = (uint64_t)r * EB * (uint64_t)sl.cum + (uint64_t)it.j0 * rowb;
-  const int lp = a.log2_page;
-  const uint64_t pmask = ((uint64_t)1 << lp) - 1;
-  const uint32_t win0 = (uint32_t)(base >> lp);
-  const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
-  const int32_t* ptg = a.pt + sg.pt_off + win0;
-  for (uint32_t i = lane; i < win_n; i += kWave) lds_pt[i] = ptg[i];
   __syncthreads();
 
   float acc[kShrinkRows][NT];
@@ -133,35 +191,12 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const SegR
 #pragma unroll
     for (int i = 0; i < NT; ++i) acc[jj][i] = 0.f;
 
-  for (int k0 = 0; k0 < d_in; k0 += kWave * VEC) {
-    const int k = k0 + lane * VEC;
-    const bool ok = k < d_in;
-    const int kk = ok ? k : 0;
-    uint4 wq[kShrinkRows];
-#pragma unroll
-    for (int jj = 0; jj < kShrinkRows; ++jj) {
-      const int jr = imin(jj, nrows - 1);
-      const uint64_t voff = base + (uint64_t)jr * rowb + (uint64_t)kk * EB;
-      const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(voff >> lp) - win0];
-      wq[jj] = ld16(a.slab + (pg << lp) + (voff & pmask));
-    }
-    float xf[NT][VEC];
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-      uint4 xq = ld16(x + ((uint64_t)tok[i] * d_in + kk) * EB);
-      if (!ok) xq = make_uint4(0, 0, 0, 0);
-      unpack<DT>(xq, xf[i]);
-    }
-#pragma unroll
-    for (int jj = 0; jj < kShrinkRows; ++jj) {
-      float wf[VEC];
-      unpack<DT>(wq[jj], wf);
-#pragma unroll
-      for (int i = 0; i < NT; ++i)
-#pragma unroll
-        for (int e = 0; e < VEC; ++e) acc[jj][i] = __builtin_fmaf(wf[e], xf[i][e], acc[jj][i]);
-    }
-  }
+  constexpr int CH = kWave * VEC;
+  const int full = d_in / CH * CH;
+  for (int k0 = 0; k0 < full; k0 += CH)
+    shrink_valu_chunk<DT, NT, false>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
+  if (full < d_in) shrink_valu_chunk<DT, NT, true>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
+
 #pragma unroll
   for (int jj = 0; jj < kShrinkRows; ++jj)
 #pragma unroll
@@ -172,70 +207,73 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const SegR
 }
 
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_shrink_valu(const LaunchArgs a, const SlotPtrs p) {
-  __shared__ int32_t lds_pt[kPtWindow];
-  const ItemRec it = a.items[blockIdx.x];
-  const SegRec sg = a.segs[it.seg];
-  const int q = blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
-  const uint8_t* x = (const uint8_t*)p.a[q];
-  float* v = (float*)p.b[q];
-  if (it.ntok <= 1) shrink_valu_body<DT, 1>(a, sg, it, sl, x, v, lds_pt);
-  else if (it.ntok == 2) shrink_valu_body<DT, 2>(a, sg, it, sl, x, v, lds_pt);
-  else shrink_valu_body<DT, kValuTok>(a, sg, it, sl, x, v, lds_pt);
+__device__ __forceinline__ void shrink_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
+                                                 const uint8_t* x, float* v, int32_t* lds_pt) {
+  if (it.ntok <= 1) shrink_valu_body<DT, 1>(a, it, sl, x, v, lds_pt);
+  else if (it.ntok == 2) shrink_valu_body<DT, 2>(a, it, sl, x, v, lds_pt);
+  else shrink_valu_body<DT, kValuTok>(a, it, sl, x, v, lds_pt);
 }
 
 // ------------------------------------------------------------------------------------------
 // expand, vector-ALU item
 // ------------------------------------------------------------------------------------------
+// Number of page-table entries of a rank-r adapter.
+__device__ __forceinline__ int table_len(const LaunchArgs& a, int r, int eb) {
+  const uint64_t S = (uint64_t)r * eb * (uint64_t)a.elems_per_rank;
+  return (int)((S + (((uint64_t)1 << a.log2_page) - 1)) >> a.log2_page);
+}
+
 // Stages, for every row j of B, the physical pages that hold the first and the last byte of the
-// item's piece of that row (an item's piece of a row is at most 4096 bytes, a page at least that).
-__device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const SegRec& sg, uint64_t base, uint64_t rowb,
-                                                uint32_t piece_bytes, int2* lds_pg) {
+// item's piece of that row (a piece is 1024 bytes, a page at least 4096).  No barrier here: the
+// caller issues its other loads first and then calls __syncthreads().
+__device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const ItemRec& it, int n_pt, uint64_t base,
+                                                uint64_t rowb, uint32_t piece_bytes, int2* lds_pg) {
   const int lp = a.log2_page;
-  const int32_t* ptg = a.pt + sg.pt_off;
-  for (int j = threadIdx.x; j < sg.rank; j += kWave) {
+  const int32_t* ptg = a.pt + it.pt_off;
+  for (int j = threadIdx.x; j < it.rank; j += kWave) {
     const uint64_t vo = base + (uint64_t)j * rowb;
     const uint32_t q0 = (uint32_t)(vo >> lp);
-    const uint32_t q1 = imin((int)((vo + piece_bytes - 1) >> lp), sg.n_pt - 1);
+    const uint32_t q1 = imin((int)((vo + piece_bytes - 1) >> lp), n_pt - 1);
     lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
   }
-  __syncthreads();
 }
 
 template <int DT, int NT>
-__device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const SegRec sg, const ItemRec it, const SlotRec sl,
+__device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
   const int lane = threadIdx.x;
-  const int r = sg.rank;
+  const int r = it.rank;
   const int d_out = sl.d_out;
-  const int n0w = blockIdx.y * (kWave * VEC);
+  const int n0w = (a.slot_fastest ? blockIdx.z : blockIdx.y) * (kWave * VEC);
   if (n0w >= d_out || r == 0) return;
   const int n = n0w + lane * VEC;
   const bool ok = n < d_out;
   const uint32_t lane_b = ok ? lane * 16 : 0;
   const int vs = a.v_stride;
   const int lp = a.log2_page;
-  const uint32_t pmask = (1u << lp) - 1;  // pages are at most 2^31 bytes
+  const uint32_t pmask = (1u << lp) - 1;  // pages are at most 2^30 bytes
   const uint64_t rowb = (uint64_t)d_out * EB;
   const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0w * EB;
-  stage_row_pages(a, sg, base, rowb, kWave * 16, lds_pg);
+  stage_row_pages(a, it, table_len(a, r, EB), base, rowb, kWave * 16, lds_pg);
 
   const float* vrow[NT];
-  int64_t tok[NT];
+  uint8_t* yp[NT];
+  uint4 yq[NT];
 #pragma unroll
   for (int i = 0; i < NT; ++i) {
-    tok[i] = a.perm[sg.tok_start + it.tok0 + imin(i, it.ntok - 1)];
-    vrow[i] = v + tok[i] * vs;
+    vrow[i] = v + (int64_t)it.tok[i] * vs;
+    yp[i] = y + ((uint64_t)it.tok[i] * d_out + (ok ? n : n0w)) * EB;
+    yq[i] = ld16(yp[i]);  // requested now, used after the loop
   }
+  __syncthreads();
   float acc[NT][VEC];
 #pragma unroll
   for (int i = 0; i < NT; ++i)
 #pragma unroll
     for (int e = 0; e < VEC; ++e) acc[i][e] = 0.f;
 
-  constexpr int U = 8;
+  constexpr int U = kExpandU;
   int j = 0;
   for (; j + U <= r; j += U) {
     uint4 wq[U];
@@ -245,7 +283,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const SegR
       const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
       const int2 pp = lds_pg[j + u];
       const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-      wq[u] = ld16(a.slab + (pg << lp) + (inpage & pmask));
+      wq[u] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -265,7 +303,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const SegR
     const int2 pp = lds_pg[j];
     const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
     float wf[VEC];
-    unpack<DT>(ld16(a.slab + (pg << lp) + (inpage & pmask)), wf);
+    unpack<DT>(ldw16(a.slab + (pg << lp) + (inpage & pmask)), wf);
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
       const float vj = vrow[i][j];
@@ -277,28 +315,21 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const SegR
 #pragma unroll
   for (int i = 0; i < NT; ++i) {
     if (i < it.ntok) {
-      uint8_t* yp = y + ((uint64_t)tok[i] * d_out + n) * EB;
       float yf[VEC];
-      unpack<DT>(ld16(yp), yf);
+      unpack<DT>(yq[i], yf);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) yf[e] = yf[e] + sg.scale * acc[i][e];
-      st16(yp, pack<DT>(yf));
+      for (int e = 0; e < VEC; ++e) yf[e] = yf[e] + it.scale * acc[i][e];
+      st16(yp[i], pack<DT>(yf));
     }
   }
 }
 
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_expand_valu(const LaunchArgs a, const SlotPtrs p) {
-  __shared__ int2 lds_pg[kMaxRank];
-  const ItemRec it = a.items[blockIdx.x];
-  const SegRec sg = a.segs[it.seg];
-  const int q = blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
-  const float* v = (const float*)p.a[q];
-  uint8_t* y = (uint8_t*)p.b[q];
-  if (it.ntok <= 1) expand_valu_body<DT, 1>(a, sg, it, sl, v, y, lds_pg);
-  else if (it.ntok == 2) expand_valu_body<DT, 2>(a, sg, it, sl, v, y, lds_pg);
-  else expand_valu_body<DT, kValuTok>(a, sg, it, sl, v, y, lds_pg);
+__device__ __forceinline__ void expand_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
+                                                 const float* v, uint8_t* y, int2* lds_pg) {
+  if (it.ntok <= 1) expand_valu_body<DT, 1>(a, it, sl, v, y, lds_pg);
+  else if (it.ntok == 2) expand_valu_body<DT, 2>(a, it, sl, v, y, lds_pg);
+  else expand_valu_body<DT, kValuTok>(a, it, sl, v, y, lds_pg);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -315,98 +346,139 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// shrink: D[token, row] += X[token, k] * A[row, k].  Within each run of 64 k-values lane group g
-// takes k = 16 g .. 16 g + 15 as two 8-wide halves, so a wavefront reads whole 128-byte lines of
-// every row; the order of the contraction index is free as long as both operands agree.
-template <int DT, int MT>
-__device__ __forceinline__ void shrink_mfma_body(const LaunchArgs& a, const SegRec sg, const ItemRec it, const SlotRec sl,
+// One iteration of the matrix-core shrink: KU runs of 64 k-values for NTL row tiles and MT token
+// tiles.  Within a run of 64 k-values (128 bytes of a row) lane group g takes k = 8 g .. 8 g + 7 of
+// the first half and of the second half, so every load instruction reads 64 contiguous bytes of
+// each of its 16 rows; the order of the contraction index is free as long as both operands agree.
+template <int DT, int MT, int NTL, int KU, bool TAIL>
+__device__ __forceinline__ void shrink_mfma_chunk(const LaunchArgs& a, const uint8_t* const* xrow, const uint64_t* wrow,
+                                                  const int32_t* lds_pt, uint32_t win0, int d_in, int k0,
+                                                  f32x4 (*acc)[NTL]) {
+  constexpr int EB = 2;
+  const int lp = a.log2_page;
+  const uint64_t pmask = ((uint64_t)1 << lp) - 1;
+  const int g8 = ((int)threadIdx.x >> 4) * 8;
+  uint4 xq[KU][2][MT], wq[KU][2][NTL];
+  bool ok[KU][2];
+#pragma unroll
+  for (int u = 0; u < KU; ++u)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int k = k0 + u * 64 + h * 32 + g8;
+      ok[u][h] = !TAIL || k < d_in;
+      const int kk = ok[u][h] ? k : 0;
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) xq[u][h][mt] = ld16(xrow[mt] + (uint64_t)kk * EB);
+#pragma unroll
+      for (int nt = 0; nt < NTL; ++nt) {
+        const uint64_t vo = wrow[nt] + (uint64_t)kk * EB;
+        const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(vo >> lp) - win0];
+        wq[u][h][nt] = ldw16(a.slab + (pg << lp) + (vo & pmask));
+      }
+    }
+#pragma unroll
+  for (int u = 0; u < KU; ++u)
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      if (TAIL) {
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt)
+          if (!ok[u][h]) wq[u][h][nt] = make_uint4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt) acc[mt][nt] = mfma16<DT>(xq[u][h][mt], wq[u][h][nt], acc[mt][nt]);
+    }
+}
+
+// shrink: D[token, row] += X[token, k] * A[row, k] for NTL tiles of 16 rows and MT tiles of 16
+// tokens.
+template <int DT, int MT, int NTL>
+__device__ __forceinline__ void shrink_mfma_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt) {
   constexpr int EB = 2;
+  constexpr int KU = NTL == 4 ? 1 : 2;  // 8 to 16 loads of 16 bytes per lane in flight per iteration
   const int lane = threadIdx.x;
   const int g = lane >> 4, c = lane & 15;
-  const int r = sg.rank;
+  const int r = it.rank;
   const int d_in = sl.d_in;
   const int vs = a.v_stride;
   const int lp = a.log2_page;
-  const uint64_t pmask = ((uint64_t)1 << lp) - 1;
+  const int32_t* perm = a.perm + it.tok[0];
 
-  if (it.j0 == 0) {  // clear v[t, r .. v_stride) for the item's tokens
-    for (int i = 0; i < it.ntok; ++i) {
-      const int64_t t = a.perm[sg.tok_start + it.tok0 + i];
-      for (int j = r + lane; j < vs; j += kWave) v[t * vs + j] = 0.f;
-    }
-  }
   const int nrows = imin(kMfmaRows, r - it.j0);
   const uint64_t rowb = (uint64_t)d_in * EB;
   const uint64_t base = (uint64_t)r * EB * (uint64_t)sl.cum + (uint64_t)it.j0 * rowb;
   const uint32_t win0 = (uint32_t)(base >> lp);
   const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
-  const int32_t* ptg = a.pt + sg.pt_off + win0;
+  const int32_t* ptg = a.pt + it.pt_off + win0;
   for (uint32_t i = lane; i < win_n; i += kWave) lds_pt[i] = ptg[i];
-  __syncthreads();
 
-  const uint64_t wrow = base + (uint64_t)imin(c, nrows - 1) * rowb;
+  uint64_t wrow[NTL];
+#pragma unroll
+  for (int nt = 0; nt < NTL; ++nt) wrow[nt] = base + (uint64_t)imin(nt * 16 + c, nrows - 1) * rowb;
   const uint8_t* xrow[MT];
+  int trow[MT];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int64_t t = a.perm[sg.tok_start + it.tok0 + imin(mt * 16 + c, it.ntok - 1)];
-    xrow[mt] = x + (uint64_t)t * d_in * EB;
+    trow[mt] = perm[imin(mt * 16 + c, it.ntok - 1)];
+    xrow[mt] = x + (uint64_t)trow[mt] * d_in * EB;
   }
-  f32x4 acc[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) acc[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  if (it.j0 == 0) {  // clear v[t, r .. v_stride) for the item's tokens
+    for (int i = 0; i < it.ntok; ++i) {
+      const int64_t t = perm[i];
+      for (int j = r + lane; j < vs; j += kWave) v[t * vs + j] = 0.f;
+    }
+  }
+  __syncthreads();
 
-  for (int k0 = 0; k0 < d_in; k0 += 64) {
-    const int k = k0 + g * 16;
-    const bool ok0 = k < d_in, ok1 = k + 8 < d_in;
-    const int ka = ok0 ? k : 0, kb = ok1 ? k + 8 : 0;
-    const uint64_t vo0 = wrow + (uint64_t)ka * EB, vo1 = wrow + (uint64_t)kb * EB;
-    const uint64_t p0 = (uint64_t)(uint32_t)lds_pt[(uint32_t)(vo0 >> lp) - win0];
-    const uint64_t p1 = (uint64_t)(uint32_t)lds_pt[(uint32_t)(vo1 >> lp) - win0];
-    uint4 w0 = ld16(a.slab + (p0 << lp) + (vo0 & pmask));
-    uint4 w1 = ld16(a.slab + (p1 << lp) + (vo1 & pmask));
-    if (!ok0) w0 = make_uint4(0, 0, 0, 0);
-    if (!ok1) w1 = make_uint4(0, 0, 0, 0);
-    uint4 x0[MT], x1[MT];
+  f32x4 acc[MT][NTL];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      x0[mt] = ld16(xrow[mt] + (uint64_t)ka * EB);
-      x1[mt] = ld16(xrow[mt] + (uint64_t)kb * EB);
-    }
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      acc[mt] = mfma16<DT>(x0[mt], w0, acc[mt]);
-      acc[mt] = mfma16<DT>(x1[mt], w1, acc[mt]);
-    }
-  }
-  // result: lane holds weight row it.j0 + c for tokens 4 g .. 4 g + 3 of every tile
-  if (c < nrows) {
+    for (int nt = 0; nt < NTL; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  constexpr int CH = 64 * KU;
+  const int full = d_in / CH * CH;
+  for (int k0 = 0; k0 < full; k0 += CH)
+    shrink_mfma_chunk<DT, MT, NTL, KU, false>(a, xrow, wrow, lds_pt, win0, d_in, k0, acc);
+  for (int k0 = full; k0 < d_in; k0 += 64)
+    shrink_mfma_chunk<DT, MT, NTL, 1, true>(a, xrow, wrow, lds_pt, win0, d_in, k0, acc);
+
+  // result: lane holds weight row it.j0 + 16 nt + c for tokens 4 g .. 4 g + 3 of every token tile
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int ti = mt * 16 + g * 4 + i;
-        if (ti < it.ntok) {
-          const int64_t t = a.perm[sg.tok_start + it.tok0 + ti];
-          v[t * vs + it.j0 + c] = acc[mt][i];
-        }
+    for (int i = 0; i < 4; ++i) {
+      const int ti = mt * 16 + g * 4 + i;
+      const int64_t t = __shfl(trow[mt], g * 4 + i, 64);
+      if (ti < it.ntok) {
+#pragma unroll
+        for (int nt = 0; nt < NTL; ++nt)
+          if (nt * 16 + c < nrows) v[t * vs + it.j0 + nt * 16 + c] = acc[mt][nt][i];
       }
-  }
+    }
+}
+
+template <int DT, int MT>
+__device__ __forceinline__ void shrink_mfma_rows(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
+                                                 const uint8_t* x, float* v, int32_t* lds_pt) {
+  const int nrows = imin(kMfmaRows, it.rank - it.j0);
+  if (kMfmaRows <= 16 || nrows <= 16) shrink_mfma_body<DT, MT, 1>(a, it, sl, x, v, lds_pt);
+  else if (kMfmaRows <= 32 || nrows <= 32) shrink_mfma_body<DT, MT, 2>(a, it, sl, x, v, lds_pt);
+  else shrink_mfma_body<DT, MT, 4>(a, it, sl, x, v, lds_pt);
 }
 
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_shrink_mfma(const LaunchArgs a, const SlotPtrs p) {
-  __shared__ int32_t lds_pt[kPtWindow];
-  const ItemRec it = a.items[blockIdx.x];
-  const SegRec sg = a.segs[it.seg];
-  const int q = blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
-  const uint8_t* x = (const uint8_t*)p.a[q];
-  float* v = (float*)p.b[q];
-  if (it.ntok <= 16) shrink_mfma_body<DT, 1>(a, sg, it, sl, x, v, lds_pt);
-  else if (it.ntok <= 32) shrink_mfma_body<DT, 2>(a, sg, it, sl, x, v, lds_pt);
-  else shrink_mfma_body<DT, 4>(a, sg, it, sl, x, v, lds_pt);
+__device__ __forceinline__ void shrink_mfma_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
+                                                 const uint8_t* x, float* v, int32_t* lds_pt) {
+  if constexpr (DT == 2) return;
+  else {
+    if (kMfmaTokS <= 16 || it.ntok <= 16) shrink_mfma_rows<DT, 1>(a, it, sl, x, v, lds_pt);
+    else shrink_mfma_rows<DT, 2>(a, it, sl, x, v, lds_pt);
+  }
 }
 
 // Splits 8 fp32 values into a high and a low 16-bit part: hi = round(v), lo = round(v - hi).
@@ -427,149 +499,229 @@ __device__ __forceinline__ void split_hi_lo(const float* f, uint4& hi, uint4& lo
   lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
 }
 
+// One K-step (32 rows of B) of the matrix-core expand for one 128-column pass.
+template <int DT, int MT, bool TAIL>
+__device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int2* lds_pg, const float* const* vrow,
+                                                  uint64_t base, uint64_t rowb, uint32_t lane_b, int r, int jb,
+                                                  f32x4 (*acc)[8]) {
+  const int g = (int)threadIdx.x >> 4;
+  const int lp = a.log2_page;
+  const uint32_t pmask = (1u << lp) - 1;
+  const int vs = a.v_stride;
+  const int j8 = jb + 8 * g;
+  float vf[MT][8];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) {
+    if ((!TAIL || j8 + 8 <= r) && (vs & 3) == 0) {
+      const float4 va = *reinterpret_cast<const float4*>(vrow[mt] + j8);
+      const float4 vb = *reinterpret_cast<const float4*>(vrow[mt] + j8 + 4);
+      vf[mt][0] = va.x; vf[mt][1] = va.y; vf[mt][2] = va.z; vf[mt][3] = va.w;
+      vf[mt][4] = vb.x; vf[mt][5] = vb.y; vf[mt][6] = vb.z; vf[mt][7] = vb.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vf[mt][e] = (j8 + e < r) ? vrow[mt][j8 + e] : 0.f;
+    }
+  }
+  uint4 wr[8];
+#pragma unroll
+  for (int jj = 0; jj < 8; ++jj) {
+    const int j = j8 + jj;
+    const int je = TAIL ? imin(j, r - 1) : j;
+    const uint64_t vo = base + (uint64_t)je * rowb;
+    const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
+    const int2 pp = lds_pg[je];
+    const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
+    wr[jj] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+  }
+  if (TAIL) {
+#pragma unroll
+    for (int jj = 0; jj < 8; ++jj)
+      if (j8 + jj >= r) wr[jj] = make_uint4(0, 0, 0, 0);
+  }
+  uint4 vhi[MT], vlo[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) split_hi_lo<DT>(vf[mt], vhi[mt], vlo[mt]);
+  // in-register transpose, two column offsets at a time: the 8 rows' values of one column
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint32_t r0 = (&wr[0].x)[d], r1 = (&wr[1].x)[d], r2 = (&wr[2].x)[d], r3 = (&wr[3].x)[d];
+    const uint32_t r4 = (&wr[4].x)[d], r5 = (&wr[5].x)[d], r6 = (&wr[6].x)[d], r7 = (&wr[7].x)[d];
+    const uint4 wlo = make_uint4(__builtin_amdgcn_perm(r1, r0, 0x05040100u), __builtin_amdgcn_perm(r3, r2, 0x05040100u),
+                                 __builtin_amdgcn_perm(r5, r4, 0x05040100u), __builtin_amdgcn_perm(r7, r6, 0x05040100u));
+    const uint4 whi = make_uint4(__builtin_amdgcn_perm(r1, r0, 0x07060302u), __builtin_amdgcn_perm(r3, r2, 0x07060302u),
+                                 __builtin_amdgcn_perm(r5, r4, 0x07060302u), __builtin_amdgcn_perm(r7, r6, 0x07060302u));
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      acc[mt][2 * d] = mfma16<DT>(vhi[mt], wlo, acc[mt][2 * d]);
+      acc[mt][2 * d] = mfma16<DT>(vlo[mt], wlo, acc[mt][2 * d]);
+      acc[mt][2 * d + 1] = mfma16<DT>(vhi[mt], whi, acc[mt][2 * d + 1]);
+      acc[mt][2 * d + 1] = mfma16<DT>(vlo[mt], whi, acc[mt][2 * d + 1]);
+    }
+  }
+}
+
 // expand: D[token, col] += V[token, j] * B[j, col], K = 32 rows of B per step.  Lane (g, c) loads
 // the 8x8 block rows 8 g .. 8 g + 7 x columns 8 c .. 8 c + 7 (16 bytes per row), transposes it in
 // registers into eight 8-value K-vectors, one per column offset cc, and issues eight MFMAs whose
 // result column l%16 stands for the real column 8 c + cc.  A lane therefore ends up with 8
 // consecutive columns of y for each of its 4 token rows: one 16-byte read-modify-write each.
+// One item covers 512 columns as 4 passes of 128.
 template <int DT, int MT>
-__device__ __forceinline__ void expand_mfma_body(const LaunchArgs& a, const SegRec sg, const ItemRec it, const SlotRec sl,
+__device__ __forceinline__ void expand_mfma_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg) {
   constexpr int EB = 2;
   const int lane = threadIdx.x;
   const int g = lane >> 4, c = lane & 15;
-  const int r = sg.rank;
+  const int r = it.rank;
   const int d_out = sl.d_out;
-  const int n0w = blockIdx.y * kMfmaCols;
-  if (n0w >= d_out) return;
-  const int n = n0w + 8 * c;
-  const bool ok = n < d_out;
-  const uint32_t lane_b = ok ? c * 16 : 0;
+  const int n0i = (a.slot_fastest ? blockIdx.z : blockIdx.y) * (kWave * 8);
+  if (n0i >= d_out) return;
   const int vs = a.v_stride;
-  const int lp = a.log2_page;
-  const uint32_t pmask = (1u << lp) - 1;
   const uint64_t rowb = (uint64_t)d_out * EB;
-  const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0w * EB;
-  stage_row_pages(a, sg, base, rowb, kMfmaCols * EB, lds_pg);
+  const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0i * EB;
+  stage_row_pages(a, it, table_len(a, r, EB), base, rowb, kWave * 16, lds_pg);
+  const int32_t* perm = a.perm + it.tok[0];
 
   const float* vrow[MT];
+  int64_t trow[MT][4];  // tokens of the result rows this lane holds
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    const int64_t t = a.perm[sg.tok_start + it.tok0 + imin(mt * 16 + c, it.ntok - 1)];
-    vrow[mt] = v + t * vs;
+    const int tc = perm[imin(mt * 16 + c, it.ntok - 1)];
+    vrow[mt] = v + (int64_t)tc * vs;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) trow[mt][i] = __shfl(tc, g * 4 + i, 64);
   }
-  f32x4 acc[MT][8];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int cc = 0; cc < 8; ++cc) acc[mt][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+  __syncthreads();
 
-  for (int jb = 0; jb < r; jb += 32) {
-    uint4 wr[8];
+  for (int pass = 0; pass < 4; ++pass) {
+    const int n = n0i + pass * kMfmaCols + 8 * c;
+    if (n0i + pass * kMfmaCols >= d_out) break;
+    const bool ok = n < d_out;
+    const uint32_t lane_b = ok ? (uint32_t)(pass * kMfmaCols * EB + c * 16) : 0;
+    f32x4 acc[MT][8];
 #pragma unroll
-    for (int jj = 0; jj < 8; ++jj) {
-      const int j = jb + 8 * g + jj;
-      const int je = imin(j, r - 1);
-      const uint64_t vo = base + (uint64_t)je * rowb;
-      const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
-      const int2 pp = lds_pg[je];
-      const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-      wr[jj] = ld16(a.slab + (pg << lp) + (inpage & pmask));
-      if (j >= r) wr[jj] = make_uint4(0, 0, 0, 0);
-    }
-    // in-register transpose: wk[cc] = the 8 rows' values of column cc
-    uint4 wk[8];
+    for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int d = 0; d < 4; ++d) {
-      const uint32_t r0 = (&wr[0].x)[d], r1 = (&wr[1].x)[d], r2 = (&wr[2].x)[d], r3 = (&wr[3].x)[d];
-      const uint32_t r4 = (&wr[4].x)[d], r5 = (&wr[5].x)[d], r6 = (&wr[6].x)[d], r7 = (&wr[7].x)[d];
-      wk[2 * d] = make_uint4(__builtin_amdgcn_perm(r1, r0, 0x05040100u), __builtin_amdgcn_perm(r3, r2, 0x05040100u),
-                             __builtin_amdgcn_perm(r5, r4, 0x05040100u), __builtin_amdgcn_perm(r7, r6, 0x05040100u));
-      wk[2 * d + 1] = make_uint4(__builtin_amdgcn_perm(r1, r0, 0x07060302u), __builtin_amdgcn_perm(r3, r2, 0x07060302u),
-                                 __builtin_amdgcn_perm(r5, r4, 0x07060302u), __builtin_amdgcn_perm(r7, r6, 0x07060302u));
-    }
+      for (int cc = 0; cc < 8; ++cc) acc[mt][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    int jb = 0;
+    for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+    if (jb < r) expand_mfma_kstep<DT, MT, true>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+
+    if (ok) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      float vf[8];
-      const int j8 = jb + 8 * g;
-      if (j8 + 8 <= r && (vs & 3) == 0) {
-        const float4 va = *reinterpret_cast<const float4*>(vrow[mt] + j8);
-        const float4 vb = *reinterpret_cast<const float4*>(vrow[mt] + j8 + 4);
-        vf[0] = va.x; vf[1] = va.y; vf[2] = va.z; vf[3] = va.w; vf[4] = vb.x; vf[5] = vb.y; vf[6] = vb.z; vf[7] = vb.w;
-      } else {
+      for (int mt = 0; mt < MT; ++mt) {
+        uint4 yq[4];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) vf[e] = (j8 + e < r) ? vrow[mt][j8 + e] : 0.f;
-      }
-      uint4 hi, lo;
-      split_hi_lo<DT>(vf, hi, lo);
+        for (int i = 0; i < 4; ++i) yq[i] = ld16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB);
 #pragma unroll
-      for (int cc = 0; cc < 8; ++cc) {
-        acc[mt][cc] = mfma16<DT>(hi, wk[cc], acc[mt][cc]);
-        acc[mt][cc] = mfma16<DT>(lo, wk[cc], acc[mt][cc]);
+        for (int i = 0; i < 4; ++i) {
+          const int ti = mt * 16 + g * 4 + i;
+          if (ti < it.ntok) {
+            float yf[8];
+            unpack<DT>(yq[i], yf);
+#pragma unroll
+            for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
+            st16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
+          }
+        }
       }
     }
   }
-  if (!ok) return;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int ti = mt * 16 + g * 4 + i;
-      if (ti < it.ntok) {
-        const int64_t t = a.perm[sg.tok_start + it.tok0 + ti];
-        uint8_t* yp = y + ((uint64_t)t * d_out + n) * EB;
-        float yf[8];
-        unpack<DT>(ld16(yp), yf);
-#pragma unroll
-        for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + sg.scale * acc[mt][cc][i];
-        st16(yp, pack<DT>(yf));
-      }
-    }
 }
 
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_expand_mfma(const LaunchArgs a, const SlotPtrs p) {
+__device__ __forceinline__ void expand_mfma_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
+                                                 const float* v, uint8_t* y, int2* lds_pg) {
+  if constexpr (DT == 2) return;
+  else {
+    if (kMfmaTokE <= 16 || it.ntok <= 16) expand_mfma_body<DT, 1>(a, it, sl, v, y, lds_pg);
+    else expand_mfma_body<DT, 2>(a, it, sl, v, y, lds_pg);
+  }
+}
+
+// KIND 0: vector-ALU items only, 1: matrix-core items only, 2: mixed list.
+template <int DT, int KIND>
+__global__ __launch_bounds__(kWave) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ int32_t lds_pt[kPtWindow];
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
+  if (it.kind < 0) return;
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  const SlotRec sl = a.slots[a.slot0 + q];
+  const uint8_t* x = (const uint8_t*)p.a[q];
+  float* v = (float*)p.b[q];
+  if constexpr (KIND == 0) shrink_valu_item<DT>(a, it, sl, x, v, lds_pt);
+  else if constexpr (KIND == 1) shrink_mfma_item<DT>(a, it, sl, x, v, lds_pt);
+  else {
+    if (it.kind) shrink_mfma_item<DT>(a, it, sl, x, v, lds_pt);
+    else shrink_valu_item<DT>(a, it, sl, x, v, lds_pt);
+  }
+}
+
+template <int DT, int KIND>
+__global__ __launch_bounds__(kWave) void k_expand(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int2 lds_pg[kMaxRank];
-  const ItemRec it = a.items[blockIdx.x];
-  const SegRec sg = a.segs[it.seg];
-  const int q = blockIdx.z;
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
+  if (it.kind < 0) return;
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[a.slot0 + q];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
-  if (it.ntok <= 16) expand_mfma_body<DT, 1>(a, sg, it, sl, v, y, lds_pg);
-  else if (it.ntok <= 32) expand_mfma_body<DT, 2>(a, sg, it, sl, v, y, lds_pg);
-  else expand_mfma_body<DT, 4>(a, sg, it, sl, v, y, lds_pg);
+  if constexpr (KIND == 0) expand_valu_item<DT>(a, it, sl, v, y, lds_pg);
+  else if constexpr (KIND == 1) expand_mfma_item<DT>(a, it, sl, v, y, lds_pg);
+  else {
+    if (it.kind) expand_mfma_item<DT>(a, it, sl, v, y, lds_pg);
+    else expand_valu_item<DT>(a, it, sl, v, y, lds_pg);
+  }
+}
+
+template <int KIND>
+void launch_shrink_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, const SlotPtrs& p) {
+  const dim3 block(kWave);
+  if (dtype == 0) hipLaunchKernelGGL((k_shrink<0, KIND>), grid, block, 0, st, a, p);
+  else if (dtype == 1) hipLaunchKernelGGL((k_shrink<1, KIND>), grid, block, 0, st, a, p);
+  else hipLaunchKernelGGL((k_shrink<2, KIND>), grid, block, 0, st, a, p);
+}
+template <int KIND>
+void launch_expand_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, const SlotPtrs& p) {
+  const dim3 block(kWave);
+  if (dtype == 0) hipLaunchKernelGGL((k_expand<0, KIND>), grid, block, 0, st, a, p);
+  else if (dtype == 1) hipLaunchKernelGGL((k_expand<1, KIND>), grid, block, 0, st, a, p);
+  else hipLaunchKernelGGL((k_expand<2, KIND>), grid, block, 0, st, a, p);
 }
 
 }  // namespace
 
-hipError_t launch_shrink(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, hipStream_t st) {
-  if (a.n_items <= 0 || n_slots <= 0) return hipSuccess;
-  const dim3 grid(a.n_items, 1, n_slots), block(kWave);
-  if (kind == 0) {
-    if (dtype == 0) hipLaunchKernelGGL(k_shrink_valu<0>, grid, block, 0, st, a, p);
-    else if (dtype == 1) hipLaunchKernelGGL(k_shrink_valu<1>, grid, block, 0, st, a, p);
-    else hipLaunchKernelGGL(k_shrink_valu<2>, grid, block, 0, st, a, p);
-  } else {
-    if (dtype == 0) hipLaunchKernelGGL(k_shrink_mfma<0>, grid, block, 0, st, a, p);
-    else if (dtype == 1) hipLaunchKernelGGL(k_shrink_mfma<1>, grid, block, 0, st, a, p);
-    else return hipErrorInvalidValue;
+hipError_t launch_shrink(int dtype, int kind, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, hipStream_t st) {
+  if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
+  if (dtype == 2 && kind == 1) return hipErrorInvalidValue;
+  LaunchArgs a = a0;
+  const int step = a0.slot_fastest ? 65535 : a0.n_items;  // grid.z is limited to 65535
+  for (int first = 0; first < a0.n_items; first += step) {
+    a.items = a0.items + first;
+    a.n_items = a0.n_items - first < step ? a0.n_items - first : step;
+    const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, a.n_items) : dim3(a.n_items, 1, n_slots);
+    if (kind == 0) launch_shrink_k<0>(dtype, grid, st, a, p);
+    else if (kind == 1) launch_shrink_k<1>(dtype, grid, st, a, p);
+    else launch_shrink_k<2>(dtype, grid, st, a, p);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_expand(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks,
+hipError_t launch_expand(int dtype, int kind, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks,
                          hipStream_t st) {
-  if (a.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
-  const dim3 grid(a.n_items, max_chunks, n_slots), block(kWave);
-  if (kind == 0) {
-    if (dtype == 0) hipLaunchKernelGGL(k_expand_valu<0>, grid, block, 0, st, a, p);
-    else if (dtype == 1) hipLaunchKernelGGL(k_expand_valu<1>, grid, block, 0, st, a, p);
-    else hipLaunchKernelGGL(k_expand_valu<2>, grid, block, 0, st, a, p);
-  } else {
-    if (dtype == 0) hipLaunchKernelGGL(k_expand_mfma<0>, grid, block, 0, st, a, p);
-    else if (dtype == 1) hipLaunchKernelGGL(k_expand_mfma<1>, grid, block, 0, st, a, p);
-    else return hipErrorInvalidValue;
+  if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
+  if (dtype == 2 && kind == 1) return hipErrorInvalidValue;
+  if (max_chunks > 65535) return hipErrorInvalidValue;
+  LaunchArgs a = a0;
+  const int step = a0.slot_fastest ? 65535 : a0.n_items;
+  for (int first = 0; first < a0.n_items; first += step) {
+    a.items = a0.items + first;
+    a.n_items = a0.n_items - first < step ? a0.n_items - first : step;
+    const dim3 grid = a.slot_fastest ? dim3(n_slots, a.n_items, max_chunks) : dim3(a.n_items, max_chunks, n_slots);
+    if (kind == 0) launch_expand_k<0>(dtype, grid, st, a, p);
+    else if (kind == 1) launch_expand_k<1>(dtype, grid, st, a, p);
+    else launch_expand_k<2>(dtype, grid, st, a, p);
   }
   return hipGetLastError();
 }

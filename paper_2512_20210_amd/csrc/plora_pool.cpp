@@ -58,10 +58,15 @@ struct plora_batch {
   uint8_t* d_img = nullptr;
   size_t cap = 0;
   // offsets inside the image
-  size_t off_segs = 0, off_perm = 0, off_pt = 0, off_items[4] = {0, 0, 0, 0};
-  int32_t n_items[4] = {0, 0, 0, 0};  // shrink valu, shrink mfma, expand valu, expand mfma
+  size_t off_perm = 0, off_pt = 0;
+  // work lists: [op][kind + 3 * layout], op 0 = shrink, 1 = expand; kind 0 = vector-ALU items,
+  // 1 = matrix-core items, 2 = both (single-launch mode); layout 0 = longest first (for launches
+  // whose fastest grid dimension is the slot), 1 = dealt into 8 interleaved XCD queues
+  size_t off_items[2][6] = {{0}, {0}};
+  int32_t n_items[2][6] = {{0}, {0}};
   std::vector<int32_t> adapters;      // pinned adapters
   std::shared_ptr<Event> done;        // recorded by plora_batch_end; the images are reusable once it has passed
+  hipEvent_t ev_img = nullptr;        // the image has arrived on the device (recorded on the pool's aux stream)
 };
 
 struct plora_pool {
@@ -86,6 +91,17 @@ struct plora_pool {
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
   // tunables
   int mfma_min_tokens = 8;
+  int fused = 0;      // 1: one launch per call over the mixed item list
+  int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
+  int overlap = 0;     // 1: matrix-core kernel on the aux stream, concurrently with the vector-ALU kernel
+  hipStream_t aux = nullptr;  // pool-owned side stream: batch images, overlapped kernels
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
+  // kernel timing (plora_profile)
+  bool profiling = false;
+  struct ProfRec { int cls; hipEvent_t e0, e1; };
+  std::vector<ProfRec> prof;
+  std::vector<hipEvent_t> prof_free;
   // statistics
   uint64_t resident_adapters = 0, resident_bytes = 0, loads = 0, evictions = 0, nomem = 0;
   uint64_t h2d_bytes = 0, h2d_copies = 0;
@@ -108,6 +124,46 @@ int poll_ready(plora_pool* p, Adapter& a) {
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Items of one adapter group that share data (x rows, v rows or a piece of B) and should meet in
+// one XCD's L2.
+struct Group {
+  std::vector<ItemRec> items;
+  double cost = 0.0;
+  bool heavy = false;
+};
+
+// Lays the items out in launch order.  Workgroup i of a launch runs on XCD i % 8, so with
+// xcd_aware the groups are spread over 8 queues (longest first, each to the least loaded queue)
+// and the queues are interleaved; queues that run out are padded with empty items.  Otherwise:
+// heavy groups first, then the rest, in group order.
+void arrange(std::vector<Group>& groups, bool xcd_aware, std::vector<ItemRec>& out) {
+  out.clear();
+  std::vector<const Group*> order;
+  for (const Group& g : groups) if (!g.items.empty()) order.push_back(&g);
+  std::stable_sort(order.begin(), order.end(), [&](const Group* a, const Group* b) {
+    if (a->heavy != b->heavy) return a->heavy;
+    return xcd_aware && a->cost > b->cost;
+  });
+  if (!xcd_aware) {
+    for (const Group* g : order) out.insert(out.end(), g->items.begin(), g->items.end());
+    return;
+  }
+  std::vector<ItemRec> q[kXcds];
+  double load[kXcds] = {0};
+  for (const Group* g : order) {
+    int best = 0;
+    for (int k = 1; k < kXcds; ++k) if (load[k] < load[best]) best = k;
+    q[best].insert(q[best].end(), g->items.begin(), g->items.end());
+    load[best] += g->cost;
+  }
+  size_t longest = 0;
+  for (int k = 0; k < kXcds; ++k) longest = std::max(longest, q[k].size());
+  ItemRec pad{};
+  pad.kind = -1;
+  for (size_t i = 0; i < longest; ++i)
+    for (int k = 0; k < kXcds; ++k) out.push_back(i < q[k].size() ? q[k][i] : pad);
+}
 
 }  // namespace
 
@@ -137,7 +193,7 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
     max_in = std::max(max_in, di);
     max_out = std::max(max_out, dn);
   }
-  if ((uint64_t)kMfmaRows * (uint64_t)max_in * elt / page_bytes + 2 > (uint64_t)kPtWindow) return PLORA_ERR_INVAL;
+  if ((uint64_t)std::max(kMfmaRows, kShrinkRows) * (uint64_t)max_in * elt / page_bytes + 2 > (uint64_t)kPtWindow) return PLORA_ERR_INVAL;
 
   plora_pool* p = new (std::nothrow) plora_pool;
   if (!p) return PLORA_ERR_NOMEM;
@@ -158,11 +214,17 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
     if (slab_or_null) p->slab = (uint8_t*)slab_or_null;
     else { e = hipMalloc((void**)&p->slab, (size_t)n_pages * page_bytes); p->own_slab = (e == hipSuccess); }
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_slots, sizeof(SlotRec) * slots.size());
+    if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMemcpy(p->d_slots, slots.data(), sizeof(SlotRec) * slots.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       g_last_hip = (int)e; (void)hipGetLastError();
       if (p->own_slab) (void)hipFree(p->slab);
       if (p->d_slots) (void)hipFree(p->d_slots);
+      if (p->aux) (void)hipStreamDestroy(p->aux);
+      if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+      if (p->ev_join) (void)hipEventDestroy(p->ev_join);
       delete p;
       return PLORA_ERR_HIP;
     }
@@ -182,10 +244,16 @@ int plora_pool_destroy(plora_pool* p) {
     }
     if (p->own_slab) (void)hipFree(p->slab);
     if (p->d_slots) (void)hipFree(p->d_slots);
+    if (p->aux) (void)hipStreamDestroy(p->aux);
+    if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
+    if (p->ev_join) (void)hipEventDestroy(p->ev_join);
+    for (auto& r : p->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
+    for (hipEvent_t e : p->prof_free) (void)hipEventDestroy(e);
   }
   for (plora_batch* b : p->batches) {
     if (b->h_img) { if (p->placement_only) ::operator delete(b->h_img); else (void)hipHostFree(b->h_img); }
     if (b->d_img) (void)hipFree(b->d_img);
+    if (b->ev_img) (void)hipEventDestroy(b->ev_img);
     delete b;
   }
   delete p;
@@ -332,6 +400,21 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->mfma_min_tokens = (int)value;
     return PLORA_OK;
   }
+  if (k == "fused" || k == "xcd_remap") {
+    if (value != 0 && value != 1) return PLORA_ERR_INVAL;
+    (k == "fused" ? p->fused : p->xcd_remap) = (int)value;
+    return PLORA_OK;
+  }
+  if (k == "overlap") {
+    if (value != 0 && value != 1) return PLORA_ERR_INVAL;
+    p->overlap = (int)value;
+    return PLORA_OK;
+  }
+  if (k == "slot_major") {
+    if (value < -1 || value > 1) return PLORA_ERR_INVAL;
+    p->slot_major = (int)value;
+    return PLORA_OK;
+  }
   return PLORA_ERR_INVAL;
 }
 
@@ -393,47 +476,90 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     if (i == -1) b->perm[none_cur++] = t; else b->perm[p->cursor[i]++] = t;
   }
 
-  // segments (+ one rank-0 pseudo segment for tokens without adapter) and work items
+  // work items, grouped per adapter (tokens without adapter form one rank-0 group: shrink clears their v rows)
   const bool mfma_ok = p->dtype != PLORA_F32 && p->mfma_min_tokens > 0;
-  std::vector<SegRec> segs;
-  std::vector<ItemRec> items[4];
+  std::vector<Group> grp[2][2];  // [op][kind]
   size_t n_pt_total = 0;
   for (int32_t u = 0; u < n_seg; ++u) {
     const Adapter& a = p->ad[touched[u]];
     const int32_t n = p->count[touched[u]];
-    SegRec sg{b->seg_start[u], n, a.rank, (int32_t)n_pt_total, a.scale, touched[u], (int32_t)a.pt.size(), 0};
-    segs.push_back(sg);
+    const int32_t start = b->seg_start[u];
+    const int32_t pt_off = (int32_t)n_pt_total;
     n_pt_total += a.pt.size();
+    const int16_t rank = (int16_t)a.rank;
     if (mfma_ok && n >= p->mfma_min_tokens) {
-      for (int32_t t0 = 0; t0 < n; t0 += kMfmaTok) {
-        const int32_t nt = std::min(kMfmaTok, n - t0);
-        for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows) items[1].push_back(ItemRec{u, t0, nt, j0});
-        items[3].push_back(ItemRec{u, t0, nt, 0});
+      Group gs, ge;
+      gs.heavy = ge.heavy = true;
+      for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
+        for (int32_t t0 = 0; t0 < n; t0 += kMfmaTokS) {
+          const int16_t nt = (int16_t)std::min(kMfmaTokS, n - t0);
+          gs.items.push_back(ItemRec{1, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+          gs.cost += std::min(kMfmaRows, a.rank - j0) + nt;
+        }
+      for (int32_t t0 = 0; t0 < n; t0 += kMfmaTokE) {
+        const int16_t nt = (int16_t)std::min(kMfmaTokE, n - t0);
+        ge.items.push_back(ItemRec{1, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+        ge.cost += a.rank + 2 * nt;
       }
+      grp[0][1].push_back(std::move(gs));
+      grp[1][1].push_back(std::move(ge));
     } else {
+      Group gs, ge;
+      std::vector<ItemRec> tg;  // one record per token group
       for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
-        const int32_t nt = std::min(kValuTok, n - t0);
-        for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows) items[0].push_back(ItemRec{u, t0, nt, j0});
-        items[2].push_back(ItemRec{u, t0, nt, 0});
+        const int16_t nt = (int16_t)std::min(kValuTok, n - t0);
+        ItemRec it{0, nt, rank, 0, a.scale, pt_off, {0, 0, 0, 0}};
+        for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
+        tg.push_back(it);
+        ge.items.push_back(it);
+        ge.cost += a.rank + 2 * nt;
       }
+      // shrink: token groups innermost, so that the re-read of a row block by the next token
+      // group follows closely and finds the rows in L2
+      for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
+        for (ItemRec it : tg) {
+          it.j0 = (int16_t)j0;
+          gs.items.push_back(it);
+          gs.cost += std::min(kShrinkRows, a.rank - j0) + it.ntok;
+        }
+      grp[0][0].push_back(std::move(gs));
+      grp[1][0].push_back(std::move(ge));
     }
   }
   if (n_none > 0) {
-    segs.push_back(SegRec{n_perm, n_none, 0, 0, 0.f, -1, 0, 0});
-    for (int32_t t0 = 0; t0 < n_none; t0 += kValuTok)
-      items[0].push_back(ItemRec{n_seg, t0, std::min(kValuTok, n_none - t0), 0});
+    Group gs;
+    for (int32_t t0 = 0; t0 < n_none; t0 += kValuTok) {
+      const int16_t nt = (int16_t)std::min(kValuTok, n_none - t0);
+      ItemRec it{0, nt, 0, 0, 0.f, 0, {0, 0, 0, 0}};
+      for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[n_perm + t0 + std::min<int>(i, nt - 1)];
+      gs.items.push_back(it);
+      gs.cost += 0.1;
+    }
+    grp[0][0].push_back(std::move(gs));
+  }
+  std::vector<ItemRec> lists[2][6];
+  for (int op = 0; op < 2; ++op) {
+    std::vector<Group> both;
+    both.reserve(grp[op][0].size() + grp[op][1].size());
+    for (const Group& g : grp[op][1]) both.push_back(g);
+    for (const Group& g : grp[op][0]) both.push_back(g);
+    for (int lay = 0; lay < 2; ++lay) {
+      arrange(grp[op][0], lay != 0, lists[op][0 + 3 * lay]);
+      arrange(grp[op][1], lay != 0, lists[op][1 + 3 * lay]);
+      arrange(both, lay != 0, lists[op][2 + 3 * lay]);
+    }
   }
   for (int32_t i : touched) p->count[i] = 0;
 
   // image layout
   size_t off = 0;
-  b->off_segs = off; off = align_up(off + segs.size() * sizeof(SegRec), 256);
   b->off_perm = off; off = align_up(off + (size_t)T * 4, 256);
   b->off_pt = off; off = align_up(off + (n_pt_total + 1) * 4, 256);
-  for (int k = 0; k < 4; ++k) {
-    b->off_items[k] = off; b->n_items[k] = (int32_t)items[k].size();
-    off = align_up(off + items[k].size() * sizeof(ItemRec), 256);
-  }
+  for (int op = 0; op < 2; ++op)
+    for (int k = 0; k < 6; ++k) {
+      b->off_items[op][k] = off; b->n_items[op][k] = (int32_t)lists[op][k].size();
+      off = align_up(off + lists[op][k].size() * sizeof(ItemRec), 256);
+    }
   const size_t need = std::max<size_t>(off, 256);
   if (need > b->cap) {
     const size_t cap = align_up(need + need / 2, 4096);
@@ -450,7 +576,6 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     }
     b->cap = cap;
   }
-  if (!segs.empty()) std::memcpy(b->h_img + b->off_segs, segs.data(), segs.size() * sizeof(SegRec));
   if (T) std::memcpy(b->h_img + b->off_perm, b->perm.data(), (size_t)T * 4);
   {
     int32_t* dst = (int32_t*)(b->h_img + b->off_pt);
@@ -461,12 +586,18 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     }
     *dst = 0;
   }
-  for (int k = 0; k < 4; ++k)
-    if (!items[k].empty()) std::memcpy(b->h_img + b->off_items[k], items[k].data(), items[k].size() * sizeof(ItemRec));
+  for (int op = 0; op < 2; ++op)
+    for (int k = 0; k < 6; ++k)
+      if (!lists[op][k].empty())
+        std::memcpy(b->h_img + b->off_items[op][k], lists[op][k].data(), lists[op][k].size() * sizeof(ItemRec));
   b->perm.resize(n_perm);
 
   if (!p->placement_only) {
-    HIP_TRY(hipMemcpyAsync(b->d_img, b->h_img, need, hipMemcpyHostToDevice, b->stream));
+    // the image travels on the pool's side stream, so it overlaps kernels already queued on `stream`
+    if (!b->ev_img) HIP_TRY(hipEventCreateWithFlags(&b->ev_img, hipEventDisableTiming));
+    HIP_TRY(hipMemcpyAsync(b->d_img, b->h_img, need, hipMemcpyHostToDevice, p->aux));
+    HIP_TRY(hipEventRecord(b->ev_img, p->aux));
+    HIP_TRY(hipStreamWaitEvent(b->stream, b->ev_img, 0));
     for (int32_t i : touched) {
       Adapter& a = p->ad[i];
       if (a.copy_pending && poll_ready(p, a) == 0) HIP_TRY(hipStreamWaitEvent(b->stream, a.ev_ready, 0));
@@ -501,13 +632,12 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     if (!in[q] || !outp[q] || ((uintptr_t)in[q] & 15) || ((uintptr_t)outp[q] & 15)) return PLORA_ERR_INVAL;
   LaunchArgs a;
   a.slab = p->slab;
-  a.segs = (const SegRec*)(b->d_img + b->off_segs);
   a.perm = (const int32_t*)(b->d_img + b->off_perm);
   a.pt = (const int32_t*)(b->d_img + b->off_pt);
   a.slots = p->d_slots;
   a.log2_page = p->log2P;
   a.v_stride = p->max_rank;
-  a.pad = 0;
+  a.elems_per_rank = p->C;
   const int vec = 16 / p->elt;
   for (int q0 = 0; q0 < n_slots; q0 += kMaxSlotsPerLaunch) {
     const int nq = std::min(kMaxSlotsPerLaunch, n_slots - q0);
@@ -519,17 +649,54 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
       max_out = std::max(max_out, (int)p->slots[slot0 + q0 + q].d_out);
     }
     a.slot0 = slot0 + q0;
-    for (int kind = 1; kind >= 0; --kind) {  // matrix-core items (the long ones) first
-      const int li = (is_shrink ? 0 : 2) + kind;
-      a.items = (const ItemRec*)(b->d_img + b->off_items[li]);
-      a.n_items = b->n_items[li];
-      hipError_t e;
-      if (is_shrink) e = launch_shrink(p->dtype, kind, a, ptrs, nq, (hipStream_t)s);
-      else {
-        const int cols = kind ? kMfmaCols : kWave * vec;
-        e = launch_expand(p->dtype, kind, a, ptrs, nq, (max_out + cols - 1) / cols, (hipStream_t)s);
+    const int op = is_shrink ? 0 : 1;
+    // slots fastest when that keeps every slot on one XCD and all XCDs equally loaded; else the
+    // items are the fastest dimension and (optionally) come dealt into XCD queues
+    a.slot_fastest = (p->slot_major == 1 || (p->slot_major < 0 && nq % kXcds == 0)) ? 1 : 0;
+    a.pad = 0;
+    const int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
+    const int chunks = (max_out + kWave * vec - 1) / (kWave * vec);
+    // launches: fused = the mixed list; else matrix-core items (the long ones) first, then the rest
+    struct L { int kind, cls; };
+    L ls[2];
+    int nl = 0;
+    if (p->fused) ls[nl++] = L{2, 4 + op};
+    else {
+      ls[nl++] = L{1, op * 2 + 1};
+      ls[nl++] = L{0, op * 2};
+    }
+    const bool overlap = p->overlap && !p->fused && !p->profiling && b->n_items[op][1 + 3 * layout] > 0 &&
+                         b->n_items[op][0 + 3 * layout] > 0;
+    for (int li = 0; li < nl; ++li) {
+      a.items = (const ItemRec*)(b->d_img + b->off_items[op][ls[li].kind + 3 * layout]);
+      a.n_items = b->n_items[op][ls[li].kind + 3 * layout];
+      if (a.n_items == 0) continue;
+      if (overlap && ls[li].kind == 1) {  // matrix-core items on the side stream, joined below
+        HIP_TRY(hipEventRecord(p->ev_fork, (hipStream_t)s));
+        HIP_TRY(hipStreamWaitEvent(p->aux, p->ev_fork, 0));
+        hipError_t e = is_shrink ? launch_shrink(p->dtype, 1, a, ptrs, nq, p->aux)
+                                 : launch_expand(p->dtype, 1, a, ptrs, nq, chunks, p->aux);
+        HIP_TRY(e);
+        HIP_TRY(hipEventRecord(p->ev_join, p->aux));
+        continue;
       }
+      plora_pool::ProfRec rec{ls[li].cls, nullptr, nullptr};
+      if (p->profiling) {
+        for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
+          if (!p->prof_free.empty()) { *ev = p->prof_free.back(); p->prof_free.pop_back(); }
+          else HIP_TRY(hipEventCreate(ev));
+        }
+        HIP_TRY(hipEventRecord(rec.e0, (hipStream_t)s));
+      }
+      hipError_t e;
+      if (is_shrink) e = launch_shrink(p->dtype, ls[li].kind, a, ptrs, nq, (hipStream_t)s);
+      else e = launch_expand(p->dtype, ls[li].kind, a, ptrs, nq, chunks, (hipStream_t)s);
       HIP_TRY(e);
+      if (p->profiling) {
+        HIP_TRY(hipEventRecord(rec.e1, (hipStream_t)s));
+        p->prof.push_back(rec);
+      }
+      if (overlap && ls[li].kind == 0) HIP_TRY(hipStreamWaitEvent((hipStream_t)s, p->ev_join, 0));
     }
   }
   return PLORA_OK;
@@ -543,6 +710,28 @@ int plora_shrink(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_s
 int plora_expand(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const float* const* v, void* const* y,
                  plora_stream s) {
   return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);
+}
+
+int plora_profile(plora_pool* p, int enable) {
+  if (!p || p->placement_only) return PLORA_ERR_INVAL;
+  p->profiling = enable != 0;
+  return PLORA_OK;
+}
+
+int plora_profile_read(plora_pool* p, double* ms, uint64_t* launches) {
+  if (!p || !ms || !launches || p->placement_only) return PLORA_ERR_INVAL;
+  for (int k = 0; k < 6; ++k) { ms[k] = 0.0; launches[k] = 0; }
+  for (auto& r : p->prof) {
+    HIP_TRY(hipEventSynchronize(r.e1));
+    float t = 0.f;
+    HIP_TRY(hipEventElapsedTime(&t, r.e0, r.e1));
+    ms[r.cls] += t;
+    launches[r.cls]++;
+    p->prof_free.push_back(r.e0);
+    p->prof_free.push_back(r.e1);
+  }
+  p->prof.clear();
+  return PLORA_OK;
 }
 
 int plora_batch_end(plora_pool* p, plora_batch* b) {
