@@ -80,7 +80,7 @@ class GpuWorkload:
         lay, cfg = self.lay, self.cfg
         self.n_ad = len(self.ranks)
         self.max_rank = cfg["max_rank"]
-        self.mfma_min = 8  # the library's default for "mfma_min_tokens"
+        self.mfma_min = 5  # the library's default for "mfma_min_tokens"
         t0 = time.perf_counter()
         self.pinned = [torch.empty(lay.adapter_elems(int(r)), dtype=torch.int16 if lay.elt == 2 else torch.float32,
                                    pin_memory=True) for r in self.ranks]

@@ -90,12 +90,10 @@ struct plora_pool {
   int open_batches = 0;
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
   // tunables
-  int mfma_min_tokens = 8;
-  int fused = 0;      // 1: one launch per call over the mixed item list
+  int mfma_min_tokens = 5;
+  int fused = 1;      // 1: one launch per call over the mixed item list
   int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
-  int overlap = 0;     // 1: matrix-core kernel on the aux stream, concurrently with the vector-ALU kernel
-  hipStream_t aux = nullptr;  // pool-owned side stream: batch images, overlapped kernels
-  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
   // kernel timing (plora_profile)
   bool profiling = false;
@@ -215,16 +213,12 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
     else { e = hipMalloc((void**)&p->slab, (size_t)n_pages * page_bytes); p->own_slab = (e == hipSuccess); }
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_slots, sizeof(SlotRec) * slots.size());
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_fork, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&p->ev_join, hipEventDisableTiming);
     if (e == hipSuccess) e = hipMemcpy(p->d_slots, slots.data(), sizeof(SlotRec) * slots.size(), hipMemcpyHostToDevice);
     if (e != hipSuccess) {
       g_last_hip = (int)e; (void)hipGetLastError();
       if (p->own_slab) (void)hipFree(p->slab);
       if (p->d_slots) (void)hipFree(p->d_slots);
       if (p->aux) (void)hipStreamDestroy(p->aux);
-      if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
-      if (p->ev_join) (void)hipEventDestroy(p->ev_join);
       delete p;
       return PLORA_ERR_HIP;
     }
@@ -245,8 +239,6 @@ int plora_pool_destroy(plora_pool* p) {
     if (p->own_slab) (void)hipFree(p->slab);
     if (p->d_slots) (void)hipFree(p->d_slots);
     if (p->aux) (void)hipStreamDestroy(p->aux);
-    if (p->ev_fork) (void)hipEventDestroy(p->ev_fork);
-    if (p->ev_join) (void)hipEventDestroy(p->ev_join);
     for (auto& r : p->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
     for (hipEvent_t e : p->prof_free) (void)hipEventDestroy(e);
   }
@@ -403,11 +395,6 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
   if (k == "fused" || k == "xcd_remap") {
     if (value != 0 && value != 1) return PLORA_ERR_INVAL;
     (k == "fused" ? p->fused : p->xcd_remap) = (int)value;
-    return PLORA_OK;
-  }
-  if (k == "overlap") {
-    if (value != 0 && value != 1) return PLORA_ERR_INVAL;
-    p->overlap = (int)value;
     return PLORA_OK;
   }
   if (k == "slot_major") {
@@ -665,21 +652,10 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
       ls[nl++] = L{1, op * 2 + 1};
       ls[nl++] = L{0, op * 2};
     }
-    const bool overlap = p->overlap && !p->fused && !p->profiling && b->n_items[op][1 + 3 * layout] > 0 &&
-                         b->n_items[op][0 + 3 * layout] > 0;
     for (int li = 0; li < nl; ++li) {
       a.items = (const ItemRec*)(b->d_img + b->off_items[op][ls[li].kind + 3 * layout]);
       a.n_items = b->n_items[op][ls[li].kind + 3 * layout];
       if (a.n_items == 0) continue;
-      if (overlap && ls[li].kind == 1) {  // matrix-core items on the side stream, joined below
-        HIP_TRY(hipEventRecord(p->ev_fork, (hipStream_t)s));
-        HIP_TRY(hipStreamWaitEvent(p->aux, p->ev_fork, 0));
-        hipError_t e = is_shrink ? launch_shrink(p->dtype, 1, a, ptrs, nq, p->aux)
-                                 : launch_expand(p->dtype, 1, a, ptrs, nq, chunks, p->aux);
-        HIP_TRY(e);
-        HIP_TRY(hipEventRecord(p->ev_join, p->aux));
-        continue;
-      }
       plora_pool::ProfRec rec{ls[li].cls, nullptr, nullptr};
       if (p->profiling) {
         for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
@@ -696,7 +672,6 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
         HIP_TRY(hipEventRecord(rec.e1, (hipStream_t)s));
         p->prof.push_back(rec);
       }
-      if (overlap && ls[li].kind == 0) HIP_TRY(hipStreamWaitEvent((hipStream_t)s, p->ev_join, 0));
     }
   }
   return PLORA_OK;
