@@ -152,9 +152,9 @@ int plora_batch_end(plora_pool* pool, plora_batch* batch);
 int plora_pool_stats(plora_pool* pool, plora_stats* out);
 
 /* Tunables.  key: "mfma_min_tokens" (adapter groups with at least this many tokens use the
- * matrix-core path; 0 disables it; takes effect for batches begun afterwards), "fused" (1 = one
- * kernel launch per call over the mixed work list, 0 = matrix-core items and vector-ALU items in
- * two launches), "xcd_remap" (1 = neighbouring work items share an XCD).  INVAL for an unknown key
+ * matrix-core path; 0 disables it; takes effect for batches begun afterwards), "fused" (expand
+ * only: 1 = one kernel launch per call over the mixed work list, 0 = matrix-core items and
+ * vector-ALU items in two launches), "xcd_remap" (1 = neighbouring work items share an XCD).  INVAL for an unknown key
  * or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 

@@ -25,12 +25,12 @@ constexpr int kExpandU = PLORA_EXPAND_U;        // rows of B in flight per vecto
 #ifndef PLORA_MFMA_TOK_E
 #define PLORA_MFMA_TOK_E 16
 #endif
-constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item (16 or 32)
+constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item
 constexpr int kMfmaTokE = PLORA_MFMA_TOK_E;     // tokens per matrix-core expand item (16 or 32)
 #ifndef PLORA_MFMA_ROWS
-#define PLORA_MFMA_ROWS 64
+#define PLORA_MFMA_ROWS 32
 #endif
-constexpr int kMfmaRows = PLORA_MFMA_ROWS;      // rows of A per matrix-core shrink item (16, 32 or 64)
+constexpr int kMfmaRows = PLORA_MFMA_ROWS;      // rows of A per matrix-core shrink item
 constexpr int kMfmaCols = 128;          // columns of B per matrix-core expand pass
 constexpr int kPtWindow = 1024;         // page-table entries a shrink item may stage in LDS
 constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for

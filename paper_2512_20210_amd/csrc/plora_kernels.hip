@@ -8,10 +8,11 @@
 //   shrink, vector-ALU item : up to 8 rows of A x up to 4 tokens.  Lanes stride along d_in with
 //                             16-byte loads, accumulate in fp32 and finish with a wavefront
 //                             reduction.
-//   shrink, matrix-core item: 32 rows of A x up to 64 tokens, v_mfma_f32_16x16x32 (bf16 / f16).
+//   shrink, matrix-core item: 32 rows of A x up to 32 tokens, v_mfma_f32_16x16x32 (bf16 / f16), by a
+//                             workgroup of 4 wavefronts that split d_in; operands staged in LDS.
 //   expand, vector-ALU item : all rows of B x 64 lanes x 16 bytes of columns x up to 4 tokens;
 //                             no reduction, read-modify-write of y.
-//   expand, matrix-core item: all rows of B x 512 columns (4 passes of 128) x up to 32 tokens; v is
+//   expand, matrix-core item: all rows of B x 512 columns (4 passes of 128) x up to 16 tokens; v is
 //                             split into a high and a low half so that fp32 v loses nothing that
 //                             matters.
 //
@@ -346,138 +347,139 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
     return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// One iteration of the matrix-core shrink: KU runs of 64 k-values for NTL row tiles and MT token
-// tiles.  Within a run of 64 k-values (128 bytes of a row) lane group g takes k = 8 g .. 8 g + 7 of
-// the first half and of the second half, so every load instruction reads 64 contiguous bytes of
-// each of its 16 rows; the order of the contraction index is free as long as both operands agree.
-template <int DT, int MT, int NTL, int KU, bool TAIL>
-__device__ __forceinline__ void shrink_mfma_chunk(const LaunchArgs& a, const uint8_t* const* xrow, const uint64_t* wrow,
-                                                  const int32_t* lds_pt, uint32_t win0, int d_in, int k0,
-                                                  f32x4 (*acc)[NTL]) {
-  constexpr int EB = 2;
-  const int lp = a.log2_page;
-  const uint64_t pmask = ((uint64_t)1 << lp) - 1;
-  const int g8 = ((int)threadIdx.x >> 4) * 8;
-  uint4 xq[KU][2][MT], wq[KU][2][NTL];
-  bool ok[KU][2];
-#pragma unroll
-  for (int u = 0; u < KU; ++u)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int k = k0 + u * 64 + h * 32 + g8;
-      ok[u][h] = !TAIL || k < d_in;
-      const int kk = ok[u][h] ? k : 0;
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) xq[u][h][mt] = ld16(xrow[mt] + (uint64_t)kk * EB);
-#pragma unroll
-      for (int nt = 0; nt < NTL; ++nt) {
-        const uint64_t vo = wrow[nt] + (uint64_t)kk * EB;
-        const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(vo >> lp) - win0];
-        wq[u][h][nt] = ldw16(a.slab + (pg << lp) + (vo & pmask));
-      }
-    }
-#pragma unroll
-  for (int u = 0; u < KU; ++u)
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      if (TAIL) {
-#pragma unroll
-        for (int nt = 0; nt < NTL; ++nt)
-          if (!ok[u][h]) wq[u][h][nt] = make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-        for (int nt = 0; nt < NTL; ++nt) acc[mt][nt] = mfma16<DT>(xq[u][h][mt], wq[u][h][nt], acc[mt][nt]);
-    }
-}
+// shrink, matrix-core item: D[token, row] += X[token, k] * A[row, k] for 32 tokens x 32 rows, by a
+// workgroup of 4 wavefronts that split the contraction (each takes every 4th run of 64 k-values'
+// worth of work as one contiguous quarter of d_in) and add their partial sums in a fixed order at
+// the end.  MFMA operands want "one row per lane", which as a global load would touch 16 cache
+// lines per instruction; instead each wavefront fetches its 32 x 128-byte tiles of A and x with
+// row-contiguous 16-byte loads (8 lanes per row), parks them in its own LDS region and reads the
+// operands back in MFMA layout.  The next tiles are requested before the current ones are
+// multiplied.
+constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16 pad per LDS row
+static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
-// shrink: D[token, row] += X[token, k] * A[row, k] for NTL tiles of 16 rows and MT tiles of 16
-// tokens.
-template <int DT, int MT, int NTL>
-__device__ __forceinline__ void shrink_mfma_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
-                                                 const uint8_t* __restrict__ x, float* __restrict__ v,
-                                                 int32_t* lds_pt) {
+template <int DT>
+__global__ __launch_bounds__(256) void k_shrink_mfma4(const LaunchArgs a, const SlotPtrs p) {
   constexpr int EB = 2;
-  constexpr int KU = NTL == 4 ? 1 : 2;  // 8 to 16 loads of 16 bytes per lane in flight per iteration
-  const int lane = threadIdx.x;
-  const int g = lane >> 4, c = lane & 15;
-  const int r = it.rank;
-  const int d_in = sl.d_in;
-  const int vs = a.v_stride;
-  const int lp = a.log2_page;
+  __shared__ __align__(16) uint8_t tile[4][2][kSmRows * kSmPitch];  // [wavefront][A | x]
+  __shared__ int32_t lds_pt[kPtWindow];
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
+  if (it.kind < 0) return;
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  const SlotRec sl = a.slots[a.slot0 + q];
+  const uint8_t* __restrict__ x = (const uint8_t*)p.a[q];
+  float* __restrict__ v = (float*)p.b[q];
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane >> 4, c = lane & 15;   // MFMA coordinates
+  const int lr = lane >> 3, lp8 = lane & 7; // staging coordinates: row within a group of 8, 16-byte piece
+  const int r = it.rank, d_in = sl.d_in, vs = a.v_stride, lp = a.log2_page;
+  const uint64_t pmask = ((uint64_t)1 << lp) - 1;
   const int32_t* perm = a.perm + it.tok[0];
 
-  const int nrows = imin(kMfmaRows, r - it.j0);
+  const int nrows = imin(kSmRows, r - it.j0);
   const uint64_t rowb = (uint64_t)d_in * EB;
   const uint64_t base = (uint64_t)r * EB * (uint64_t)sl.cum + (uint64_t)it.j0 * rowb;
   const uint32_t win0 = (uint32_t)(base >> lp);
   const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
   const int32_t* ptg = a.pt + it.pt_off + win0;
-  for (uint32_t i = lane; i < win_n; i += kWave) lds_pt[i] = ptg[i];
+  for (uint32_t i = tid; i < win_n; i += 256) lds_pt[i] = ptg[i];
 
-  uint64_t wrow[NTL];
+  uint64_t wrow[4];          // virtual offsets of the 4 rows of A this lane stages
+  const uint8_t* xrow[4];    // and of its 4 token rows
 #pragma unroll
-  for (int nt = 0; nt < NTL; ++nt) wrow[nt] = base + (uint64_t)imin(nt * 16 + c, nrows - 1) * rowb;
-  const uint8_t* xrow[MT];
-  int trow[MT];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt) {
-    trow[mt] = perm[imin(mt * 16 + c, it.ntok - 1)];
-    xrow[mt] = x + (uint64_t)trow[mt] * d_in * EB;
+  for (int i = 0; i < 4; ++i) {
+    wrow[i] = base + (uint64_t)imin(lr + 8 * i, nrows - 1) * rowb;
+    xrow[i] = x + (uint64_t)perm[imin(lr + 8 * i, it.ntok - 1)] * rowb;
   }
   if (it.j0 == 0) {  // clear v[t, r .. v_stride) for the item's tokens
-    for (int i = 0; i < it.ntok; ++i) {
+    for (int i = wave; i < it.ntok; i += 4) {
       const int64_t t = perm[i];
       for (int j = r + lane; j < vs; j += kWave) v[t * vs + j] = 0.f;
     }
   }
   __syncthreads();
 
-  f32x4 acc[MT][NTL];
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int nt = 0; nt < NTL; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+  // this wavefront's quarter of the contraction, in runs of 64 k-values
+  const int nrun = (d_in + 63) >> 6;
+  const int per = (nrun + 3) >> 2;
+  const int c0 = wave * per, c1 = imin(nrun, c0 + per);
 
-  constexpr int CH = 64 * KU;
-  const int full = d_in / CH * CH;
-  for (int k0 = 0; k0 < full; k0 += CH)
-    shrink_mfma_chunk<DT, MT, NTL, KU, false>(a, xrow, wrow, lds_pt, win0, d_in, k0, acc);
-  for (int k0 = full; k0 < d_in; k0 += 64)
-    shrink_mfma_chunk<DT, MT, NTL, 1, true>(a, xrow, wrow, lds_pt, win0, d_in, k0, acc);
-
-  // result: lane holds weight row it.j0 + 16 nt + c for tokens 4 g .. 4 g + 3 of every token tile
+  f32x4 acc[2][2];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  uint8_t* tw = tile[wave][0];
+  uint8_t* tx = tile[wave][1];
+  uint4 wq[4], xq[4];
+  auto fetch = [&](int run) {
+    const int k = run * 64 + lp8 * 8;
+    const bool ok = k < d_in;
+    const uint64_t kb = (uint64_t)(ok ? k : 0) * EB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      const int ti = mt * 16 + g * 4 + i;
-      const int64_t t = __shfl(trow[mt], g * 4 + i, 64);
-      if (ti < it.ntok) {
-#pragma unroll
-        for (int nt = 0; nt < NTL; ++nt)
-          if (nt * 16 + c < nrows) v[t * vs + it.j0 + nt * 16 + c] = acc[mt][nt][i];
-      }
+      const uint64_t vo = wrow[i] + kb;
+      const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(vo >> lp) - win0];
+      wq[i] = ldw16(a.slab + (pg << lp) + (vo & pmask));
+      xq[i] = ld16(xrow[i] + kb);
     }
-}
+    if (!ok) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { wq[i] = make_uint4(0, 0, 0, 0); xq[i] = make_uint4(0, 0, 0, 0); }
+    }
+  };
+  if (c0 < c1) fetch(c0);
+  for (int run = c0; run < c1; ++run) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      *reinterpret_cast<uint4*>(tw + (lr + 8 * i) * kSmPitch + lp8 * 16) = wq[i];
+      *reinterpret_cast<uint4*>(tx + (lr + 8 * i) * kSmPitch + lp8 * 16) = xq[i];
+    }
+    __syncthreads();
+    if (run + 1 < c1) fetch(run + 1);  // in flight while this run is multiplied
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      uint4 wo[2], xo[2];
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        wo[t] = *reinterpret_cast<const uint4*>(tw + (16 * t + c) * kSmPitch + h * 64 + g * 16);
+        xo[t] = *reinterpret_cast<const uint4*>(tx + (16 * t + c) * kSmPitch + h * 64 + g * 16);
+      }
+#pragma unroll
+      for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = mfma16<DT>(xo[mt], wo[nt], acc[mt][nt]);
+    }
+    __syncthreads();
+  }
+  // every wavefront passes 2 * per barriers: those whose quarter is shorter (or empty) catch up here
+  const int mine = c1 > c0 ? c1 - c0 : 0;
+  for (int run = mine; run < per; ++run) { __syncthreads(); __syncthreads(); }
 
-template <int DT, int MT>
-__device__ __forceinline__ void shrink_mfma_rows(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
-                                                 const uint8_t* x, float* v, int32_t* lds_pt) {
-  const int nrows = imin(kMfmaRows, it.rank - it.j0);
-  if (kMfmaRows <= 16 || nrows <= 16) shrink_mfma_body<DT, MT, 1>(a, it, sl, x, v, lds_pt);
-  else if (kMfmaRows <= 32 || nrows <= 32) shrink_mfma_body<DT, MT, 2>(a, it, sl, x, v, lds_pt);
-  else shrink_mfma_body<DT, MT, 4>(a, it, sl, x, v, lds_pt);
-}
-
-template <int DT>
-__device__ __forceinline__ void shrink_mfma_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
-                                                 const uint8_t* x, float* v, int32_t* lds_pt) {
-  if constexpr (DT == 2) return;
-  else {
-    if (kMfmaTokS <= 16 || it.ntok <= 16) shrink_mfma_rows<DT, 1>(a, it, sl, x, v, lds_pt);
-    else shrink_mfma_rows<DT, 2>(a, it, sl, x, v, lds_pt);
+  // add the 4 partial sums in wavefront order: thread (w, lane) finishes tile (mt, nt) = (w >> 1, w & 1)
+  float* red = reinterpret_cast<float*>(&tile[0][0][0]);  // 4 x 64 x 16 floats = 16 KiB, tiles are free now
+#pragma unroll
+  for (int mt = 0; mt < 2; ++mt)
+#pragma unroll
+    for (int nt = 0; nt < 2; ++nt)
+      *reinterpret_cast<f32x4*>(red + ((wave * 64 + lane) * 4 + mt * 2 + nt) * 4) = acc[mt][nt];
+  __syncthreads();
+  const int mt = wave >> 1, nt = wave & 1;
+  f32x4 sum = *reinterpret_cast<const f32x4*>(red + ((0 * 64 + lane) * 4 + wave) * 4);
+#pragma unroll
+  for (int w = 1; w < 4; ++w) {
+    const f32x4 t = *reinterpret_cast<const f32x4*>(red + ((w * 64 + lane) * 4 + wave) * 4);
+    sum[0] += t[0]; sum[1] += t[1]; sum[2] += t[2]; sum[3] += t[3];
+  }
+  // lane (g, c) of a result tile: row 16 nt + c of A, tokens 16 mt + 4 g .. + 3
+  if (16 * nt + c < nrows) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int ti = 16 * mt + 4 * g + i;
+      if (ti < it.ntok) v[(int64_t)perm[ti] * vs + it.j0 + 16 * nt + c] = sum[i];
+    }
   }
 }
 
@@ -640,24 +642,17 @@ __device__ __forceinline__ void expand_mfma_item(const LaunchArgs& a, const Item
   }
 }
 
-// KIND 0: vector-ALU items only, 1: matrix-core items only, 2: mixed list.
-template <int DT, int KIND>
-__global__ __launch_bounds__(kWave) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
+template <int DT>
+__global__ __launch_bounds__(kWave) void k_shrink_valu(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int32_t lds_pt[kPtWindow];
   const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
   if (it.kind < 0) return;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[a.slot0 + q];
-  const uint8_t* x = (const uint8_t*)p.a[q];
-  float* v = (float*)p.b[q];
-  if constexpr (KIND == 0) shrink_valu_item<DT>(a, it, sl, x, v, lds_pt);
-  else if constexpr (KIND == 1) shrink_mfma_item<DT>(a, it, sl, x, v, lds_pt);
-  else {
-    if (it.kind) shrink_mfma_item<DT>(a, it, sl, x, v, lds_pt);
-    else shrink_valu_item<DT>(a, it, sl, x, v, lds_pt);
-  }
+  shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
 }
 
+// KIND 0: vector-ALU items only, 1: matrix-core items only, 2: mixed list.
 template <int DT, int KIND>
 __global__ __launch_bounds__(kWave) void k_expand(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int2 lds_pg[kMaxRank];
@@ -676,13 +671,6 @@ __global__ __launch_bounds__(kWave) void k_expand(const LaunchArgs a, const Slot
 }
 
 template <int KIND>
-void launch_shrink_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, const SlotPtrs& p) {
-  const dim3 block(kWave);
-  if (dtype == 0) hipLaunchKernelGGL((k_shrink<0, KIND>), grid, block, 0, st, a, p);
-  else if (dtype == 1) hipLaunchKernelGGL((k_shrink<1, KIND>), grid, block, 0, st, a, p);
-  else hipLaunchKernelGGL((k_shrink<2, KIND>), grid, block, 0, st, a, p);
-}
-template <int KIND>
 void launch_expand_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, const SlotPtrs& p) {
   const dim3 block(kWave);
   if (dtype == 0) hipLaunchKernelGGL((k_expand<0, KIND>), grid, block, 0, st, a, p);
@@ -694,16 +682,21 @@ void launch_expand_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, 
 
 hipError_t launch_shrink(int dtype, int kind, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, hipStream_t st) {
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
-  if (dtype == 2 && kind == 1) return hipErrorInvalidValue;
+  if (kind > 1 || (dtype == 2 && kind == 1)) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int step = a0.slot_fastest ? 65535 : a0.n_items;  // grid.z is limited to 65535
   for (int first = 0; first < a0.n_items; first += step) {
     a.items = a0.items + first;
     a.n_items = a0.n_items - first < step ? a0.n_items - first : step;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, a.n_items) : dim3(a.n_items, 1, n_slots);
-    if (kind == 0) launch_shrink_k<0>(dtype, grid, st, a, p);
-    else if (kind == 1) launch_shrink_k<1>(dtype, grid, st, a, p);
-    else launch_shrink_k<2>(dtype, grid, st, a, p);
+    if (kind == 1) {
+      if (dtype == 0) hipLaunchKernelGGL(k_shrink_mfma4<0>, grid, dim3(256), 0, st, a, p);
+      else hipLaunchKernelGGL(k_shrink_mfma4<1>, grid, dim3(256), 0, st, a, p);
+    } else {
+      if (dtype == 0) hipLaunchKernelGGL(k_shrink_valu<0>, grid, dim3(kWave), 0, st, a, p);
+      else if (dtype == 1) hipLaunchKernelGGL(k_shrink_valu<1>, grid, dim3(kWave), 0, st, a, p);
+      else hipLaunchKernelGGL(k_shrink_valu<2>, grid, dim3(kWave), 0, st, a, p);
+    }
   }
   return hipGetLastError();
 }

@@ -647,7 +647,7 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     struct L { int kind, cls; };
     L ls[2];
     int nl = 0;
-    if (p->fused) ls[nl++] = L{2, 4 + op};
+    if (p->fused && !is_shrink) ls[nl++] = L{2, 4 + op};  // shrink kernels differ in workgroup size: never fused
     else {
       ls[nl++] = L{1, op * 2 + 1};
       ls[nl++] = L{0, op * 2};
