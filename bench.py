@@ -187,12 +187,122 @@ def cpu_baseline(w, t2a, budget_s=15.0):
                 tokens_per_s=len(t2a) / (per_slot * lay.n_slots), seconds=t_total)
 
 
+class _PoolForManager:
+    """Adapts PagedLoraPool to the manager's load/evict interface and samples utilisation."""
+
+    def __init__(self, pool, lay):
+        self.pool, self.lay = pool, lay
+        self.filled = False
+        self.page_util, self.byte_util = [], []
+
+    def load(self, aid, rank, scale, blob, stream=None):
+        try:
+            pt = self.pool.load(aid, rank, scale, blob, stream)
+        except Exception as e:
+            if getattr(e, "code", None) == -2:
+                self.filled = True
+            raise
+        if self.filled:  # sampled after every load once the pool has first run out of pages
+            st = self.pool.stats()
+            self.page_util.append(st["used_pages"] / st["n_pages"])
+            self.byte_util.append(st["resident_bytes"] / (st["n_pages"] * st["page_bytes"]))
+        return pt
+
+    def evict(self, aid):
+        self.pool.evict(aid)
+
+
+def churn_setup(name="cfg3", blobs_per_rank=8):
+    """Pool, shared pinned blobs (blobs_per_rank distinct weight sets per rank) and the request trace."""
+    import torch
+    import paper_2512_20210_amd as P
+    from workload import churn_trace, make_adapter
+    cfg, lay, ranks, scales, page_bytes, n_pages = workload_params(name)
+    pop = cfg["population"]
+    rng = np.random.default_rng(cfg["seed"] + 1000)
+    pinned = {}
+    for r in sorted(set(int(x) for x in ranks)):
+        for k in range(blobs_per_rank):
+            t = torch.empty(lay.adapter_elems(r), dtype=torch.int16, pin_memory=True)
+            make_adapter(rng, lay, r, out=t.numpy().view(np.uint16))
+            pinned[(r, k)] = t
+    pool = P.PagedLoraPool(page_bytes, n_pages, lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
+    trace = churn_trace(np.random.default_rng(cfg["seed"] + 1), cfg["n_events"], pop, cfg["zipf"], cfg["window"],
+                        cfg["burst_prob"], cfg["burst_mult"])
+    return cfg, lay, ranks, scales, pool, pinned, trace
+
+
+def run_churn(args):
+    """cfg3: load/evict churn interleaved with decode batches; utilisation, H2D and kernel rates."""
+    import torch
+    from paper_2512_20210_amd.manager import ResidencyManager
+    from workload import zipf_probs
+    cfg, lay, ranks, scales, pool, pinned, trace = churn_setup("cfg3")
+    pop, T = cfg["population"], cfg["tokens"]
+    k_blobs = len(pinned) // len(set(int(x) for x in ranks))
+    copy_stream = torch.cuda.Stream()
+    stream = torch.cuda.current_stream().cuda_stream
+    pm = _PoolForManager(pool, lay)
+    popularity = zipf_probs(pop, cfg["zipf"])
+    mgr = ResidencyManager(pm, ranks, scales, lambda i: pinned[(int(ranks[i]), i % k_blobs)],
+                           p_hat=popularity / popularity.max(), copy_stream=copy_stream.cuda_stream)
+    rng = np.random.default_rng(cfg["seed"] + 7)
+    dt = torch.int16
+    x = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_in]
+    y = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_out]
+    v = [torch.empty((T, cfg["max_rank"]), dtype=torch.float32, device="cuda") for _ in lay.d_in]
+    slots = list(range(lay.n_slots))
+    pool.profile(True)
+    events = batches = 0
+    kbytes = 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for win in trace:
+        for aid in win:
+            mgr.request(int(aid))
+            events += 1
+            if events >= cfg["n_events"]:
+                break
+        res = np.fromiter(mgr.resident(), dtype=np.int32)
+        res.sort()
+        p = popularity[res] / popularity[res].sum()
+        t2a = res[rng.choice(len(res), size=T, p=p)].astype(np.int32)
+        b = pool.batch_begin(t2a, stream)
+        pool.shrink(b, 0, x, v, stream)
+        pool.expand(b, 0, v, y, stream)
+        pool.batch_end(b)
+        kbytes += algorithmic_bytes(lay, ranks, t2a, slots)["total"]
+        batches += 1
+        if events >= cfg["n_events"]:
+            break
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    kms, kn = pool.profile_read()
+    st = pool.stats()
+    out = {
+        "metric": "pool utilisation under churn + H2D prefetch GB/s + decode kernel GB/s", "workload": "cfg3",
+        "events": events, "decode_batches": batches, "wall_s": round(wall, 3),
+        "page_util_avg": round(float(np.mean(pm.page_util)), 4), "page_util_min": round(float(np.min(pm.page_util)), 4),
+        "byte_util_avg": round(float(np.mean(pm.byte_util)), 4), "byte_util_min": round(float(np.min(pm.byte_util)), 4),
+        "hit_rate": round(mgr.hits / max(1, mgr.hits + mgr.misses), 4), "loads": st["loads"], "evictions": st["evictions"],
+        "skipped_busy_victims": mgr.skipped_busy, "failed_loads": mgr.failed,
+        "h2d_gb": round(st["h2d_bytes"] / 1e9, 2), "h2d_copies": st["h2d_copies"],
+        "h2d_gbs_copy_time": round(st["h2d_bytes"] / 1e6 / max(st["h2d_ms"], 1e-9), 2),
+        "h2d_gbs_wall": round(st["h2d_bytes"] / 1e9 / wall, 2),
+        "decode_kernel_gbs": round(kbytes / 1e6 / max(sum(kms), 1e-9), 1),
+        "decode_kernel_ms_per_batch": round(sum(kms) / max(batches, 1), 4),
+        "resident_adapters_end": st["resident_adapters"],
+    }
+    pool.close()
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
     ap.add_argument("--mfma-min-tokens", type=int, default=-1)
     ap.add_argument("--fused", type=int, default=-1, help="1 = one launch per call over the mixed item list")
@@ -210,6 +320,9 @@ def main():
         print("bench.py: needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    if args.workload == "cfg3":
+        run_churn(args)
+        return
 
     w = GpuWorkload(args.workload, verbose=args.verbose)
     cfg, lay = w.cfg, w.lay

@@ -1,0 +1,87 @@
+"""Churn: load/evict decisions of the residency manager driven on the GPU pool, replayed on the oracle.
+
+The eviction policy is outside both implementations (parity unpinned: the paper fixes neither the
+weights nor the normalisation of its score), so the check is that the same sequence of loads and
+evictions yields bit-identical page tables and counters on both sides, >= 87 % pool utilisation
+once the pool has filled, and a decode batch over the survivors that matches the oracle.
+"""
+import numpy as np
+import pytest
+
+from workload import from_elt, make_act, zipf_probs
+from helpers import TOL_V, TOL_Y, raw_to_torch, rel_err, torch_to_raw
+
+pytestmark = pytest.mark.gpu
+
+
+def test_churn_tables_utilisation_and_decode(oracle_mod):
+    import torch
+    import bench
+    from paper_2512_20210_amd.manager import ResidencyManager
+    cfg, lay, ranks, scales, pool, pinned, trace = bench.churn_setup("cfg3", blobs_per_rank=3)
+    pop = cfg["population"]
+    kb = 3
+    blob = lambda i: pinned[(int(ranks[i]), i % kb)]
+    copy_stream = torch.cuda.Stream()
+    pm = bench._PoolForManager(pool, lay)
+    mgr = ResidencyManager(pm, ranks, scales, blob, copy_stream=copy_stream.cuda_stream)
+    n = 0
+    for win in trace:
+        for aid in win:
+            mgr.request(int(aid))
+            n += 1
+        if n >= 3000:
+            break
+    torch.cuda.synchronize()
+    print("requests", n, "hits", mgr.hits, "misses", mgr.misses, "evictions", mgr.evictions, flush=True)
+    assert mgr.evictions > 200 and mgr.failed == 0
+    assert min(pm.byte_util) >= 0.87, "utilisation fell to %.3f" % min(pm.byte_util)
+
+    op = oracle_mod.OraclePool(cfg["page_bytes"], cfg["n_pages"], lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
+    for what, aid in mgr.log:
+        if what == "load":
+            op.load(aid, int(ranks[aid]), float(scales[aid]), blob(aid).numpy().view(np.uint16))
+        else:
+            op.evict(aid)
+    so, sg = op.stats(), pool.stats()
+    for k in ("used_pages", "free_pages", "resident_bytes", "loads", "evictions"):
+        assert so[k] == sg[k], k
+    res = np.array(sorted(mgr.resident()), dtype=np.int32)
+    # page tables of the survivors: the library hands out a pointer at load time only, so compare through
+    # a fresh load of one evicted adapter and through the decode below (which gathers through every table)
+    rng = np.random.default_rng(5)
+    T = 96
+    p = zipf_probs(pop, 1.0)[res]
+    t2a = res[rng.choice(len(res), size=T, p=p / p.sum())].astype(np.int32)
+    stream = torch.cuda.current_stream().cuda_stream
+    b = pool.batch_begin(t2a, stream)
+    perm, sa, ss = pool.batch_info(b)
+    o_perm, o_sa, o_ss = op.translate(t2a)
+    assert perm.tolist() == o_perm.tolist() and sa.tolist() == o_sa.tolist() and ss.tolist() == o_ss.tolist()
+    xs = [make_act(rng, T, d, lay.dtype) for d in lay.d_in]
+    y0 = [make_act(rng, T, d, lay.dtype) for d in lay.d_out]
+    xd = [raw_to_torch(a, "cuda") for a in xs]
+    yd = [raw_to_torch(a, "cuda") for a in y0]
+    vd = [torch.full((T, cfg["max_rank"]), float("nan"), device="cuda") for _ in xs]
+    pool.shrink(b, 0, xd, vd, stream)
+    pool.expand(b, 0, vd, yd, stream)
+    pool.batch_end(b)
+    torch.cuda.synchronize()
+    sel = np.arange(0, T, 5, dtype=np.int32)
+    for s in range(lay.n_slots):
+        v_ref = op.shrink(s, xs[s], t2a, acc64=True, tok_sel=sel)
+        y_ref = op.expand(s, v_ref, t2a, y0[s].copy(), acc64=True, tok_sel=sel)
+        v_got = vd[s].cpu().numpy()
+        y_got = torch_to_raw(yd[s], lay.dtype)
+        assert rel_err(v_got[sel], v_ref[sel]) <= TOL_V
+        assert rel_err(from_elt(y_got[sel], lay.dtype), from_elt(y_ref[sel], lay.dtype)) <= TOL_Y[lay.dtype]
+    # an evicted adapter comes back onto the same pages on both sides
+    victim = int(res[0])
+    pool.evict(victim)
+    op.evict(victim)
+    pt_g = pool.load(victim, int(ranks[victim]), float(scales[victim]), blob(victim), copy_stream.cuda_stream)
+    pt_o = op.load(victim, int(ranks[victim]), float(scales[victim]), blob(victim).numpy().view(np.uint16))
+    assert pt_g.tolist() == pt_o.tolist()
+    torch.cuda.synchronize()
+    op.close()
+    pool.close()
