@@ -26,7 +26,7 @@ from workload import (CONFIGS, RAW_DTYPE, config_layout, draw_ranks, draw_tok2ad
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
-KCLASS = ["shrink_valu", "shrink_mfma", "expand_valu", "expand_mfma", "shrink_fused", "expand_fused"]
+KCLASS = ["-", "-", "expand_valu", "expand_mfma", "shrink", "expand"]
 
 
 def workload_params(name):
@@ -105,11 +105,13 @@ class GpuWorkload:
                       st["h2d_bytes"] / 1e9 / self.t_load, st["h2d_copies"],
                       st["h2d_bytes"] / 1e6 / max(st["h2d_ms"], 1e-9)), file=sys.stderr, flush=True)
 
-    def alloc_activations(self, T, seed, zero_y=False):
-        """x ~ N(0,1), y0 ~ N(0,1) per slot on the device (raw element tensors), v buffers."""
+    def alloc_activations(self, T, seed, zero_y=False, min_bytes=0):
+        """x ~ N(0,1), y0 ~ N(0,1) per slot on the device (raw element tensors), v buffers.  With
+        min_bytes > 0 the whole set is replicated until it exceeds that many bytes and step() rotates
+        through the replicas, so that activations cannot stay in the 256 MB last-level cache from
+        one step to the next."""
         torch, lay = self.torch, self.lay
         rng = np.random.default_rng(seed)
-        dt = torch.int16 if lay.elt == 2 else torch.float32
         self.T = T
         self.x, self.y, self.v = [], [], []
         # one draw per distinct width, re-used with a per-slot roll so that slots differ
@@ -128,6 +130,11 @@ class GpuWorkload:
                 y.zero_()
             self.y.append(y)
             self.v.append(torch.empty((T, self.max_rank), dtype=torch.float32, device="cuda"))
+        one = sum(t.numel() * t.element_size() for t in self.x + self.y + self.v)
+        self.act_sets = [(self.x, self.y, self.v)]
+        while one * len(self.act_sets) < min_bytes:
+            self.act_sets.append(([t.clone() for t in self.x], [t.clone() for t in self.y], [t.clone() for t in self.v]))
+        self.act_bytes, self.step_no = one, 0
         torch.cuda.synchronize()
 
     def set_mfma_min(self, n):
@@ -144,11 +151,13 @@ class GpuWorkload:
         pool, n = self.pool, self.lay.n_slots
         if len(t2a) > self.T:  # the library cannot see buffer sizes: never launch past the activations
             raise ValueError("batch of %d tokens but activation buffers hold %d" % (len(t2a), self.T))
+        x, y, v = self.act_sets[self.step_no % len(self.act_sets)]
+        self.step_no += 1
         b = pool.batch_begin(t2a, self.stream)
         for s0 in range(0, n, slots_per_call):
             s1 = min(n, s0 + slots_per_call)
-            pool.shrink(b, s0, self.x[s0:s1], self.v[s0:s1], self.stream)
-            pool.expand(b, s0, self.v[s0:s1], self.y[s0:s1], self.stream)
+            pool.shrink(b, s0, x[s0:s1], v[s0:s1], self.stream)
+            pool.expand(b, s0, v[s0:s1], y[s0:s1], self.stream)
         pool.batch_end(b)
 
     def close(self):
@@ -336,7 +345,7 @@ def main():
     n_draws = 1 if args.same_batch else args.steps + args.warmup
     batches = [draw_batch(cfg, rng, w.n_ad) for _ in range(n_draws)]
     T = max(len(b) for b in batches)
-    w.alloc_activations(T, cfg["seed"] + 9)
+    w.alloc_activations(T, cfg["seed"] + 9, min_bytes=768 << 20)
     spc = args.slots_per_call or lay.n_slots
     all_slots = list(range(lay.n_slots))
 
@@ -396,7 +405,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": args.workload, "slots": lay.n_slots, "tokens": int(T), "adapters": int(w.n_ad),
                    "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc),
-                   "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1)},
+                   "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1),
+                   "activation_sets": len(w.act_sets), "activation_bytes_per_set": int(w.act_bytes)},
         "tokens_per_s": round(tokens_total / elapsed, 1),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_step": int(bytes_total / args.steps),

@@ -78,7 +78,7 @@ typedef struct {
  * n_pages * page_bytes bytes, 256-byte aligned, that stays valid until plora_pool_destroy (the
  * caller keeps ownership), or NULL to let the pool allocate and own the slab.  The layout arrays are
  * copied.  INVAL for bad sizes or a layout whose rows would need more page-table window than the
- * kernels stage (64 * max(d_in) * elt / page_bytes + 2 > 1024). */
+ * kernels stage (32 * max(d_in) * elt / page_bytes + 8 > 1024). */
 int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* layout, void* slab_or_null,
                       uint32_t flags, plora_pool** out);
 
@@ -161,8 +161,8 @@ int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand bracket
  * every kernel launch with a pair of HIP events on the launch stream; plora_profile(pool, 0) stops.
  * plora_profile_read waits for the recorded events and returns, per kernel class
- * (0 shrink vector-ALU, 1 shrink matrix-core, 2 expand vector-ALU, 3 expand matrix-core, 4 shrink
- * fused, 5 expand fused), the summed duration in ms and the number of launches since the last read,
+ * (0, 1 unused, 2 expand vector-ALU items, 3 expand matrix-core items, 4 shrink, 5 expand as one
+ * mixed launch), the summed duration in ms and the number of launches since the last read,
  * then clears the record.  ms and launches: host, 6 entries each. */
 int plora_profile(plora_pool* pool, int enable);
 int plora_profile_read(plora_pool* pool, double* ms, uint64_t* launches);

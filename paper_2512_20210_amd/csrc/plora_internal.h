@@ -75,13 +75,14 @@ struct LaunchArgs {
   int32_t pad;
 };
 
-// Launchers (plora_kernels.hip).  kind: 0 = list holds vector-ALU items only, 1 = matrix-core items
-// only, 2 = mixed.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
+// Launchers (plora_kernels.hip).  Shrink takes a list of blocks of 4 records (one matrix-core item +
+// 3 padding records, or up to 4 vector-ALU items) and runs one 256-thread workgroup per block and
+// slot.  Expand: kind 0 = list holds vector-ALU items only, 1 = matrix-core items only, 2 = mixed.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
 // a.slot_fastest is set: consecutive workgroups go to consecutive XCDs, so with a slot count that
 // is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
 // slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row
 // of B (shrink: chunks = 1).
-hipError_t launch_shrink(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, hipStream_t st);
+hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, hipStream_t st);
 hipError_t launch_expand(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks,
                          hipStream_t st);
 

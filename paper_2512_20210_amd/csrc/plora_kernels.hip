@@ -113,6 +113,16 @@ __device__ __forceinline__ float wave_sum(float s) {
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 
+// Orders one wavefront's LDS writes before its later LDS reads (any lane).  LDS instructions of a
+// wavefront execute in order, so only the compiler has to be kept from moving them: no s_barrier,
+// which lets the wavefronts of a 256-thread workgroup run independent vector-ALU items.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+__device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
+
 // ------------------------------------------------------------------------------------------
 // shrink, vector-ALU item
 // ------------------------------------------------------------------------------------------
@@ -123,7 +133,7 @@ __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uin
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
   const int lp = a.log2_page;
   const uint64_t pmask = ((uint64_t)1 << lp) - 1;
-  const int k = k0 + (int)threadIdx.x * VEC;
+  const int k = k0 + lane_id() * VEC;
   const bool ok = !TAIL || k < d_in;
   const int kk = ok ? k : 0;
   uint4 xq[NT];
@@ -159,7 +169,7 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
-  const int lane = threadIdx.x;
+  const int lane = lane_id();
   const int r = it.rank;
   const int d_in = sl.d_in;
   const int vs = a.v_stride;
@@ -184,7 +194,7 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
         for (int j = r + lane; j < vs; j += kWave) v[tok[i] * vs + j] = 0.f;
   }
   if (r == 0) return;
-  __syncthreads();
+  wave_sync();
 
   float acc[kShrinkRows][NT];
 #pragma unroll
@@ -226,12 +236,12 @@ __device__ __forceinline__ int table_len(const LaunchArgs& a, int r, int eb) {
 
 // Stages, for every row j of B, the physical pages that hold the first and the last byte of the
 // item's piece of that row (a piece is 1024 bytes, a page at least 4096).  No barrier here: the
-// caller issues its other loads first and then calls __syncthreads().
+// caller issues its other loads first and then calls wave_sync().
 __device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const ItemRec& it, int n_pt, uint64_t base,
                                                 uint64_t rowb, uint32_t piece_bytes, int2* lds_pg) {
   const int lp = a.log2_page;
   const int32_t* ptg = a.pt + it.pt_off;
-  for (int j = threadIdx.x; j < it.rank; j += kWave) {
+  for (int j = lane_id(); j < it.rank; j += kWave) {
     const uint64_t vo = base + (uint64_t)j * rowb;
     const uint32_t q0 = (uint32_t)(vo >> lp);
     const uint32_t q1 = imin((int)((vo + piece_bytes - 1) >> lp), n_pt - 1);
@@ -243,7 +253,7 @@ template <int DT, int NT>
 __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
-  const int lane = threadIdx.x;
+  const int lane = lane_id();
   const int r = it.rank;
   const int d_out = sl.d_out;
   const int n0w = (a.slot_fastest ? blockIdx.z : blockIdx.y) * (kWave * VEC);
@@ -267,7 +277,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
     yp[i] = y + ((uint64_t)it.tok[i] * d_out + (ok ? n : n0w)) * EB;
     yq[i] = ld16(yp[i]);  // requested now, used after the loop
   }
-  __syncthreads();
+  wave_sync();
   float acc[NT][VEC];
 #pragma unroll
   for (int i = 0; i < NT; ++i)
@@ -359,16 +369,10 @@ constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16
 static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
 template <int DT>
-__global__ __launch_bounds__(256) void k_shrink_mfma4(const LaunchArgs a, const SlotPtrs p) {
+__device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
+                                                  uint8_t (*tile)[2][kSmRows * kSmPitch], int32_t* lds_pt) {
   constexpr int EB = 2;
-  __shared__ __align__(16) uint8_t tile[4][2][kSmRows * kSmPitch];  // [wavefront][A | x]
-  __shared__ int32_t lds_pt[kPtWindow];
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
-  if (it.kind < 0) return;
-  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
-  const uint8_t* __restrict__ x = (const uint8_t*)p.a[q];
-  float* __restrict__ v = (float*)p.b[q];
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;   // MFMA coordinates
@@ -506,7 +510,7 @@ template <int DT, int MT, bool TAIL>
 __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int2* lds_pg, const float* const* vrow,
                                                   uint64_t base, uint64_t rowb, uint32_t lane_b, int r, int jb,
                                                   f32x4 (*acc)[8]) {
-  const int g = (int)threadIdx.x >> 4;
+  const int g = lane_id() >> 4;
   const int lp = a.log2_page;
   const uint32_t pmask = (1u << lp) - 1;
   const int vs = a.v_stride;
@@ -572,7 +576,7 @@ template <int DT, int MT>
 __device__ __forceinline__ void expand_mfma_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg) {
   constexpr int EB = 2;
-  const int lane = threadIdx.x;
+  const int lane = lane_id();
   const int g = lane >> 4, c = lane & 15;
   const int r = it.rank;
   const int d_out = sl.d_out;
@@ -593,7 +597,7 @@ __device__ __forceinline__ void expand_mfma_body(const LaunchArgs& a, const Item
 #pragma unroll
     for (int i = 0; i < 4; ++i) trow[mt][i] = __shfl(tc, g * 4 + i, 64);
   }
-  __syncthreads();
+  wave_sync();
 
   for (int pass = 0; pass < 4; ++pass) {
     const int n = n0i + pass * kMfmaCols + 8 * c;
@@ -642,14 +646,31 @@ __device__ __forceinline__ void expand_mfma_item(const LaunchArgs& a, const Item
   }
 }
 
+// Shrink: workgroups of 4 wavefronts.  The work list is a sequence of blocks of 4 records: either
+// one matrix-core item (first record, the other three are padding) that the 4 wavefronts share,
+// or up to 4 independent vector-ALU items, one per wavefront.  The matrix-core blocks come first in
+// the list, so their long dependent chains start first and the short items fill the machine around
+// and after them in the same launch.
 template <int DT>
-__global__ __launch_bounds__(kWave) void k_shrink_valu(const LaunchArgs a, const SlotPtrs p) {
+__global__ __launch_bounds__(256) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ __align__(16) uint8_t tile[4][2][kSmRows * kSmPitch];  // [wavefront][A | x]
   __shared__ int32_t lds_pt[kPtWindow];
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
-  if (it.kind < 0) return;
+  const int blk = a.slot_fastest ? blockIdx.z : blockIdx.x;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[a.slot0 + q];
-  shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
+  const uint8_t* x = (const uint8_t*)p.a[q];
+  float* v = (float*)p.b[q];
+  const ItemRec first = a.items[4 * blk];
+  if constexpr (DT != 2) {
+    if (first.kind == 1) {
+      shrink_mfma4_body<DT>(a, first, sl, x, v, tile, lds_pt);
+      return;
+    }
+  }
+  const int wave = threadIdx.x >> 6;
+  const ItemRec it = a.items[4 * blk + wave];
+  if (it.kind < 0) return;  // this path has no workgroup barrier: a wavefront may leave alone
+  shrink_valu_item<DT>(a, it, sl, x, v, lds_pt + wave * (kPtWindow / 4));
 }
 
 // KIND 0: vector-ALU items only, 1: matrix-core items only, 2: mixed list.
@@ -680,23 +701,20 @@ void launch_expand_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, 
 
 }  // namespace
 
-hipError_t launch_shrink(int dtype, int kind, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, hipStream_t st) {
+hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, hipStream_t st) {
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
-  if (kind > 1 || (dtype == 2 && kind == 1)) return hipErrorInvalidValue;
+  if (a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
   LaunchArgs a = a0;
-  const int step = a0.slot_fastest ? 65535 : a0.n_items;  // grid.z is limited to 65535
-  for (int first = 0; first < a0.n_items; first += step) {
-    a.items = a0.items + first;
-    a.n_items = a0.n_items - first < step ? a0.n_items - first : step;
-    const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, a.n_items) : dim3(a.n_items, 1, n_slots);
-    if (kind == 1) {
-      if (dtype == 0) hipLaunchKernelGGL(k_shrink_mfma4<0>, grid, dim3(256), 0, st, a, p);
-      else hipLaunchKernelGGL(k_shrink_mfma4<1>, grid, dim3(256), 0, st, a, p);
-    } else {
-      if (dtype == 0) hipLaunchKernelGGL(k_shrink_valu<0>, grid, dim3(kWave), 0, st, a, p);
-      else if (dtype == 1) hipLaunchKernelGGL(k_shrink_valu<1>, grid, dim3(kWave), 0, st, a, p);
-      else hipLaunchKernelGGL(k_shrink_valu<2>, grid, dim3(kWave), 0, st, a, p);
-    }
+  const int n_blocks = a0.n_items / 4;
+  const int step = a0.slot_fastest ? 65535 : n_blocks;  // grid.z is limited to 65535
+  for (int first = 0; first < n_blocks; first += step) {
+    const int nb = n_blocks - first < step ? n_blocks - first : step;
+    a.items = a0.items + 4 * first;
+    a.n_items = 4 * nb;
+    const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, nb) : dim3(nb, 1, n_slots);
+    if (dtype == 0) hipLaunchKernelGGL(k_shrink<0>, grid, dim3(256), 0, st, a, p);
+    else if (dtype == 1) hipLaunchKernelGGL(k_shrink<1>, grid, dim3(256), 0, st, a, p);
+    else hipLaunchKernelGGL(k_shrink<2>, grid, dim3(256), 0, st, a, p);
   }
   return hipGetLastError();
 }

@@ -163,6 +163,46 @@ void arrange(std::vector<Group>& groups, bool xcd_aware, std::vector<ItemRec>& o
     for (int k = 0; k < kXcds; ++k) out.push_back(i < q[k].size() ? q[k][i] : pad);
 }
 
+
+// Shrink work list: blocks of 4 records, one 256-thread workgroup each.  A matrix-core item fills a
+// block alone (3 padding records); vector-ALU items go four to a block, one per wavefront.
+// Matrix-core blocks first (their dependent chains are the long ones).  With xcd_aware the groups
+// are dealt into 8 queues as in arrange() and the queues are interleaved block by block.
+void arrange_blocks(const std::vector<Group>& heavy, const std::vector<Group>& light, bool xcd_aware,
+                    std::vector<ItemRec>& out) {
+  out.clear();
+  ItemRec pad{};
+  pad.kind = -1;
+  const int nq = xcd_aware ? kXcds : 1;
+  std::vector<std::vector<ItemRec>> qh(nq), ql(nq);
+  std::vector<double> load(nq, 0.0);
+  auto deal = [&](const std::vector<Group>& groups, std::vector<std::vector<ItemRec>>& dst) {
+    std::vector<const Group*> order;
+    for (const Group& g : groups) if (!g.items.empty()) order.push_back(&g);
+    if (xcd_aware)
+      std::stable_sort(order.begin(), order.end(), [](const Group* a, const Group* b) { return a->cost > b->cost; });
+    for (const Group* g : order) {
+      int best = 0;
+      for (int k = 1; k < nq; ++k) if (load[k] < load[best]) best = k;
+      dst[best].insert(dst[best].end(), g->items.begin(), g->items.end());
+      load[best] += g->cost;
+    }
+  };
+  deal(heavy, qh);
+  deal(light, ql);
+  std::vector<std::vector<ItemRec>> blocks(nq);  // per queue, 4 records per block
+  size_t longest = 0;
+  for (int k = 0; k < nq; ++k) {
+    for (const ItemRec& it : qh[k]) { blocks[k].push_back(it); blocks[k].insert(blocks[k].end(), 3, pad); }
+    blocks[k].insert(blocks[k].end(), ql[k].begin(), ql[k].end());
+    while (blocks[k].size() % 4) blocks[k].push_back(pad);
+    longest = std::max(longest, blocks[k].size() / 4);
+  }
+  for (size_t i = 0; i < longest; ++i)
+    for (int k = 0; k < nq; ++k)
+      for (int w = 0; w < 4; ++w) out.push_back(4 * i + w < blocks[k].size() ? blocks[k][4 * i + w] : pad);
+}
+
 }  // namespace
 
 extern "C" {
@@ -191,7 +231,10 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
     max_in = std::max(max_in, di);
     max_out = std::max(max_out, dn);
   }
-  if ((uint64_t)std::max(kMfmaRows, kShrinkRows) * (uint64_t)max_in * elt / page_bytes + 2 > (uint64_t)kPtWindow) return PLORA_ERR_INVAL;
+  // page-table windows staged in LDS: 32 rows per matrix-core item (kPtWindow entries), 8 rows per
+  // vector-ALU item (a quarter of that)
+  static_assert(kMfmaRows == 4 * kShrinkRows, "window budget assumes 32 and 8 rows");
+  if ((uint64_t)kMfmaRows * (uint64_t)max_in * elt / page_bytes + 8 > (uint64_t)kPtWindow) return PLORA_ERR_INVAL;
 
   plora_pool* p = new (std::nothrow) plora_pool;
   if (!p) return PLORA_ERR_NOMEM;
@@ -475,21 +518,29 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     n_pt_total += a.pt.size();
     const int16_t rank = (int16_t)a.rank;
     if (mfma_ok && n >= p->mfma_min_tokens) {
-      Group gs, ge;
-      gs.heavy = ge.heavy = true;
-      for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
-        for (int32_t t0 = 0; t0 < n; t0 += kMfmaTokS) {
-          const int16_t nt = (int16_t)std::min(kMfmaTokS, n - t0);
-          gs.items.push_back(ItemRec{1, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
-          gs.cost += std::min(kMfmaRows, a.rank - j0) + nt;
+      // Large groups (prefill) are cut into blocks of kTokBlock tokens: a block is the unit that is
+      // dealt to an XCD, and inside a block the items go row group by row group with the token
+      // groups innermost, so a tile of A is re-read back to back and the block's x tiles (at most
+      // kTokBlock rows) stay in L2 for the next row group.
+      constexpr int kTokBlock = 128;
+      for (int32_t b0 = 0; b0 < n; b0 += kTokBlock) {
+        const int32_t b1 = std::min(n, b0 + kTokBlock);
+        Group gs, ge;
+        gs.heavy = ge.heavy = true;
+        for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
+          for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokS) {
+            const int16_t nt = (int16_t)std::min(kMfmaTokS, b1 - t0);
+            gs.items.push_back(ItemRec{1, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+            gs.cost += std::min(kMfmaRows, a.rank - j0) + nt;
+          }
+        for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokE) {
+          const int16_t nt = (int16_t)std::min(kMfmaTokE, b1 - t0);
+          ge.items.push_back(ItemRec{1, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+          ge.cost += a.rank + 2 * nt;
         }
-      for (int32_t t0 = 0; t0 < n; t0 += kMfmaTokE) {
-        const int16_t nt = (int16_t)std::min(kMfmaTokE, n - t0);
-        ge.items.push_back(ItemRec{1, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
-        ge.cost += a.rank + 2 * nt;
+        grp[0][1].push_back(std::move(gs));
+        grp[1][1].push_back(std::move(ge));
       }
-      grp[0][1].push_back(std::move(gs));
-      grp[1][1].push_back(std::move(ge));
     } else {
       Group gs, ge;
       std::vector<ItemRec> tg;  // one record per token group
@@ -525,7 +576,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     grp[0][0].push_back(std::move(gs));
   }
   std::vector<ItemRec> lists[2][6];
-  for (int op = 0; op < 2; ++op) {
+  for (int lay = 0; lay < 2; ++lay) arrange_blocks(grp[0][1], grp[0][0], lay != 0, lists[0][3 * lay]);
+  for (int op = 1; op < 2; ++op) {
     std::vector<Group> both;
     both.reserve(grp[op][0].size() + grp[op][1].size());
     for (const Group& g : grp[op][1]) both.push_back(g);
@@ -643,14 +695,16 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     a.pad = 0;
     const int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
     const int chunks = (max_out + kWave * vec - 1) / (kWave * vec);
-    // launches: fused = the mixed list; else matrix-core items (the long ones) first, then the rest
+    // shrink: one launch over the block list; expand: the mixed list in one launch, or matrix-core
+    // items (the long ones) first and then the rest
     struct L { int kind, cls; };
     L ls[2];
     int nl = 0;
-    if (p->fused && !is_shrink) ls[nl++] = L{2, 4 + op};  // shrink kernels differ in workgroup size: never fused
+    if (is_shrink) ls[nl++] = L{0, 4};
+    else if (p->fused) ls[nl++] = L{2, 5};
     else {
-      ls[nl++] = L{1, op * 2 + 1};
-      ls[nl++] = L{0, op * 2};
+      ls[nl++] = L{1, 3};
+      ls[nl++] = L{0, 2};
     }
     for (int li = 0; li < nl; ++li) {
       a.items = (const ItemRec*)(b->d_img + b->off_items[op][ls[li].kind + 3 * layout]);
@@ -665,7 +719,7 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
         HIP_TRY(hipEventRecord(rec.e0, (hipStream_t)s));
       }
       hipError_t e;
-      if (is_shrink) e = launch_shrink(p->dtype, ls[li].kind, a, ptrs, nq, (hipStream_t)s);
+      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, (hipStream_t)s);
       else e = launch_expand(p->dtype, ls[li].kind, a, ptrs, nq, chunks, (hipStream_t)s);
       HIP_TRY(e);
       if (p->profiling) {

@@ -21,6 +21,10 @@ CONFIGS = {
     "cfg2": dict(seed=BASE_SEED + 2, dtype=DT_BF16, slots=[(4096, 4096)] * 4, requests=32, len_lo=64,
                  len_hi=256, n_adapters=128, ranks=None, rank_choices=[8, 16, 32, 64, 128], zipf=1.2,
                  scale=None, page_bytes=64 * KIB, n_pages=None, max_rank=128),
+    # the same prefill batch over 8 layers (32 slots): shows the kernels with ample parallelism
+    "cfg2x8": dict(seed=BASE_SEED + 2, dtype=DT_BF16, slots=[(4096, 4096)] * 32, requests=32, len_lo=64,
+                   len_hi=256, n_adapters=128, ranks=None, rank_choices=[8, 16, 32, 64, 128], zipf=1.2,
+                   scale=None, page_bytes=64 * KIB, n_pages=None, max_rank=128),
     # churn: 2 GiB pool of 64 KiB pages, 10,000 load/evict-driving requests over a population of
     # adapters with ranks in {4,...,128}, Zipf(1.0) popularity, bursts (x8 for 10% of windows),
     # interleaved with 512-token bf16 decode batches at hidden 4096 (q,k,v,o of one layer)
