@@ -26,7 +26,7 @@ from workload import (CONFIGS, RAW_DTYPE, config_layout, draw_ranks, draw_tok2ad
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
-KCLASS = ["-", "-", "expand_valu", "expand_mfma", "shrink", "expand"]
+KCLASS = ["shrink", "expand"]
 
 
 def workload_params(name):
@@ -80,7 +80,6 @@ class GpuWorkload:
         lay, cfg = self.lay, self.cfg
         self.n_ad = len(self.ranks)
         self.max_rank = cfg["max_rank"]
-        self.mfma_min = 5  # the library's default for "mfma_min_tokens"
         t0 = time.perf_counter()
         self.pinned = [torch.empty(lay.adapter_elems(int(r)), dtype=torch.int16 if lay.elt == 2 else torch.float32,
                                    pin_memory=True) for r in self.ranks]
@@ -136,10 +135,6 @@ class GpuWorkload:
             self.act_sets.append(([t.clone() for t in self.x], [t.clone() for t in self.y], [t.clone() for t in self.v]))
         self.act_bytes, self.step_no = one, 0
         torch.cuda.synchronize()
-
-    def set_mfma_min(self, n):
-        self.pool.set_option("mfma_min_tokens", n)
-        self.mfma_min = n
 
     def host_x(self, s):
         return np.roll(self.x_host_base[self.lay.d_in[s]], s, axis=0)
@@ -313,8 +308,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
-    ap.add_argument("--mfma-min-tokens", type=int, default=-1)
-    ap.add_argument("--fused", type=int, default=-1, help="1 = one launch per call over the mixed item list")
+    ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="matrix-core threshold of shrink (library default 5)")
+    ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand (library default 16)")
     ap.add_argument("--xcd-remap", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
@@ -336,9 +331,9 @@ def main():
     w = GpuWorkload(args.workload, verbose=args.verbose)
     cfg, lay = w.cfg, w.lay
     if args.mfma_min_tokens >= 0:
-        w.set_mfma_min(args.mfma_min_tokens)
-    if args.fused >= 0:
-        w.pool.set_option("fused", args.fused)
+        w.pool.set_option("mfma_min_tokens", args.mfma_min_tokens)
+    if args.mfma_min_tokens_expand >= 0:
+        w.pool.set_option("mfma_min_tokens_expand", args.mfma_min_tokens_expand)
     if args.xcd_remap >= 0:
         w.pool.set_option("xcd_remap", args.xcd_remap)
     rng = np.random.default_rng(cfg["seed"] + 7)
@@ -361,7 +356,7 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
-    kms, kn = ([0.0] * 6, [0] * 6)
+    kms, kn = ([0.0] * 2, [0] * 2)
     if not args.no_kernel_events:
         w.pool.profile(False)
         kms, kn = w.pool.profile_read()
@@ -376,27 +371,14 @@ def main():
     roof = None
     if not args.no_kernel_events and sum(kn):
         dom = int(np.argmax(kms))
-        is_shrink = dom in (0, 1, 4)
-        mfma_min = w.mfma_min
-        kb = 0
-        for t2a in timed:
-            has = t2a >= 0
-            ids, counts = np.unique(t2a[has], return_counts=True)
-            on_mfma = (counts >= mfma_min) if (mfma_min > 0 and lay.dtype != 2) else np.zeros(len(ids), bool)
-            sel = np.ones(len(ids), bool) if dom >= 4 else (on_mfma if dom % 2 == 1 else ~on_mfma)
-            sum_r_u = int(sum(int(w.ranks[u]) for u in ids[sel]))
-            ntok = int(counts[sel].sum())
-            sum_r_t = int(sum(int(w.ranks[u]) * int(c) for u, c in zip(ids[sel], counts[sel])))
-            for s in all_slots:
-                d = lay.d_in[s] if is_shrink else lay.d_out[s]
-                kb += sum_r_u * d * lay.elt + (1 if is_shrink else 2) * ntok * d * lay.elt + sum_r_t * 4 + 4 * ntok
+        kb = sum(a["shrink" if dom == 0 else "expand"] for a in ab)
         avg_ms = kms[dom] / kn[dom]
         per_launch = kb / kn[dom]
         ach = per_launch / (avg_ms * 1e-3) / 1e9
         roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(ach / HBM_PEAK_GBS, 4), traffic=None, avg_launch_ms=round(avg_ms, 5),
                     launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
-                    all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(6) if kn[k]})
+                    all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(2) if kn[k]})
 
     out = {
         "metric": METRIC, "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,

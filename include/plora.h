@@ -151,19 +151,19 @@ int plora_batch_end(plora_pool* pool, plora_batch* batch);
 /* Counters of the pool (Sec. V-A lists memory utilisation and fragmentation as metrics). */
 int plora_pool_stats(plora_pool* pool, plora_stats* out);
 
-/* Tunables.  key: "mfma_min_tokens" (adapter groups with at least this many tokens use the
- * matrix-core path; 0 disables it; takes effect for batches begun afterwards), "fused" (expand
- * only: 1 = one kernel launch per call over the mixed work list, 0 = matrix-core items and
- * vector-ALU items in two launches), "xcd_remap" (1 = neighbouring work items share an XCD).  INVAL for an unknown key
- * or a value out of range. */
+/* Tunables.  key: "mfma_min_tokens" / "mfma_min_tokens_expand" (adapter groups with at least this
+ * many tokens use the matrix-core items in shrink / expand; 0 disables them; defaults 5 / 16; take
+ * effect for batches begun afterwards), "slot_major" (-1 =
+ * slots are the fastest grid dimension when their count is a multiple of 8, 0 never, 1 always),
+ * "xcd_remap" (1 = for launches whose fastest dimension is the work item, neighbouring work items
+ * share an XCD).  INVAL for an unknown key or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand bracket
  * every kernel launch with a pair of HIP events on the launch stream; plora_profile(pool, 0) stops.
- * plora_profile_read waits for the recorded events and returns, per kernel class
- * (0, 1 unused, 2 expand vector-ALU items, 3 expand matrix-core items, 4 shrink, 5 expand as one
- * mixed launch), the summed duration in ms and the number of launches since the last read,
- * then clears the record.  ms and launches: host, 6 entries each. */
+ * plora_profile_read waits for the recorded events and returns, per kernel (0 shrink, 1 expand), the
+ * summed duration in ms and the number of launches since the last read, then clears the record.
+ * ms and launches: host, 2 entries each. */
 int plora_profile(plora_pool* pool, int enable);
 int plora_profile_read(plora_pool* pool, double* ms, uint64_t* launches);
 

@@ -158,10 +158,9 @@ def plora_profile(pool, enable):
 
 
 def plora_profile_read(pool):
-    """-> (status, ms[6], launches[6]) for shrink-valu, shrink-mfma, expand-valu, expand-mfma,
-    shrink-fused, expand-fused."""
-    ms = (C.c_double * 6)()
-    n = (C.c_uint64 * 6)()
+    """-> (status, ms[2], launches[2]) for the shrink and the expand kernel."""
+    ms = (C.c_double * 2)()
+    n = (C.c_uint64 * 2)()
     rc = lib.plora_profile_read(pool, ms, n)
     return rc, list(ms), list(n)
 

@@ -23,17 +23,17 @@ constexpr int kExpandU = PLORA_EXPAND_U;        // rows of B in flight per vecto
 #define PLORA_MFMA_TOK_S 32
 #endif
 #ifndef PLORA_MFMA_TOK_E
-#define PLORA_MFMA_TOK_E 16
+#define PLORA_MFMA_TOK_E 64  // 64: token-split panel form for large groups; 16 or 32: column-split form only
 #endif
 constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item
-constexpr int kMfmaTokE = PLORA_MFMA_TOK_E;     // tokens per matrix-core expand item (16 or 32)
+constexpr int kMfmaTokE = PLORA_MFMA_TOK_E;     // tokens per matrix-core expand item
 #ifndef PLORA_MFMA_ROWS
 #define PLORA_MFMA_ROWS 32
 #endif
 constexpr int kMfmaRows = PLORA_MFMA_ROWS;      // rows of A per matrix-core shrink item
 constexpr int kMfmaCols = 128;          // columns of B per matrix-core expand pass
 constexpr int kPtWindow = 1024;         // page-table entries a shrink item may stage in LDS
-constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for
+constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for (4 KiB of LDS)
 constexpr int kXcds = 8;                // consecutive workgroups go to consecutive XCDs
 
 // One wavefront's worth of work, self-contained so that a wavefront needs a single 32-byte read
@@ -75,15 +75,15 @@ struct LaunchArgs {
   int32_t pad;
 };
 
-// Launchers (plora_kernels.hip).  Shrink takes a list of blocks of 4 records (one matrix-core item +
-// 3 padding records, or up to 4 vector-ALU items) and runs one 256-thread workgroup per block and
-// slot.  Expand: kind 0 = list holds vector-ALU items only, 1 = matrix-core items only, 2 = mixed.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
+// Launchers (plora_kernels.hip).  Both take a list of blocks of 4 records (one matrix-core item +
+// 3 padding records, or up to 4 vector-ALU items) and run one 256-thread workgroup per block, slot
+// and (expand) 512-column chunk.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
 // a.slot_fastest is set: consecutive workgroups go to consecutive XCDs, so with a slot count that
 // is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
 // slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row
 // of B (shrink: chunks = 1).
 hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, hipStream_t st);
-hipError_t launch_expand(int dtype, int kind, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks,
+hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks,
                          hipStream_t st);
 
 }  // namespace plora

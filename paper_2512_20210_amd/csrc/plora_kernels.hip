@@ -12,9 +12,9 @@
 //                             workgroup of 4 wavefronts that split d_in; operands staged in LDS.
 //   expand, vector-ALU item : all rows of B x 64 lanes x 16 bytes of columns x up to 4 tokens;
 //                             no reduction, read-modify-write of y.
-//   expand, matrix-core item: all rows of B x 512 columns (4 passes of 128) x up to 16 tokens; v is
-//                             split into a high and a low half so that fp32 v loses nothing that
-//                             matters.
+//   expand, matrix-core item: all rows of B x 512 columns x up to 64 tokens by a workgroup of 4
+//                             wavefronts with B stationary in LDS; v is split into a high and a low
+//                             half so that fp32 v loses nothing that matters.
 //
 // Address translation: virtual byte o of an adapter is at slab + pt[o >> log2P] * P + (o & (P-1)).
 // A 16-byte vector never straddles a page (all offsets are multiples of 16).  Each item stages the
@@ -41,8 +41,15 @@ template <> struct Elt<2> { static constexpr int B = 4, VEC = 4; };
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 // Weights are read once per batch: a streaming (non-temporal) load keeps them from pushing the
 // re-used x / y / v rows and page-table entries out of L2.
+// Minimum workgroups per CU the compiler must leave room for (bounds the VGPR budget).
+#ifndef PLORA_SHRINK_WG_PER_CU
+#define PLORA_SHRINK_WG_PER_CU 3
+#endif
+#ifndef PLORA_EXPAND_WG_PER_CU
+#define PLORA_EXPAND_WG_PER_CU 3
+#endif
 #ifndef PLORA_NT_WEIGHTS
-#define PLORA_NT_WEIGHTS 1
+#define PLORA_NT_WEIGHTS 0
 #endif
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 __device__ __forceinline__ uint4 ldw16(const void* p) {
@@ -251,12 +258,13 @@ __device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const ItemR
 
 template <int DT, int NT>
 __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
-                                                 const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg) {
+                                                 const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg,
+                                                 int chunk) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
   const int lane = lane_id();
   const int r = it.rank;
   const int d_out = sl.d_out;
-  const int n0w = (a.slot_fastest ? blockIdx.z : blockIdx.y) * (kWave * VEC);
+  const int n0w = chunk * (kWave * VEC);
   if (n0w >= d_out || r == 0) return;
   const int n = n0w + lane * VEC;
   const bool ok = n < d_out;
@@ -337,10 +345,10 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
 
 template <int DT>
 __device__ __forceinline__ void expand_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
-                                                 const float* v, uint8_t* y, int2* lds_pg) {
-  if (it.ntok <= 1) expand_valu_body<DT, 1>(a, it, sl, v, y, lds_pg);
-  else if (it.ntok == 2) expand_valu_body<DT, 2>(a, it, sl, v, y, lds_pg);
-  else expand_valu_body<DT, kValuTok>(a, it, sl, v, y, lds_pg);
+                                                 const float* v, uint8_t* y, int2* lds_pg, int chunk) {
+  if (it.ntok <= 1) expand_valu_body<DT, 1>(a, it, sl, v, y, lds_pg, chunk);
+  else if (it.ntok == 2) expand_valu_body<DT, 2>(a, it, sl, v, y, lds_pg, chunk);
+  else expand_valu_body<DT, kValuTok>(a, it, sl, v, y, lds_pg, chunk);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -566,30 +574,26 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
   }
 }
 
-// expand: D[token, col] += V[token, j] * B[j, col], K = 32 rows of B per step.  Lane (g, c) loads
-// the 8x8 block rows 8 g .. 8 g + 7 x columns 8 c .. 8 c + 7 (16 bytes per row), transposes it in
-// registers into eight 8-value K-vectors, one per column offset cc, and issues eight MFMAs whose
-// result column l%16 stands for the real column 8 c + cc.  A lane therefore ends up with 8
-// consecutive columns of y for each of its 4 token rows: one 16-byte read-modify-write each.
-// One item covers 512 columns as 4 passes of 128.
+// Column-split form for items of at most 32 tokens: every wavefront takes its own 128 columns of the
+// 512-column chunk and all MT token tiles, loads its tile of B straight into registers (each tile is
+// used by one wavefront only, so nothing is shared and there is no barrier after the page staging),
+// transposes and multiplies.
 template <int DT, int MT>
-__device__ __forceinline__ void expand_mfma_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
-                                                 const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg) {
+__device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+                                                      const float* __restrict__ v, uint8_t* __restrict__ y,
+                                                      const int2* lds_pg, int chunk, uint64_t base, uint64_t rowb) {
   constexpr int EB = 2;
-  const int lane = lane_id();
+  const int wave = threadIdx.x >> 6, lane = lane_id();
   const int g = lane >> 4, c = lane & 15;
-  const int r = it.rank;
-  const int d_out = sl.d_out;
-  const int n0i = (a.slot_fastest ? blockIdx.z : blockIdx.y) * (kWave * 8);
-  if (n0i >= d_out) return;
-  const int vs = a.v_stride;
-  const uint64_t rowb = (uint64_t)d_out * EB;
-  const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0i * EB;
-  stage_row_pages(a, it, table_len(a, r, EB), base, rowb, kWave * 16, lds_pg);
+  const int r = it.rank, d_out = sl.d_out, vs = a.v_stride;
+  const int n0 = chunk * 512 + wave * kMfmaCols;
+  if (n0 >= d_out) return;
+  const int n = n0 + 8 * c;
+  const bool ok = n < d_out;
+  const uint32_t lane_b = ok ? (uint32_t)(wave * kMfmaCols * EB + c * 16) : 0;
   const int32_t* perm = a.perm + it.tok[0];
-
   const float* vrow[MT];
-  int64_t trow[MT][4];  // tokens of the result rows this lane holds
+  int64_t trow[MT][4];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int tc = perm[imin(mt * 16 + c, it.ntok - 1)];
@@ -597,53 +601,179 @@ __device__ __forceinline__ void expand_mfma_body(const LaunchArgs& a, const Item
 #pragma unroll
     for (int i = 0; i < 4; ++i) trow[mt][i] = __shfl(tc, g * 4 + i, 64);
   }
-  wave_sync();
-
-  for (int pass = 0; pass < 4; ++pass) {
-    const int n = n0i + pass * kMfmaCols + 8 * c;
-    if (n0i + pass * kMfmaCols >= d_out) break;
-    const bool ok = n < d_out;
-    const uint32_t lane_b = ok ? (uint32_t)(pass * kMfmaCols * EB + c * 16) : 0;
-    f32x4 acc[MT][8];
+  f32x4 acc[MT][8];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+  for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-      for (int cc = 0; cc < 8; ++cc) acc[mt][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    int jb = 0;
-    for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
-    if (jb < r) expand_mfma_kstep<DT, MT, true>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
-
-    if (ok) {
+    for (int cc = 0; cc < 8; ++cc) acc[mt][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+  int jb = 0;
+  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+  if (jb < r) expand_mfma_kstep<DT, MT, true>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+  if (!ok) return;
 #pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        uint4 yq[4];
+  for (int mt = 0; mt < MT; ++mt) {
+    uint4 yq[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) yq[i] = ld16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB);
+    for (int i = 0; i < 4; ++i) yq[i] = ld16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const int ti = mt * 16 + g * 4 + i;
-          if (ti < it.ntok) {
-            float yf[8];
-            unpack<DT>(yq[i], yf);
+    for (int i = 0; i < 4; ++i) {
+      if (mt * 16 + g * 4 + i < it.ntok) {
+        float yf[8];
+        unpack<DT>(yq[i], yf);
 #pragma unroll
-            for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
-            st16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
-          }
-        }
+        for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
+        st16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
       }
     }
   }
 }
 
+// expand, matrix-core item: D[token, col] += V[token, j] * B[j, col] for up to 64 tokens x 512
+// columns, by a workgroup of 4 wavefronts with B held stationary in LDS.  The 512 columns are done as
+// two halves of 256; rows of B in panels of 64.  For a panel the 4 wavefronts each fetch one
+// 32-row x 128-column tile of B (8 loads of 16 bytes per lane: lane (g, c) gets the 8x8 block rows
+// 8 g .. 8 g + 7 x columns 8 c .. 8 c + 7), transpose it in registers into eight 8-value K-vectors
+// (one per column offset cc) and park them in LDS in MFMA operand order.  Then wavefront w multiplies
+// token tile w (16 tokens) against all four tiles: MFMA cc of a tile yields the real columns
+// 8 c + cc, so a lane ends with 8 consecutive columns of y for each of its 4 token rows and updates
+// y with 16-byte read-modify-writes.  B is read once per 64 tokens; v goes in as hi + lo 16-bit
+// halves (two MFMAs) so that fp32 v loses nothing that matters.  Items of at most 32 tokens take the
+// column-split form above instead.
+static_assert(kMfmaTokE == 64 || kMfmaTokE == 32 || kMfmaTokE == 16, "host work items must match the kernel's tiles");
+
 template <int DT>
-__device__ __forceinline__ void expand_mfma_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
-                                                 const float* v, uint8_t* y, int2* lds_pg) {
-  if constexpr (DT == 2) return;
-  else {
-    if (kMfmaTokE <= 16 || it.ntok <= 16) expand_mfma_body<DT, 1>(a, it, sl, v, y, lds_pg);
-    else expand_mfma_body<DT, 2>(a, it, sl, v, y, lds_pg);
+__device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+                                                  const float* __restrict__ v, uint8_t* __restrict__ y,
+                                                  uint4 (*op)[8][kWave], int2* lds_pg, int chunk) {
+  constexpr int EB = 2;
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int g = lane >> 4, c = lane & 15;
+  const int r = it.rank, d_out = sl.d_out, vs = a.v_stride, lp = a.log2_page;
+  const int n0i = chunk * 512;
+  if (n0i >= d_out) return;  // uniform over the workgroup
+  const uint32_t pmask = (1u << lp) - 1;
+  const uint64_t rowb = (uint64_t)d_out * EB;
+  const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0i * EB;
+  {  // page pairs of every row's 1 KiB piece, by all 256 threads
+    const int n_pt = table_len(a, r, EB);
+    const int32_t* ptg = a.pt + it.pt_off;
+    for (int j = tid; j < r; j += 256) {
+      const uint64_t vo = base + (uint64_t)j * rowb;
+      const uint32_t q0 = (uint32_t)(vo >> lp);
+      const uint32_t q1 = imin((int)((vo + 1023) >> lp), n_pt - 1);
+      lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
+    }
   }
+  if (kMfmaTokE <= 32 || it.ntok <= 32) {  // uniform: few tokens -> split the columns, not the tokens
+    __syncthreads();
+    if (kMfmaTokE <= 16 || it.ntok <= 16) expand_mfma_cols_body<DT, 1>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+    else expand_mfma_cols_body<DT, 2>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+    return;
+  }
+  if constexpr (kMfmaTokE > 32) {
+  const int32_t* perm = a.perm + it.tok[0];
+  const bool has_tok = wave * 16 < it.ntok;            // this wavefront owns token tile `wave`
+  const int tc = perm[imin(wave * 16 + c, it.ntok - 1)];  // token of operand row c
+  const float* vrow = v + (int64_t)tc * vs;
+  int64_t trow[4];                                       // tokens of the result rows this lane holds
+#pragma unroll
+  for (int i = 0; i < 4; ++i) trow[i] = __shfl(tc, g * 4 + i, 64);
+  __syncthreads();
+
+  const int ks_w = wave >> 1, ct_w = wave & 1;  // the tile this wavefront stages: K-step in panel, column tile
+  for (int half = 0; half < 2; ++half) {
+    const int nh0 = n0i + half * 256;
+    if (nh0 >= d_out) break;
+    f32x4 acc[2][8];
+#pragma unroll
+    for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+      for (int cc = 0; cc < 8; ++cc) acc[ct][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    for (int j0 = 0; j0 < r; j0 += 64) {
+      {  // stage tile (ks_w, ct_w) of this panel
+        const int ncol = nh0 + ct_w * 128 + 8 * c;
+        const bool okc = ncol < d_out;
+        const uint32_t lane_b = okc ? (uint32_t)((half * 256 + ct_w * 128) * EB + c * 16) : 0;
+        const int j8 = j0 + ks_w * 32 + 8 * g;
+        uint4 wr[8];
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj) {
+          const int je = imin(j8 + jj, r - 1);
+          const uint64_t vo = base + (uint64_t)je * rowb;
+          const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
+          const int2 pp = lds_pg[je];
+          const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
+          wr[jj] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+        }
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj)
+          if (j8 + jj >= r || !okc) wr[jj] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const uint32_t r0 = (&wr[0].x)[d], r1 = (&wr[1].x)[d], r2 = (&wr[2].x)[d], r3 = (&wr[3].x)[d];
+          const uint32_t r4 = (&wr[4].x)[d], r5 = (&wr[5].x)[d], r6 = (&wr[6].x)[d], r7 = (&wr[7].x)[d];
+          op[wave][2 * d][lane] =
+              make_uint4(__builtin_amdgcn_perm(r1, r0, 0x05040100u), __builtin_amdgcn_perm(r3, r2, 0x05040100u),
+                         __builtin_amdgcn_perm(r5, r4, 0x05040100u), __builtin_amdgcn_perm(r7, r6, 0x05040100u));
+          op[wave][2 * d + 1][lane] =
+              make_uint4(__builtin_amdgcn_perm(r1, r0, 0x07060302u), __builtin_amdgcn_perm(r3, r2, 0x07060302u),
+                         __builtin_amdgcn_perm(r5, r4, 0x07060302u), __builtin_amdgcn_perm(r7, r6, 0x07060302u));
+        }
+      }
+      __syncthreads();
+      if (has_tok) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+          const int jv = j0 + ks * 32 + 8 * g;
+          if (j0 + ks * 32 < r) {  // uniform
+            float vf[8];
+            if (jv + 8 <= r && (vs & 3) == 0) {
+              const float4 va = *reinterpret_cast<const float4*>(vrow + jv);
+              const float4 vb = *reinterpret_cast<const float4*>(vrow + jv + 4);
+              vf[0] = va.x; vf[1] = va.y; vf[2] = va.z; vf[3] = va.w; vf[4] = vb.x; vf[5] = vb.y; vf[6] = vb.z; vf[7] = vb.w;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) vf[e] = (jv + e < r) ? vrow[jv + e] : 0.f;
+            }
+            uint4 vhi, vlo;
+            split_hi_lo<DT>(vf, vhi, vlo);
+#pragma unroll
+            for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+              for (int cc = 0; cc < 8; ++cc) {
+                const uint4 w = op[ks * 2 + ct][cc][lane];
+                acc[ct][cc] = mfma16<DT>(vhi, w, acc[ct][cc]);
+                acc[ct][cc] = mfma16<DT>(vlo, w, acc[ct][cc]);
+              }
+          }
+        }
+      }
+      __syncthreads();
+    }
+    if (has_tok) {
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        const int n = nh0 + ct * 128 + 8 * c;
+        if (n < d_out) {
+          uint4 yq[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) yq[i] = ld16(y + ((uint64_t)trow[i] * d_out + n) * EB);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            if (wave * 16 + g * 4 + i < it.ntok) {
+              float yf[8];
+              unpack<DT>(yq[i], yf);
+#pragma unroll
+              for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[ct][cc][i];
+              st16(y + ((uint64_t)trow[i] * d_out + n) * EB, pack<DT>(yf));
+            }
+          }
+        }
+      }
+    }
+  }
+  }  // kMfmaTokE > 32
 }
 
 // Shrink: workgroups of 4 wavefronts.  The work list is a sequence of blocks of 4 records: either
@@ -652,7 +782,7 @@ __device__ __forceinline__ void expand_mfma_item(const LaunchArgs& a, const Item
 // the list, so their long dependent chains start first and the short items fill the machine around
 // and after them in the same launch.
 template <int DT>
-__global__ __launch_bounds__(256) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
+__global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
   __shared__ __align__(16) uint8_t tile[4][2][kSmRows * kSmPitch];  // [wavefront][A | x]
   __shared__ int32_t lds_pt[kPtWindow];
   const int blk = a.slot_fastest ? blockIdx.z : blockIdx.x;
@@ -673,30 +803,32 @@ __global__ __launch_bounds__(256) void k_shrink(const LaunchArgs a, const SlotPt
   shrink_valu_item<DT>(a, it, sl, x, v, lds_pt + wave * (kPtWindow / 4));
 }
 
-// KIND 0: vector-ALU items only, 1: matrix-core items only, 2: mixed list.
-template <int DT, int KIND>
-__global__ __launch_bounds__(kWave) void k_expand(const LaunchArgs a, const SlotPtrs p) {
+// Expand: same block structure as shrink (one matrix-core item per workgroup, or up to 4
+// independent vector-ALU items, one per wavefront); the column chunk (512 columns) comes from the
+// grid.
+template <int DT>
+__global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ __align__(16) uint4 op[4][8][kWave];  // 4 staged tiles of B in MFMA operand order (32 KiB)
   __shared__ int2 lds_pg[kMaxRank];
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
-  if (it.kind < 0) return;
+  const int blk = a.slot_fastest ? blockIdx.y : blockIdx.x;
+  const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[a.slot0 + q];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
-  if constexpr (KIND == 0) expand_valu_item<DT>(a, it, sl, v, y, lds_pg);
-  else if constexpr (KIND == 1) expand_mfma_item<DT>(a, it, sl, v, y, lds_pg);
-  else {
-    if (it.kind) expand_mfma_item<DT>(a, it, sl, v, y, lds_pg);
-    else expand_valu_item<DT>(a, it, sl, v, y, lds_pg);
+  const ItemRec first = a.items[4 * blk];
+  if constexpr (DT != 2) {
+    if (first.kind == 1) {
+      expand_mfma4_body<DT>(a, first, sl, v, y, op, lds_pg, chunk);
+      return;
+    }
   }
-}
-
-template <int KIND>
-void launch_expand_k(int dtype, dim3 grid, hipStream_t st, const LaunchArgs& a, const SlotPtrs& p) {
-  const dim3 block(kWave);
-  if (dtype == 0) hipLaunchKernelGGL((k_expand<0, KIND>), grid, block, 0, st, a, p);
-  else if (dtype == 1) hipLaunchKernelGGL((k_expand<1, KIND>), grid, block, 0, st, a, p);
-  else hipLaunchKernelGGL((k_expand<2, KIND>), grid, block, 0, st, a, p);
+  const int wave = threadIdx.x >> 6;
+  const ItemRec it = a.items[4 * blk + wave];
+  if (it.kind < 0) return;  // this path has no workgroup barrier: a wavefront may leave alone
+  // each wavefront stages its row pages in its own part of LDS: the operand tiles are unused here
+  int2* my_pg = reinterpret_cast<int2*>(&op[wave][0][0]);
+  expand_valu_item<DT>(a, it, sl, v, y, my_pg, chunk);
 }
 
 }  // namespace
@@ -719,20 +851,21 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
   return hipGetLastError();
 }
 
-hipError_t launch_expand(int dtype, int kind, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks,
+hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks,
                          hipStream_t st) {
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
-  if (dtype == 2 && kind == 1) return hipErrorInvalidValue;
-  if (max_chunks > 65535) return hipErrorInvalidValue;
+  if (a0.n_items % 4 || max_chunks > 65535) return hipErrorInvalidValue;
   LaunchArgs a = a0;
-  const int step = a0.slot_fastest ? 65535 : a0.n_items;
-  for (int first = 0; first < a0.n_items; first += step) {
-    a.items = a0.items + first;
-    a.n_items = a0.n_items - first < step ? a0.n_items - first : step;
-    const dim3 grid = a.slot_fastest ? dim3(n_slots, a.n_items, max_chunks) : dim3(a.n_items, max_chunks, n_slots);
-    if (kind == 0) launch_expand_k<0>(dtype, grid, st, a, p);
-    else if (kind == 1) launch_expand_k<1>(dtype, grid, st, a, p);
-    else launch_expand_k<2>(dtype, grid, st, a, p);
+  const int n_blocks = a0.n_items / 4;
+  const int step = a0.slot_fastest ? 65535 : n_blocks;  // grid.y is limited to 65535
+  for (int first = 0; first < n_blocks; first += step) {
+    const int nb = n_blocks - first < step ? n_blocks - first : step;
+    a.items = a0.items + 4 * first;
+    a.n_items = 4 * nb;
+    const dim3 grid = a.slot_fastest ? dim3(n_slots, nb, max_chunks) : dim3(nb, max_chunks, n_slots);
+    if (dtype == 0) hipLaunchKernelGGL(k_expand<0>, grid, dim3(256), 0, st, a, p);
+    else if (dtype == 1) hipLaunchKernelGGL(k_expand<1>, grid, dim3(256), 0, st, a, p);
+    else hipLaunchKernelGGL(k_expand<2>, grid, dim3(256), 0, st, a, p);
   }
   return hipGetLastError();
 }

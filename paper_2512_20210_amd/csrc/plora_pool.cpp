@@ -59,11 +59,11 @@ struct plora_batch {
   size_t cap = 0;
   // offsets inside the image
   size_t off_perm = 0, off_pt = 0;
-  // work lists: [op][kind + 3 * layout], op 0 = shrink, 1 = expand; kind 0 = vector-ALU items,
-  // 1 = matrix-core items, 2 = both (single-launch mode); layout 0 = longest first (for launches
-  // whose fastest grid dimension is the slot), 1 = dealt into 8 interleaved XCD queues
-  size_t off_items[2][6] = {{0}, {0}};
-  int32_t n_items[2][6] = {{0}, {0}};
+  // work lists (blocks of 4 records): [op][layout], op 0 = shrink, 1 = expand; layout 0 = longest
+  // first (for launches whose fastest grid dimension is the slot), 1 = dealt into 8 interleaved XCD
+  // queues
+  size_t off_items[2][2] = {{0, 0}, {0, 0}};
+  int32_t n_items[2][2] = {{0, 0}, {0, 0}};
   std::vector<int32_t> adapters;      // pinned adapters
   std::shared_ptr<Event> done;        // recorded by plora_batch_end; the images are reusable once it has passed
   hipEvent_t ev_img = nullptr;        // the image has arrived on the device (recorded on the pool's aux stream)
@@ -90,8 +90,8 @@ struct plora_pool {
   int open_batches = 0;
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
   // tunables
-  int mfma_min_tokens = 5;
-  int fused = 1;      // 1: one launch per call over the mixed item list
+  int mfma_min_tokens = 5;          // shrink: groups of at least this many tokens take matrix-core items
+  int mfma_min_tokens_expand = 16;  // expand: likewise (its vector-ALU items stay ahead for longer)
   int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
@@ -131,43 +131,12 @@ struct Group {
   bool heavy = false;
 };
 
-// Lays the items out in launch order.  Workgroup i of a launch runs on XCD i % 8, so with
-// xcd_aware the groups are spread over 8 queues (longest first, each to the least loaded queue)
-// and the queues are interleaved; queues that run out are padded with empty items.  Otherwise:
-// heavy groups first, then the rest, in group order.
-void arrange(std::vector<Group>& groups, bool xcd_aware, std::vector<ItemRec>& out) {
-  out.clear();
-  std::vector<const Group*> order;
-  for (const Group& g : groups) if (!g.items.empty()) order.push_back(&g);
-  std::stable_sort(order.begin(), order.end(), [&](const Group* a, const Group* b) {
-    if (a->heavy != b->heavy) return a->heavy;
-    return xcd_aware && a->cost > b->cost;
-  });
-  if (!xcd_aware) {
-    for (const Group* g : order) out.insert(out.end(), g->items.begin(), g->items.end());
-    return;
-  }
-  std::vector<ItemRec> q[kXcds];
-  double load[kXcds] = {0};
-  for (const Group* g : order) {
-    int best = 0;
-    for (int k = 1; k < kXcds; ++k) if (load[k] < load[best]) best = k;
-    q[best].insert(q[best].end(), g->items.begin(), g->items.end());
-    load[best] += g->cost;
-  }
-  size_t longest = 0;
-  for (int k = 0; k < kXcds; ++k) longest = std::max(longest, q[k].size());
-  ItemRec pad{};
-  pad.kind = -1;
-  for (size_t i = 0; i < longest; ++i)
-    for (int k = 0; k < kXcds; ++k) out.push_back(i < q[k].size() ? q[k][i] : pad);
-}
-
-
-// Shrink work list: blocks of 4 records, one 256-thread workgroup each.  A matrix-core item fills a
+// Work list of a kernel: blocks of 4 records, one 256-thread workgroup each.  Workgroup i of a launch
+// runs on XCD i % 8.  A matrix-core item fills a
 // block alone (3 padding records); vector-ALU items go four to a block, one per wavefront.
 // Matrix-core blocks first (their dependent chains are the long ones).  With xcd_aware the groups
-// are dealt into 8 queues as in arrange() and the queues are interleaved block by block.
+// are dealt into 8 queues (longest first, each to the least loaded queue) and the queues are
+// interleaved block by block; queues that run out are padded with empty blocks.
 void arrange_blocks(const std::vector<Group>& heavy, const std::vector<Group>& light, bool xcd_aware,
                     std::vector<ItemRec>& out) {
   out.clear();
@@ -190,6 +159,11 @@ void arrange_blocks(const std::vector<Group>& heavy, const std::vector<Group>& l
   };
   deal(heavy, qh);
   deal(light, ql);
+  // The 4 wavefronts of a block hold their workgroup's resources until the last one ends: put items
+  // of similar length together (longest first; equal ranks keep their order, so the token groups of
+  // one adapter stay neighbours).
+  for (int k = 0; k < nq; ++k)
+    std::stable_sort(ql[k].begin(), ql[k].end(), [](const ItemRec& x, const ItemRec& y) { return x.rank > y.rank; });
   std::vector<std::vector<ItemRec>> blocks(nq);  // per queue, 4 records per block
   size_t longest = 0;
   for (int k = 0; k < nq; ++k) {
@@ -430,14 +404,14 @@ int plora_pool_stats(plora_pool* p, plora_stats* o) {
 int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
   if (!p || !key) return PLORA_ERR_INVAL;
   const std::string k(key);
-  if (k == "mfma_min_tokens") {
+  if (k == "mfma_min_tokens" || k == "mfma_min_tokens_expand") {
     if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
-    p->mfma_min_tokens = (int)value;
+    (k == "mfma_min_tokens" ? p->mfma_min_tokens : p->mfma_min_tokens_expand) = (int)value;
     return PLORA_OK;
   }
-  if (k == "fused" || k == "xcd_remap") {
+  if (k == "xcd_remap") {
     if (value != 0 && value != 1) return PLORA_ERR_INVAL;
-    (k == "fused" ? p->fused : p->xcd_remap) = (int)value;
+    p->xcd_remap = (int)value;
     return PLORA_OK;
   }
   if (k == "slot_major") {
@@ -507,7 +481,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   }
 
   // work items, grouped per adapter (tokens without adapter form one rank-0 group: shrink clears their v rows)
-  const bool mfma_ok = p->dtype != PLORA_F32 && p->mfma_min_tokens > 0;
+  const bool mfma_ok = p->dtype != PLORA_F32;  // matrix-core items exist for the 16-bit element types
   std::vector<Group> grp[2][2];  // [op][kind]
   size_t n_pt_total = 0;
   for (int32_t u = 0; u < n_seg; ++u) {
@@ -517,31 +491,39 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     const int32_t pt_off = (int32_t)n_pt_total;
     n_pt_total += a.pt.size();
     const int16_t rank = (int16_t)a.rank;
-    if (mfma_ok && n >= p->mfma_min_tokens) {
-      // Large groups (prefill) are cut into blocks of kTokBlock tokens: a block is the unit that is
-      // dealt to an XCD, and inside a block the items go row group by row group with the token
-      // groups innermost, so a tile of A is re-read back to back and the block's x tiles (at most
-      // kTokBlock rows) stay in L2 for the next row group.
-      constexpr int kTokBlock = 128;
-      for (int32_t b0 = 0; b0 < n; b0 += kTokBlock) {
-        const int32_t b1 = std::min(n, b0 + kTokBlock);
-        Group gs, ge;
-        gs.heavy = ge.heavy = true;
+    const bool mf_s = mfma_ok && p->mfma_min_tokens > 0 && n >= p->mfma_min_tokens;
+    const bool mf_e = mfma_ok && p->mfma_min_tokens_expand > 0 && n >= p->mfma_min_tokens_expand;
+    // Matrix-core items.  Large groups (prefill) are cut into blocks of kTokBlock tokens: a block is
+    // the unit that is dealt to an XCD, and inside a block the shrink items go row group by row
+    // group with the token groups innermost, so a tile of A is re-read back to back and the block's
+    // x tiles (at most kTokBlock rows) stay in L2 for the next row group.
+    constexpr int kTokBlock = 128;
+    for (int32_t b0 = 0; b0 < n && (mf_s || mf_e); b0 += kTokBlock) {
+      const int32_t b1 = std::min(n, b0 + kTokBlock);
+      if (mf_s) {
+        Group gs;
+        gs.heavy = true;
         for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
           for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokS) {
             const int16_t nt = (int16_t)std::min(kMfmaTokS, b1 - t0);
             gs.items.push_back(ItemRec{1, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
             gs.cost += std::min(kMfmaRows, a.rank - j0) + nt;
           }
+        grp[0][1].push_back(std::move(gs));
+      }
+      if (mf_e) {
+        Group ge;
+        ge.heavy = true;
         for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokE) {
           const int16_t nt = (int16_t)std::min(kMfmaTokE, b1 - t0);
           ge.items.push_back(ItemRec{1, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
           ge.cost += a.rank + 2 * nt;
         }
-        grp[0][1].push_back(std::move(gs));
         grp[1][1].push_back(std::move(ge));
       }
-    } else {
+    }
+    // Vector-ALU items.
+    if (!mf_s || !mf_e) {
       Group gs, ge;
       std::vector<ItemRec> tg;  // one record per token group
       for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
@@ -549,19 +531,22 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
         ItemRec it{0, nt, rank, 0, a.scale, pt_off, {0, 0, 0, 0}};
         for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
         tg.push_back(it);
-        ge.items.push_back(it);
-        ge.cost += a.rank + 2 * nt;
+        if (!mf_e) {
+          ge.items.push_back(it);
+          ge.cost += a.rank + 2 * nt;
+        }
       }
       // shrink: token groups innermost, so that the re-read of a row block by the next token
       // group follows closely and finds the rows in L2
-      for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
-        for (ItemRec it : tg) {
-          it.j0 = (int16_t)j0;
-          gs.items.push_back(it);
-          gs.cost += std::min(kShrinkRows, a.rank - j0) + it.ntok;
-        }
-      grp[0][0].push_back(std::move(gs));
-      grp[1][0].push_back(std::move(ge));
+      if (!mf_s)
+        for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
+          for (ItemRec it : tg) {
+            it.j0 = (int16_t)j0;
+            gs.items.push_back(it);
+            gs.cost += std::min(kShrinkRows, a.rank - j0) + it.ntok;
+          }
+      if (!gs.items.empty()) grp[0][0].push_back(std::move(gs));
+      if (!ge.items.empty()) grp[1][0].push_back(std::move(ge));
     }
   }
   if (n_none > 0) {
@@ -575,19 +560,9 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     }
     grp[0][0].push_back(std::move(gs));
   }
-  std::vector<ItemRec> lists[2][6];
-  for (int lay = 0; lay < 2; ++lay) arrange_blocks(grp[0][1], grp[0][0], lay != 0, lists[0][3 * lay]);
-  for (int op = 1; op < 2; ++op) {
-    std::vector<Group> both;
-    both.reserve(grp[op][0].size() + grp[op][1].size());
-    for (const Group& g : grp[op][1]) both.push_back(g);
-    for (const Group& g : grp[op][0]) both.push_back(g);
-    for (int lay = 0; lay < 2; ++lay) {
-      arrange(grp[op][0], lay != 0, lists[op][0 + 3 * lay]);
-      arrange(grp[op][1], lay != 0, lists[op][1 + 3 * lay]);
-      arrange(both, lay != 0, lists[op][2 + 3 * lay]);
-    }
-  }
+  std::vector<ItemRec> lists[2][2];  // [op][layout]
+  for (int op = 0; op < 2; ++op)
+    for (int lay = 0; lay < 2; ++lay) arrange_blocks(grp[op][1], grp[op][0], lay != 0, lists[op][lay]);
   for (int32_t i : touched) p->count[i] = 0;
 
   // image layout
@@ -595,7 +570,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   b->off_perm = off; off = align_up(off + (size_t)T * 4, 256);
   b->off_pt = off; off = align_up(off + (n_pt_total + 1) * 4, 256);
   for (int op = 0; op < 2; ++op)
-    for (int k = 0; k < 6; ++k) {
+    for (int k = 0; k < 2; ++k) {
       b->off_items[op][k] = off; b->n_items[op][k] = (int32_t)lists[op][k].size();
       off = align_up(off + lists[op][k].size() * sizeof(ItemRec), 256);
     }
@@ -626,7 +601,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     *dst = 0;
   }
   for (int op = 0; op < 2; ++op)
-    for (int k = 0; k < 6; ++k)
+    for (int k = 0; k < 2; ++k)
       if (!lists[op][k].empty())
         std::memcpy(b->h_img + b->off_items[op][k], lists[op][k].data(), lists[op][k].size() * sizeof(ItemRec));
   b->perm.resize(n_perm);
@@ -695,37 +670,24 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     a.pad = 0;
     const int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
     const int chunks = (max_out + kWave * vec - 1) / (kWave * vec);
-    // shrink: one launch over the block list; expand: the mixed list in one launch, or matrix-core
-    // items (the long ones) first and then the rest
-    struct L { int kind, cls; };
-    L ls[2];
-    int nl = 0;
-    if (is_shrink) ls[nl++] = L{0, 4};
-    else if (p->fused) ls[nl++] = L{2, 5};
-    else {
-      ls[nl++] = L{1, 3};
-      ls[nl++] = L{0, 2};
+    a.items = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
+    a.n_items = b->n_items[op][layout];
+    if (a.n_items == 0) continue;
+    plora_pool::ProfRec rec{op, nullptr, nullptr};
+    if (p->profiling) {
+      for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
+        if (!p->prof_free.empty()) { *ev = p->prof_free.back(); p->prof_free.pop_back(); }
+        else HIP_TRY(hipEventCreate(ev));
+      }
+      HIP_TRY(hipEventRecord(rec.e0, (hipStream_t)s));
     }
-    for (int li = 0; li < nl; ++li) {
-      a.items = (const ItemRec*)(b->d_img + b->off_items[op][ls[li].kind + 3 * layout]);
-      a.n_items = b->n_items[op][ls[li].kind + 3 * layout];
-      if (a.n_items == 0) continue;
-      plora_pool::ProfRec rec{ls[li].cls, nullptr, nullptr};
-      if (p->profiling) {
-        for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
-          if (!p->prof_free.empty()) { *ev = p->prof_free.back(); p->prof_free.pop_back(); }
-          else HIP_TRY(hipEventCreate(ev));
-        }
-        HIP_TRY(hipEventRecord(rec.e0, (hipStream_t)s));
-      }
-      hipError_t e;
-      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, (hipStream_t)s);
-      else e = launch_expand(p->dtype, ls[li].kind, a, ptrs, nq, chunks, (hipStream_t)s);
-      HIP_TRY(e);
-      if (p->profiling) {
-        HIP_TRY(hipEventRecord(rec.e1, (hipStream_t)s));
-        p->prof.push_back(rec);
-      }
+    hipError_t e;
+    if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, (hipStream_t)s);
+    else e = launch_expand(p->dtype, a, ptrs, nq, chunks, (hipStream_t)s);
+    HIP_TRY(e);
+    if (p->profiling) {
+      HIP_TRY(hipEventRecord(rec.e1, (hipStream_t)s));
+      p->prof.push_back(rec);
     }
   }
   return PLORA_OK;
@@ -749,7 +711,7 @@ int plora_profile(plora_pool* p, int enable) {
 
 int plora_profile_read(plora_pool* p, double* ms, uint64_t* launches) {
   if (!p || !ms || !launches || p->placement_only) return PLORA_ERR_INVAL;
-  for (int k = 0; k < 6; ++k) { ms[k] = 0.0; launches[k] = 0; }
+  for (int k = 0; k < 2; ++k) { ms[k] = 0.0; launches[k] = 0; }
   for (auto& r : p->prof) {
     HIP_TRY(hipEventSynchronize(r.e1));
     float t = 0.f;

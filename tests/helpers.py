@@ -54,11 +54,16 @@ class Case:
         self.opool = oracle_mod.OraclePool(page_bytes, n_pages, layout.d_in, layout.d_out, layout.dtype, na, self.max_rank)
         self.gpool = P.PagedLoraPool(page_bytes, n_pages, layout.d_in, layout.d_out, layout.dtype, na, self.max_rank)
         if mfma_min_tokens is not None:
-            self.gpool.set_option("mfma_min_tokens", mfma_min_tokens)
+            self.set_mfma(mfma_min_tokens)
         self.stream = torch.cuda.current_stream().cuda_stream
         self.copy_stream = torch.cuda.Stream()
         for i in (load_order if load_order is not None else range(len(ranks))):
             self.load(i)
+
+    def set_mfma(self, n, n_expand=None):
+        """Threshold (tokens per adapter group) of the matrix-core items in shrink and in expand."""
+        self.gpool.set_option("mfma_min_tokens", n)
+        self.gpool.set_option("mfma_min_tokens_expand", n if n_expand is None else n_expand)
 
     def load(self, i):
         pt_o = self.opool.load(i, self.ranks[i], self.scales[i], self.blobs[i])

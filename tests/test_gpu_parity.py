@@ -16,9 +16,9 @@ def test_cfg0_small_workload(oracle_mod):
     rng = np.random.default_rng(cfg["seed"])
     t2a = draw_tok2adapter(rng, cfg["tokens"], np.arange(4), s=None)
     print("cfg0 t2a", t2a.tolist(), flush=True)
-    for mfma, fused, remap in ((0, 0, 1), (1, 0, 1), (4, 1, 1), (2, 1, 0), (1, 0, 0)):
-        case.gpool.set_option("mfma_min_tokens", mfma)
-        case.gpool.set_option("fused", fused)
+    for mfma, major, remap in ((0, -1, 1), (1, 0, 1), (4, 1, 1), (2, 0, 0), (1, 1, 0)):
+        case.set_mfma(mfma, 0 if mfma == 4 else mfma)
+        case.gpool.set_option("slot_major", major)
         case.gpool.set_option("xcd_remap", remap)
         out = case.run(t2a, seed=1)
         print("mfma_min", mfma, "err_v %.3g err_y %.3g" % (out[0]["err_v"], out[0]["err_y"]), flush=True)
@@ -29,8 +29,8 @@ def test_cfg0_small_workload(oracle_mod):
 
 
 @pytest.mark.parametrize("dtype", [DT_BF16, DT_F16, DT_F32])
-@pytest.mark.parametrize("mfma,fused", [(0, 0), (1, 0), (3, 1)])
-def test_ragged_multi_slot(oracle_mod, dtype, mfma, fused):
+@pytest.mark.parametrize("mfma,major", [(0, -1), (1, 0), (3, 1)])
+def test_ragged_multi_slot(oracle_mod, dtype, mfma, major):
     """Several tiles and ragged tails everywhere: d not a multiple of the wave width, ranks 1..40
     (not multiples of 8), rows straddling 4 KiB pages, tokens without adapter, scattered pages."""
     lay = Layout((1000, 520, 72), (264, 1304, 8), dtype)
@@ -38,7 +38,7 @@ def test_ragged_multi_slot(oracle_mod, dtype, mfma, fused):
     scales = [16.0 / r for r in ranks]
     case = Case(oracle_mod, lay, ranks, scales, 4096, 1024, seed=77, load_order=[4, 0, 6, 2, 1, 7, 3, 5],
                 mfma_min_tokens=mfma)
-    case.gpool.set_option("fused", fused)
+    case.gpool.set_option("slot_major", major)
     # scatter: evict two adapters and reload them so that their pages interleave
     case.evict(0)
     case.evict(6)

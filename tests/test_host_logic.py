@@ -144,13 +144,13 @@ def test_pool_create_rejects_bad_arguments():
                 dict(d_in=[1 << 20], d_out=[64]),  # 64 rows of 2 MiB over 4 KiB pages: window too large
                 ):
         assert create(**bad) == B.PLORA_ERR_INVAL, bad
-    assert B.plora_pool_set_option(None, "fused", 1) == B.PLORA_ERR_INVAL
+    assert B.plora_pool_set_option(None, "xcd_remap", 1) == B.PLORA_ERR_INVAL
 
 
 def test_options_validate():
     import paper_2512_20210_amd as B
     g = B.PagedLoraPool(4096, 4, [64], [64], B.PLORA_BF16, 4, 16, placement_only=True)
-    for key, good, bad in (("mfma_min_tokens", 3, -1), ("fused", 0, 2), ("xcd_remap", 1, 5), ("slot_major", -1, 2)):
+    for key, good, bad in (("mfma_min_tokens", 3, -1), ("mfma_min_tokens_expand", 0, -2), ("xcd_remap", 1, 5), ("slot_major", -1, 2)):
         assert B.plora_pool_set_option(g.h, key, good) == B.PLORA_OK
         assert B.plora_pool_set_option(g.h, key, bad) == B.PLORA_ERR_INVAL
     assert B.plora_pool_set_option(g.h, "no_such_option", 1) == B.PLORA_ERR_INVAL
