@@ -25,6 +25,10 @@ from workload import (CONFIGS, RAW_DTYPE, config_layout, draw_ranks, draw_tok2ad
                       prefill_requests, to_elt)
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+# HBM bytes per launch of the (shrink, expand) kernels measured with rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE (scaled by the factors found on a copy kernel of known size: 2.0 and 1.0); sources:
+# profiles/decode_7b_cfg1_*.md, profiles/decode_13b_layer_cfg4_*.md, profiles/prefill_cfg2_*.md
+MEASURED_TRAFFIC = {"cfg1": (1.818e9, 2.162e9), "cfg4": (2.335e9, 2.418e9), "cfg2": (0.252e9, 0.406e9)}
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
 KCLASS = ["shrink", "expand"]
 
@@ -72,7 +76,7 @@ def algorithmic_bytes(lay, ranks, t2a, slots):
 class GpuWorkload:
     """Pool with all adapters resident + per-slot activation buffers on the device."""
 
-    def __init__(self, name, workers=16, verbose=False):
+    def __init__(self, name, workers=16, verbose=False, scatter=False):
         import torch
         import paper_2512_20210_amd as P
         self.torch, self.P, self.name = torch, P, name
@@ -96,6 +100,22 @@ class GpuWorkload:
         self.copy_stream.synchronize()
         self.t_load = time.perf_counter() - t0
         self.stats_after_load = self.pool.stats()
+        if scatter:
+            # evict / reload in shuffled order twice, so that every adapter's pages are scattered
+            # over the slab in short runs (the kernels then translate across many more page breaks)
+            rs = np.random.default_rng(cfg["seed"] + 5)
+            for rnd in range(2):
+                ids = [i for i in range(self.n_ad) if i % 2 == rnd]
+                rs.shuffle(ids)
+                small_first = sorted(ids, key=lambda i: int(self.ranks[i]))
+                for i in ids:
+                    self.pool.evict(i)
+                for i in (small_first if rnd == 0 else small_first[::-1]):
+                    self.tables[i] = self.pool.load(i, int(self.ranks[i]), self.scales[i], self.pinned[i],
+                                                    self.copy_stream.cuda_stream)
+                self.copy_stream.synchronize()
+        runs = sum(int((np.diff(t) != 1).sum()) + 1 for t in self.tables)
+        self.mean_run_pages = sum(len(t) for t in self.tables) / runs
         if verbose:
             st = self.stats_after_load
             print("[bench] %s: %d adapters, %.2f GB in %d pages of %d KiB; generated in %.1fs; H2D %.2f GB/s wall "
@@ -314,6 +334,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--same-batch", action="store_true", help="reuse one token->adapter draw for every step")
+    ap.add_argument("--scatter", action="store_true", help="evict and reload adapters so that their pages are scattered")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -328,7 +349,7 @@ def main():
         run_churn(args)
         return
 
-    w = GpuWorkload(args.workload, verbose=args.verbose)
+    w = GpuWorkload(args.workload, verbose=args.verbose, scatter=args.scatter)
     cfg, lay = w.cfg, w.lay
     if args.mfma_min_tokens >= 0:
         w.pool.set_option("mfma_min_tokens", args.mfma_min_tokens)
@@ -375,8 +396,9 @@ def main():
         avg_ms = kms[dom] / kn[dom]
         per_launch = kb / kn[dom]
         ach = per_launch / (avg_ms * 1e-3) / 1e9
+        traffic = MEASURED_TRAFFIC.get(args.workload) if spc == lay.n_slots else None
         roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=None, avg_launch_ms=round(avg_ms, 5),
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=int(traffic[dom]) if traffic else None, avg_launch_ms=round(avg_ms, 5),
                     launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
                     all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(2) if kn[k]})
 
@@ -388,7 +410,7 @@ def main():
         "config": {"workload": args.workload, "slots": lay.n_slots, "tokens": int(T), "adapters": int(w.n_ad),
                    "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc),
                    "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1),
-                   "activation_sets": len(w.act_sets), "activation_bytes_per_set": int(w.act_bytes)},
+                   "mean_run_of_consecutive_pages": round(w.mean_run_pages, 1), "activation_sets": len(w.act_sets), "activation_bytes_per_set": int(w.act_bytes)},
         "tokens_per_s": round(tokens_total / elapsed, 1),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_step": int(bytes_total / args.steps),
