@@ -116,3 +116,36 @@ def test_error_paths_on_gpu(oracle_mod):
     assert P.plora_evict(g.h, 0) == P.PLORA_OK
     assert P.plora_evict(g.h, 0) == P.PLORA_ERR_NOTFOUND
     case.close()
+
+
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F16])
+def test_large_groups_panels_and_odd_strides(oracle_mod, dtype):
+    """Prefill-like groups (hundreds of tokens per adapter) through the token-split matrix-core
+    expand and the split-K matrix-core shrink, with a row stride of v that is not a multiple of 4,
+    ragged widths and ranks, 2 MiB pages (the paper's default page size)."""
+    lay = Layout((1096, 328), (712, 1544), dtype)
+    ranks = [37, 8, 64, 19, 3]
+    scales = [16.0 / r for r in ranks]
+    case = Case(oracle_mod, lay, ranks, scales, 2 << 20, 8, seed=31, max_rank=67, mfma_min_tokens=5)
+    rng = np.random.default_rng(8)
+    # group sizes 1, 7, 33, 70, 260: vector-ALU, column-split, and token-split items
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in zip(range(5), (260, 70, 33, 7, 1))])
+    rng.shuffle(t2a)
+    for major in (-1, 1):
+        case.gpool.set_option("slot_major", major)
+        out = case.run(t2a, seed=3)
+        print("panels dtype", dtype, "slot_major", major, "err_v", ["%.2g" % o["err_v"] for o in out],
+              "err_y", ["%.2g" % o["err_y"] for o in out], flush=True)
+    case.close()
+
+
+def test_many_small_adapters_64k_pages(oracle_mod):
+    """200 adapters of ranks 1..16 on 64 KiB pages, most tokens alone with their adapter."""
+    lay = Layout((512,), (1024,), DT_BF16)
+    rng = np.random.default_rng(12)
+    ranks = rng.integers(1, 17, size=200).tolist()
+    case = Case(oracle_mod, lay, ranks, [1.0] * 200, 65536, 200, seed=13)
+    t2a = draw_tok2adapter(rng, 333, np.arange(200), s=0.7, none_frac=0.05)
+    out = case.run(t2a, seed=1)
+    print("small adapters err_v %.2g err_y %.2g" % (out[0]["err_v"], out[0]["err_y"]), flush=True)
+    case.close()
