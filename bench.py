@@ -329,7 +329,7 @@ def main():
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
     ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="matrix-core threshold of shrink (library default 5)")
-    ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand (library default 16)")
+    ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand (library default 64)")
     ap.add_argument("--xcd-remap", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")

@@ -831,39 +831,73 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
   expand_valu_item<DT>(a, it, sl, v, y, my_pg, chunk);
 }
 
+// One vector-ALU item per single-wavefront workgroup: record i of the list is item i (padding
+// records do nothing).  Fewer registers and no LDS tiles, so more items are resident per CU than in
+// the 256-thread kernels; used for the vector-ALU part of a list when it is launched on its own.
+template <int DT>
+__global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ int2 lds_pg[kMaxRank];
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
+  if (it.kind != 0) return;
+  const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  const SlotRec sl = a.slots[a.slot0 + q];
+  expand_valu_item<DT>(a, it, sl, (const float*)p.a[q], (uint8_t*)p.b[q], lds_pg, chunk);
+}
+
+template <int DT>
+__global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ int32_t lds_pt[kPtWindow / 4];
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
+  if (it.kind != 0) return;
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  const SlotRec sl = a.slots[a.slot0 + q];
+  shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
+}
+
 }  // namespace
 
-hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, hipStream_t st) {
+hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, bool single, hipStream_t st) {
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
-  if (a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
+  if (!single && a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
   LaunchArgs a = a0;
-  const int n_blocks = a0.n_items / 4;
+  const int per = single ? 1 : 4;  // records per workgroup
+  const int n_blocks = a0.n_items / per;
   const int step = a0.slot_fastest ? 65535 : n_blocks;  // grid.z is limited to 65535
   for (int first = 0; first < n_blocks; first += step) {
     const int nb = n_blocks - first < step ? n_blocks - first : step;
-    a.items = a0.items + 4 * first;
-    a.n_items = 4 * nb;
+    a.items = a0.items + per * first;
+    a.n_items = per * nb;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, nb) : dim3(nb, 1, n_slots);
-    if (dtype == 0) hipLaunchKernelGGL(k_shrink<0>, grid, dim3(256), 0, st, a, p);
+    if (single) {
+      if (dtype == 0) hipLaunchKernelGGL(k_shrink_valu1<0>, grid, dim3(kWave), 0, st, a, p);
+      else if (dtype == 1) hipLaunchKernelGGL(k_shrink_valu1<1>, grid, dim3(kWave), 0, st, a, p);
+      else hipLaunchKernelGGL(k_shrink_valu1<2>, grid, dim3(kWave), 0, st, a, p);
+    } else if (dtype == 0) hipLaunchKernelGGL(k_shrink<0>, grid, dim3(256), 0, st, a, p);
     else if (dtype == 1) hipLaunchKernelGGL(k_shrink<1>, grid, dim3(256), 0, st, a, p);
     else hipLaunchKernelGGL(k_shrink<2>, grid, dim3(256), 0, st, a, p);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks,
+hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks, bool single,
                          hipStream_t st) {
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
-  if (a0.n_items % 4 || max_chunks > 65535) return hipErrorInvalidValue;
+  if ((!single && a0.n_items % 4) || max_chunks > 65535) return hipErrorInvalidValue;
   LaunchArgs a = a0;
-  const int n_blocks = a0.n_items / 4;
+  const int per = single ? 1 : 4;  // records per workgroup
+  const int n_blocks = a0.n_items / per;
   const int step = a0.slot_fastest ? 65535 : n_blocks;  // grid.y is limited to 65535
   for (int first = 0; first < n_blocks; first += step) {
     const int nb = n_blocks - first < step ? n_blocks - first : step;
-    a.items = a0.items + 4 * first;
-    a.n_items = 4 * nb;
+    a.items = a0.items + per * first;
+    a.n_items = per * nb;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, nb, max_chunks) : dim3(nb, max_chunks, n_slots);
-    if (dtype == 0) hipLaunchKernelGGL(k_expand<0>, grid, dim3(256), 0, st, a, p);
+    if (single) {
+      if (dtype == 0) hipLaunchKernelGGL(k_expand_valu1<0>, grid, dim3(kWave), 0, st, a, p);
+      else if (dtype == 1) hipLaunchKernelGGL(k_expand_valu1<1>, grid, dim3(kWave), 0, st, a, p);
+      else hipLaunchKernelGGL(k_expand_valu1<2>, grid, dim3(kWave), 0, st, a, p);
+    } else if (dtype == 0) hipLaunchKernelGGL(k_expand<0>, grid, dim3(256), 0, st, a, p);
     else if (dtype == 1) hipLaunchKernelGGL(k_expand<1>, grid, dim3(256), 0, st, a, p);
     else hipLaunchKernelGGL(k_expand<2>, grid, dim3(256), 0, st, a, p);
   }

@@ -64,6 +64,7 @@ struct plora_batch {
   // queues
   size_t off_items[2][2] = {{0, 0}, {0, 0}};
   int32_t n_items[2][2] = {{0, 0}, {0, 0}};
+  int32_t n_heavy[2] = {0, 0};  // layout 0 only: records of the leading matrix-core blocks
   std::vector<int32_t> adapters;      // pinned adapters
   std::shared_ptr<Event> done;        // recorded by plora_batch_end; the images are reusable once it has passed
   hipEvent_t ev_img = nullptr;        // the image has arrived on the device (recorded on the pool's aux stream)
@@ -91,9 +92,11 @@ struct plora_pool {
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
   // tunables
   int mfma_min_tokens = 5;          // shrink: groups of at least this many tokens take matrix-core items
-  int mfma_min_tokens_expand = 16;  // expand: likewise (its vector-ALU items stay ahead for longer)
+  int mfma_min_tokens_expand = 64;  // expand: likewise (its vector-ALU items stay ahead up to decode-sized groups)
   int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
+  int split[2] = {0, 1}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
+                         // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
   int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
   // kernel timing (plora_profile)
   bool profiling = false;
@@ -138,7 +141,7 @@ struct Group {
 // are dealt into 8 queues (longest first, each to the least loaded queue) and the queues are
 // interleaved block by block; queues that run out are padded with empty blocks.
 void arrange_blocks(const std::vector<Group>& heavy, const std::vector<Group>& light, bool xcd_aware,
-                    std::vector<ItemRec>& out) {
+                    std::vector<ItemRec>& out, int32_t* n_heavy_records = nullptr) {
   out.clear();
   ItemRec pad{};
   pad.kind = -1;
@@ -175,6 +178,7 @@ void arrange_blocks(const std::vector<Group>& heavy, const std::vector<Group>& l
   for (size_t i = 0; i < longest; ++i)
     for (int k = 0; k < nq; ++k)
       for (int w = 0; w < 4; ++w) out.push_back(4 * i + w < blocks[k].size() ? blocks[k][4 * i + w] : pad);
+  if (n_heavy_records) *n_heavy_records = nq == 1 ? (int32_t)(4 * qh[0].size()) : 0;
 }
 
 }  // namespace
@@ -414,6 +418,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->xcd_remap = (int)value;
     return PLORA_OK;
   }
+  if (k == "split_shrink" || k == "split_expand") {
+    if (value != 0 && value != 1) return PLORA_ERR_INVAL;
+    p->split[k == "split_expand"] = (int)value;
+    return PLORA_OK;
+  }
   if (k == "slot_major") {
     if (value < -1 || value > 1) return PLORA_ERR_INVAL;
     p->slot_major = (int)value;
@@ -562,7 +571,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   }
   std::vector<ItemRec> lists[2][2];  // [op][layout]
   for (int op = 0; op < 2; ++op)
-    for (int lay = 0; lay < 2; ++lay) arrange_blocks(grp[op][1], grp[op][0], lay != 0, lists[op][lay]);
+    for (int lay = 0; lay < 2; ++lay)
+      arrange_blocks(grp[op][1], grp[op][0], lay != 0, lists[op][lay], lay == 0 ? &b->n_heavy[op] : nullptr);
   for (int32_t i : touched) p->count[i] = 0;
 
   // image layout
@@ -670,9 +680,15 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     a.pad = 0;
     const int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
     const int chunks = (max_out + kWave * vec - 1) / (kWave * vec);
-    a.items = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
-    a.n_items = b->n_items[op][layout];
-    if (a.n_items == 0) continue;
+    const ItemRec* list = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
+    const int n_all = b->n_items[op][layout];
+    if (n_all == 0) continue;
+    // one launch over the whole block list, or (longest-first list only) the matrix-core blocks in the
+    // 256-thread kernel followed by the vector-ALU records one per single-wavefront workgroup
+    const bool split = layout == 0 && p->split[op] && n_all > b->n_heavy[op];
+    struct Part { const ItemRec* items; int n; bool single; };
+    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, false},
+                           {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, true}};
     plora_pool::ProfRec rec{op, nullptr, nullptr};
     if (p->profiling) {
       for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
@@ -681,10 +697,15 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
       }
       HIP_TRY(hipEventRecord(rec.e0, (hipStream_t)s));
     }
-    hipError_t e;
-    if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, (hipStream_t)s);
-    else e = launch_expand(p->dtype, a, ptrs, nq, chunks, (hipStream_t)s);
-    HIP_TRY(e);
+    for (const Part& part : parts) {
+      if (part.n == 0) continue;
+      a.items = part.items;
+      a.n_items = part.n;
+      hipError_t e;
+      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, part.single, (hipStream_t)s);
+      else e = launch_expand(p->dtype, a, ptrs, nq, chunks, part.single, (hipStream_t)s);
+      HIP_TRY(e);
+    }
     if (p->profiling) {
       HIP_TRY(hipEventRecord(rec.e1, (hipStream_t)s));
       p->prof.push_back(rec);

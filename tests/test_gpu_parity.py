@@ -16,10 +16,12 @@ def test_cfg0_small_workload(oracle_mod):
     rng = np.random.default_rng(cfg["seed"])
     t2a = draw_tok2adapter(rng, cfg["tokens"], np.arange(4), s=None)
     print("cfg0 t2a", t2a.tolist(), flush=True)
-    for mfma, major, remap in ((0, -1, 1), (1, 0, 1), (4, 1, 1), (2, 0, 0), (1, 1, 0)):
+    for mfma, major, remap, split in ((0, -1, 1, 0), (1, 0, 1, 1), (4, 1, 1, 1), (2, 0, 0, 0), (1, 1, 0, 0)):
         case.set_mfma(mfma, 0 if mfma == 4 else mfma)
         case.gpool.set_option("slot_major", major)
         case.gpool.set_option("xcd_remap", remap)
+        case.gpool.set_option("split_shrink", split)
+        case.gpool.set_option("split_expand", 1 - split if major == 1 else split)
         out = case.run(t2a, seed=1)
         print("mfma_min", mfma, "err_v %.3g err_y %.3g" % (out[0]["err_v"], out[0]["err_y"]), flush=True)
         out = case.run(t2a, seed=2, y0_zero=True)
@@ -39,6 +41,7 @@ def test_ragged_multi_slot(oracle_mod, dtype, mfma, major):
     case = Case(oracle_mod, lay, ranks, scales, 4096, 1024, seed=77, load_order=[4, 0, 6, 2, 1, 7, 3, 5],
                 mfma_min_tokens=mfma)
     case.gpool.set_option("slot_major", major)
+    case.gpool.set_option("split_shrink", 1 if mfma == 3 else 0)
     # scatter: evict two adapters and reload them so that their pages interleave
     case.evict(0)
     case.evict(6)
