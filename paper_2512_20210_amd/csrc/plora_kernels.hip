@@ -112,6 +112,17 @@ __device__ __forceinline__ uint4 pack(const float* f) {
   return q;
 }
 
+// a.lo * b.lo + a.hi * b.hi + c for a pair of 16-bit elements per register, summed in fp32.
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+template <int DT>
+__device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
+  if constexpr (DT == 1)
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+  else
+    return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, a), __builtin_bit_cast(f16x2_t, b), c, false);
+}
+
 __device__ __forceinline__ float wave_sum(float s) {
 #pragma unroll
   for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
@@ -133,7 +144,7 @@ __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 // ------------------------------------------------------------------------------------------
 // shrink, vector-ALU item
 // ------------------------------------------------------------------------------------------
-template <int DT, int NT, bool TAIL>
+template <int DT, int NT, int ROWS, bool TAIL>
 __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uint8_t* __restrict__ x, const int64_t* tok,
                                                   const int32_t* lds_pt, uint32_t win0, uint64_t base, uint64_t rowb,
                                                   int nrows, int d_in, int k0, float (*acc)[NT]) {
@@ -146,32 +157,47 @@ __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uin
   uint4 xq[NT];
 #pragma unroll
   for (int i = 0; i < NT; ++i) xq[i] = ld16(x + ((uint64_t)tok[i] * d_in + kk) * EB);
-  uint4 wq[kShrinkRows];
+  uint4 wq[ROWS];
 #pragma unroll
-  for (int jj = 0; jj < kShrinkRows; ++jj) {
+  for (int jj = 0; jj < ROWS; ++jj) {
     const int jr = imin(jj, nrows - 1);
     const uint64_t voff = base + (uint64_t)jr * rowb + (uint64_t)kk * EB;
     const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(voff >> lp) - win0];
     wq[jj] = ldw16(a.slab + (pg << lp) + (voff & pmask));
   }
-  float xf[NT][VEC];
 #pragma unroll
-  for (int i = 0; i < NT; ++i) {
+  for (int i = 0; i < NT; ++i)
     if (TAIL && !ok) xq[i] = make_uint4(0, 0, 0, 0);
-    unpack<DT>(xq[i], xf[i]);
-  }
+  if constexpr (DT == 2) {
+    float xf[NT][VEC];
 #pragma unroll
-  for (int jj = 0; jj < kShrinkRows; ++jj) {
-    float wf[VEC];
-    unpack<DT>(wq[jj], wf);
+    for (int i = 0; i < NT; ++i) unpack<DT>(xq[i], xf[i]);
 #pragma unroll
-    for (int i = 0; i < NT; ++i)
+    for (int jj = 0; jj < ROWS; ++jj) {
+      float wf[VEC];
+      unpack<DT>(wq[jj], wf);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) acc[jj][i] = __builtin_fmaf(wf[e], xf[i][e], acc[jj][i]);
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[jj][i] = __builtin_fmaf(wf[e], xf[i][e], acc[jj][i]);
+    }
+  } else {
+    // 16-bit elements: two products per instruction straight from the packed pairs, fp32 sum
+#pragma unroll
+    for (int jj = 0; jj < ROWS; ++jj)
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        float s = acc[jj][i];
+        s = dot2<DT>(wq[jj].x, xq[i].x, s);
+        s = dot2<DT>(wq[jj].y, xq[i].y, s);
+        s = dot2<DT>(wq[jj].z, xq[i].z, s);
+        s = dot2<DT>(wq[jj].w, xq[i].w, s);
+        acc[jj][i] = s;
+      }
   }
 }
 
-template <int DT, int NT>
+template <int DT, int NT, int ROWS>
 __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt) {
@@ -184,7 +210,7 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
 #pragma unroll
   for (int i = 0; i < NT; ++i) tok[i] = it.tok[i];
 
-  const int nrows = imin(kShrinkRows, r - it.j0);
+  const int nrows = imin(ROWS, r - it.j0);
   const uint64_t rowb = (uint64_t)d_in * EB;
   const uint64_t base = (uint64_t)r * EB * (uint64_t)sl.cum + (uint64_t)it.j0 * rowb;
   const int lp = a.log2_page;
@@ -203,20 +229,20 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
   if (r == 0) return;
   wave_sync();
 
-  float acc[kShrinkRows][NT];
+  float acc[ROWS][NT];
 #pragma unroll
-  for (int jj = 0; jj < kShrinkRows; ++jj)
+  for (int jj = 0; jj < ROWS; ++jj)
 #pragma unroll
     for (int i = 0; i < NT; ++i) acc[jj][i] = 0.f;
 
   constexpr int CH = kWave * VEC;
   const int full = d_in / CH * CH;
   for (int k0 = 0; k0 < full; k0 += CH)
-    shrink_valu_chunk<DT, NT, false>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
-  if (full < d_in) shrink_valu_chunk<DT, NT, true>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
+    shrink_valu_chunk<DT, NT, ROWS, false>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
+  if (full < d_in) shrink_valu_chunk<DT, NT, ROWS, true>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
 
 #pragma unroll
-  for (int jj = 0; jj < kShrinkRows; ++jj)
+  for (int jj = 0; jj < ROWS; ++jj)
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
       const float s = wave_sum(acc[jj][i]);
@@ -227,9 +253,9 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
 template <int DT>
 __device__ __forceinline__ void shrink_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
                                                  const uint8_t* x, float* v, int32_t* lds_pt) {
-  if (it.ntok <= 1) shrink_valu_body<DT, 1>(a, it, sl, x, v, lds_pt);
-  else if (it.ntok == 2) shrink_valu_body<DT, 2>(a, it, sl, x, v, lds_pt);
-  else shrink_valu_body<DT, kValuTok>(a, it, sl, x, v, lds_pt);
+  if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows>(a, it, sl, x, v, lds_pt);
+  else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows>(a, it, sl, x, v, lds_pt);
+  else shrink_valu_body<DT, kValuTok, kShrinkRows>(a, it, sl, x, v, lds_pt);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -373,6 +399,17 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
 // row-contiguous 16-byte loads (8 lanes per row), parks them in its own LDS region and reads the
 // operands back in MFMA layout.  The next tiles are requested before the current ones are
 // multiplied.
+#ifndef PLORA_SM_INTERLEAVE
+#define PLORA_SM_INTERLEAVE 1
+#endif
+#ifndef PLORA_SM_BARRIER
+#define PLORA_SM_BARRIER 1
+#endif
+#if PLORA_SM_BARRIER
+#define SM_SYNC() __syncthreads()
+#else
+#define SM_SYNC() wave_sync()
+#endif
 constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16 pad per LDS row
 static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
@@ -415,7 +452,14 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
   // this wavefront's quarter of the contraction, in runs of 64 k-values
   const int nrun = (d_in + 63) >> 6;
   const int per = (nrun + 3) >> 2;
-  const int c0 = wave * per, c1 = imin(nrun, c0 + per);
+#if PLORA_SM_INTERLEAVE
+  const int mine = (nrun - wave + 3) >> 2;  // runs wave, wave + 4, ...
+#define SM_RUN(i) ((i) * 4 + wave)
+#else
+  const int c0 = imin(nrun, wave * per), c1 = imin(nrun, c0 + per);
+  const int mine = c1 - c0;
+#define SM_RUN(i) (c0 + (i))
+#endif
 
   f32x4 acc[2][2];
 #pragma unroll
@@ -442,15 +486,15 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
       for (int i = 0; i < 4; ++i) { wq[i] = make_uint4(0, 0, 0, 0); xq[i] = make_uint4(0, 0, 0, 0); }
     }
   };
-  if (c0 < c1) fetch(c0);
-  for (int run = c0; run < c1; ++run) {
+  if (mine > 0) fetch(SM_RUN(0));
+  for (int i = 0; i < mine; ++i) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       *reinterpret_cast<uint4*>(tw + (lr + 8 * i) * kSmPitch + lp8 * 16) = wq[i];
       *reinterpret_cast<uint4*>(tx + (lr + 8 * i) * kSmPitch + lp8 * 16) = xq[i];
     }
-    __syncthreads();
-    if (run + 1 < c1) fetch(run + 1);  // in flight while this run is multiplied
+    SM_SYNC();
+    if (i + 1 < mine) fetch(SM_RUN(i + 1));  // in flight while this run is multiplied
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       uint4 wo[2], xo[2];
@@ -464,11 +508,15 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = mfma16<DT>(xo[mt], wo[nt], acc[mt][nt]);
     }
-    __syncthreads();
+    SM_SYNC();
   }
-  // every wavefront passes 2 * per barriers: those whose quarter is shorter (or empty) catch up here
-  const int mine = c1 > c0 ? c1 - c0 : 0;
+#if PLORA_SM_BARRIER
+  // every wavefront passes 2 * per barriers: those with fewer runs (or none) catch up here
   for (int run = mine; run < per; ++run) { __syncthreads(); __syncthreads(); }
+#else
+  __syncthreads();  // the reduction below reuses every wavefront's tiles
+#endif
+#undef SM_RUN
 
   // add the 4 partial sums in wavefront order: thread (w, lane) finishes tile (mt, nt) = (w >> 1, w & 1)
   float* red = reinterpret_cast<float*>(&tile[0][0][0]);  // 4 x 64 x 16 floats = 16 KiB, tiles are free now
