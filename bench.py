@@ -328,8 +328,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
-    ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="matrix-core threshold of shrink (library default 5)")
-    ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand (library default 64)")
+    ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="plain token threshold of the matrix-core items in shrink (default: the library's work-based rule)")
+    ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand")
     ap.add_argument("--xcd-remap", type=int, default=-1)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
@@ -351,10 +351,12 @@ def main():
 
     w = GpuWorkload(args.workload, verbose=args.verbose, scatter=args.scatter)
     cfg, lay = w.cfg, w.lay
-    if args.mfma_min_tokens >= 0:
+    if args.mfma_min_tokens >= 0:   # a plain token threshold: the work condition is switched off
         w.pool.set_option("mfma_min_tokens", args.mfma_min_tokens)
+        w.pool.set_option("mfma_min_work", 1 << 30)
     if args.mfma_min_tokens_expand >= 0:
         w.pool.set_option("mfma_min_tokens_expand", args.mfma_min_tokens_expand)
+        w.pool.set_option("mfma_min_work_expand", 1 << 30)
     if args.xcd_remap >= 0:
         w.pool.set_option("xcd_remap", args.xcd_remap)
     rng = np.random.default_rng(cfg["seed"] + 7)

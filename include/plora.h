@@ -151,14 +151,16 @@ int plora_batch_end(plora_pool* pool, plora_batch* batch);
 /* Counters of the pool (Sec. V-A lists memory utilisation and fragmentation as metrics). */
 int plora_pool_stats(plora_pool* pool, plora_stats* out);
 
-/* Tunables.  key: "mfma_min_tokens" / "mfma_min_tokens_expand" (adapter groups with at least this
- * many tokens use the matrix-core items in shrink / expand; 0 disables them; defaults 5 / 64; take
- * effect for batches begun afterwards), "slot_major" (-1 =
+/* Tunables.  An adapter group of n tokens and rank r uses the matrix-core items when n >=
+ * "mfma_min_tokens" / "mfma_min_tokens_expand" (shrink / expand; defaults 16 / 64; 0 = never, 1 =
+ * always) or when its work reaches "mfma_min_work" / "mfma_min_work_expand" (defaults 64 / 768; 1 ..
+ * 2^30), where work = n * r for shrink and n * r * r / (r rounded up to a multiple of 32) for expand;
+ * they take effect for batches begun afterwards.  "slot_major" (-1 =
  * slots are the fastest grid dimension when their count is a multiple of 8, 0 never, 1 always),
  * "xcd_remap" (1 = for launches whose fastest dimension is the work item, neighbouring work items
  * share an XCD), "split_shrink" / "split_expand" (1 = when slots are the fastest dimension, launch the
  * matrix-core blocks in the 256-thread kernel and then the vector-ALU items one per single-wavefront
- * workgroup, instead of one mixed launch; defaults 0 / 1).  INVAL for an unknown key or a value out of range. */
+ * workgroup, instead of one mixed launch; defaults 0 / 0).  INVAL for an unknown key or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand bracket

@@ -27,6 +27,9 @@ constexpr int kExpandU = PLORA_EXPAND_U;        // rows of B in flight per vecto
 #endif
 constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item
 constexpr int kMfmaTokE = PLORA_MFMA_TOK_E;     // tokens per matrix-core expand item
+constexpr int kMfmaTokCols = 16;        // items of at most this many tokens take the column-split form
+constexpr int kMfmaColsMaxGroup = 32;   // groups (or last blocks of groups) of at most this many tokens are cut
+                                        // into column-split items
 #ifndef PLORA_MFMA_ROWS
 #define PLORA_MFMA_ROWS 32
 #endif

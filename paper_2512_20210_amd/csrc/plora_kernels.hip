@@ -654,20 +654,23 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int cc = 0; cc < 8; ++cc) acc[mt][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
+  const int nn = ok ? n : n0;
+  uint4 yq[MT][4];  // requested now, used after the loop
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int i = 0; i < 4; ++i) yq[mt][i] = ld16(y + ((uint64_t)trow[mt][i] * d_out + nn) * EB);
   int jb = 0;
   for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
   if (jb < r) expand_mfma_kstep<DT, MT, true>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
   if (!ok) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    uint4 yq[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) yq[i] = ld16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB);
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       if (mt * 16 + g * 4 + i < it.ntok) {
         float yf[8];
-        unpack<DT>(yq[i], yf);
+        unpack<DT>(yq[mt][i], yf);
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
         st16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
@@ -712,10 +715,9 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
       lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
     }
   }
-  if (kMfmaTokE <= 32 || it.ntok <= 32) {  // uniform: few tokens -> split the columns, not the tokens
+  if (kMfmaTokE <= kMfmaTokCols || it.ntok <= kMfmaTokCols) {  // uniform: few tokens -> split the columns, not the tokens
     __syncthreads();
-    if (kMfmaTokE <= 16 || it.ntok <= 16) expand_mfma_cols_body<DT, 1>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
-    else expand_mfma_cols_body<DT, 2>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+    expand_mfma_cols_body<DT, 1>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
     return;
   }
   if constexpr (kMfmaTokE > 32) {

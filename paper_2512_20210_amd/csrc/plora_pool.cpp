@@ -91,11 +91,14 @@ struct plora_pool {
   int open_batches = 0;
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
   // tunables
-  int mfma_min_tokens = 5;          // shrink: groups of at least this many tokens take matrix-core items
-  int mfma_min_tokens_expand = 64;  // expand: likewise (its vector-ALU items stay ahead up to decode-sized groups)
+  // A group of n tokens on a rank-r adapter takes matrix-core items when n >= min_tokens or its work
+  // reaches min_work (min_tokens 0 = never).  Shrink: work = n * r.  Expand: work = n * r * (r / r
+  // rounded up to 32), the second factor being the used part of the 32-row contraction tile.
+  int mfma_min_tokens = 16, mfma_min_tokens_expand = 64;
+  int64_t mfma_min_work = 64, mfma_min_work_expand = 768;
   int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
-  int split[2] = {0, 1}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
+  int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
                          // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
   int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
   // kernel timing (plora_profile)
@@ -413,6 +416,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     (k == "mfma_min_tokens" ? p->mfma_min_tokens : p->mfma_min_tokens_expand) = (int)value;
     return PLORA_OK;
   }
+  if (k == "mfma_min_work" || k == "mfma_min_work_expand") {
+    if (value < 1 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    (k == "mfma_min_work" ? p->mfma_min_work : p->mfma_min_work_expand) = value;
+    return PLORA_OK;
+  }
   if (k == "xcd_remap") {
     if (value != 0 && value != 1) return PLORA_ERR_INVAL;
     p->xcd_remap = (int)value;
@@ -500,8 +508,11 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     const int32_t pt_off = (int32_t)n_pt_total;
     n_pt_total += a.pt.size();
     const int16_t rank = (int16_t)a.rank;
-    const bool mf_s = mfma_ok && p->mfma_min_tokens > 0 && n >= p->mfma_min_tokens;
-    const bool mf_e = mfma_ok && p->mfma_min_tokens_expand > 0 && n >= p->mfma_min_tokens_expand;
+    const int64_t r32 = ((int64_t)a.rank + 31) / 32 * 32;
+    const bool mf_s = mfma_ok && p->mfma_min_tokens > 0 &&
+                      (n >= p->mfma_min_tokens || (int64_t)n * a.rank >= p->mfma_min_work);
+    const bool mf_e = mfma_ok && p->mfma_min_tokens_expand > 0 &&
+                      (n >= p->mfma_min_tokens_expand || (int64_t)n * a.rank * a.rank >= p->mfma_min_work_expand * r32);
     // Matrix-core items.  Large groups (prefill) are cut into blocks of kTokBlock tokens: a block is
     // the unit that is dealt to an XCD, and inside a block the shrink items go row group by row
     // group with the token groups innermost, so a tile of A is re-read back to back and the block's
@@ -523,10 +534,13 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       if (mf_e) {
         Group ge;
         ge.heavy = true;
-        for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokE) {
-          const int16_t nt = (int16_t)std::min(kMfmaTokE, b1 - t0);
+        // a remainder of at most kMfmaColsMaxGroup tokens goes as column-split items of one token tile
+        for (int32_t t0 = b0; t0 < b1;) {
+          const int32_t left = b1 - t0;
+          const int16_t nt = (int16_t)std::min(left <= kMfmaColsMaxGroup ? kMfmaTokCols : kMfmaTokE, left);
           ge.items.push_back(ItemRec{1, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
           ge.cost += a.rank + 2 * nt;
+          t0 += nt;
         }
         grp[1][1].push_back(std::move(ge));
       }

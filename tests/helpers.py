@@ -61,9 +61,12 @@ class Case:
             self.load(i)
 
     def set_mfma(self, n, n_expand=None):
-        """Threshold (tokens per adapter group) of the matrix-core items in shrink and in expand."""
+        """Matrix-core items in shrink and in expand exactly for the adapter groups of at least n
+        (n_expand) tokens, whatever their rank; 0 = never."""
         self.gpool.set_option("mfma_min_tokens", n)
         self.gpool.set_option("mfma_min_tokens_expand", n if n_expand is None else n_expand)
+        self.gpool.set_option("mfma_min_work", 1 << 30)
+        self.gpool.set_option("mfma_min_work_expand", 1 << 30)
 
     def load(self, i):
         pt_o = self.opool.load(i, self.ranks[i], self.scales[i], self.blobs[i])
