@@ -236,16 +236,18 @@ class _PoolForManager:
         self.pool.evict(aid)
 
 
-def churn_setup(name="cfg3", blobs_per_rank=8):
-    """Pool, shared pinned blobs (blobs_per_rank distinct weight sets per rank) and the request trace."""
+def churn_setup(name="cfg3", blobs_per_rank=8, pinned=None):
+    """Pool, shared pinned blobs (blobs_per_rank distinct weight sets per rank; made unless given) and
+    the request trace."""
     import torch
     import paper_2512_20210_amd as P
     from workload import churn_trace, make_adapter
     cfg, lay, ranks, scales, page_bytes, n_pages = workload_params(name)
     pop = cfg["population"]
     rng = np.random.default_rng(cfg["seed"] + 1000)
-    pinned = {}
-    for r in sorted(set(int(x) for x in ranks)):
+    make = pinned is None
+    pinned = {} if make else pinned
+    for r in sorted(set(int(x) for x in ranks)) if make else ():
         for k in range(blobs_per_rank):
             t = torch.empty(lay.adapter_elems(r), dtype=torch.int16, pin_memory=True)
             make_adapter(rng, lay, r, out=t.numpy().view(np.uint16))
@@ -256,22 +258,23 @@ def churn_setup(name="cfg3", blobs_per_rank=8):
     return cfg, lay, ranks, scales, pool, pinned, trace
 
 
-def run_churn(args):
-    """cfg3: load/evict churn interleaved with decode batches; utilisation, H2D and kernel rates."""
+def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
+    """One pass over the churn trace.  quality None: adapters are loaded on demand only; otherwise the
+    prefetch manager runs on a synthetic prediction of that quality before every window."""
     import torch
-    from paper_2512_20210_amd.manager import ResidencyManager
+    from paper_2512_20210_amd.prefetch import PrefetchManager, SyntheticPredictor
     from workload import zipf_probs
-    cfg, lay, ranks, scales, pool, pinned, trace = churn_setup("cfg3")
     pop, T = cfg["population"], cfg["tokens"]
     k_blobs = len(pinned) // len(set(int(x) for x in ranks))
-    copy_stream = torch.cuda.Stream()
+    copy_stream, prefetch_stream = torch.cuda.Stream(), torch.cuda.Stream()
     stream = torch.cuda.current_stream().cuda_stream
     pm = _PoolForManager(pool, lay)
     popularity = zipf_probs(pop, cfg["zipf"])
-    mgr = ResidencyManager(pm, ranks, scales, lambda i: pinned[(int(ranks[i]), i % k_blobs)],
-                           p_hat=popularity / popularity.max(), copy_stream=copy_stream.cuda_stream)
+    mgr = PrefetchManager(pm, ranks, scales, lambda i: pinned[(int(ranks[i]), i % k_blobs)],
+                          p_hat=popularity / popularity.max(), copy_stream=copy_stream.cuda_stream,
+                          prefetch_stream=prefetch_stream.cuda_stream)
+    pred = SyntheticPredictor(pop, popularity, quality, seed=cfg["seed"] + 11) if quality is not None else None
     rng = np.random.default_rng(cfg["seed"] + 7)
-    dt = torch.int16
     x = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_in]
     y = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_out]
     v = [torch.empty((T, cfg["max_rank"]), dtype=torch.float32, device="cuda") for _ in lay.d_in]
@@ -279,11 +282,30 @@ def run_churn(args):
     pool.profile(True)
     events = batches = 0
     kbytes = 0
+    pending, ttr_ms = {}, []   # cold misses whose copy is still running -> host time of the request
+    prefetched_ready = prefetched_first_use = 0
+
+    def poll():
+        now = time.perf_counter()
+        for a in list(pending):
+            if a not in mgr.last_use:   # became ready and was evicted again between two polls
+                del pending[a]
+            elif pool.ready(a):
+                ttr_ms.append((now - pending.pop(a)) * 1e3)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for win in trace:
+        if pred is not None:  # between two decode batches: the copies run beside the next batch's kernels
+            mgr.begin_interval(pred.predict(win))
         for aid in win:
-            mgr.request(int(aid))
+            aid = int(aid)
+            if aid in mgr.prefetched:
+                prefetched_first_use += 1
+                prefetched_ready += bool(pool.ready(aid))
+            if not mgr.request(aid) and aid in mgr.last_use:
+                pending[aid] = time.perf_counter()
+            if pending:
+                poll()
             events += 1
             if events >= cfg["n_events"]:
                 break
@@ -301,14 +323,21 @@ def run_churn(args):
             break
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    poll()
     kms, kn = pool.profile_read()
     st = pool.stats()
     out = {
-        "metric": "pool utilisation under churn + H2D prefetch GB/s + decode kernel GB/s", "workload": "cfg3",
-        "events": events, "decode_batches": batches, "wall_s": round(wall, 3),
+        "prediction_quality": quality, "events": events, "decode_batches": batches, "wall_s": round(wall, 3),
         "page_util_avg": round(float(np.mean(pm.page_util)), 4), "page_util_min": round(float(np.min(pm.page_util)), 4),
         "byte_util_avg": round(float(np.mean(pm.byte_util)), 4), "byte_util_min": round(float(np.min(pm.byte_util)), 4),
-        "hit_rate": round(mgr.hits / max(1, mgr.hits + mgr.misses), 4), "loads": st["loads"], "evictions": st["evictions"],
+        "hit_rate": round(mgr.hits / max(1, mgr.hits + mgr.misses), 4),
+        "cold_start_rate": round(mgr.cold_starts / max(1, events), 4),
+        "cold_time_to_ready_ms_mean": round(float(np.mean(ttr_ms)), 3) if ttr_ms else None,
+        "cold_time_to_ready_ms_p95": round(float(np.percentile(ttr_ms, 95)), 3) if ttr_ms else None,
+        "prefetch_loads": mgr.prefetch_loads, "useful_prefetches": mgr.useful_prefetches,
+        "wasted_prefetches": mgr.wasted_prefetches,
+        "prefetched_ready_at_first_use": round(prefetched_ready / max(1, prefetched_first_use), 4) if pred is not None else None,
+        "loads": st["loads"], "evictions": st["evictions"],
         "skipped_busy_victims": mgr.skipped_busy, "failed_loads": mgr.failed,
         "h2d_gb": round(st["h2d_bytes"] / 1e9, 2), "h2d_copies": st["h2d_copies"],
         "h2d_gbs_copy_time": round(st["h2d_bytes"] / 1e6 / max(st["h2d_ms"], 1e-9), 2),
@@ -317,7 +346,19 @@ def run_churn(args):
         "decode_kernel_ms_per_batch": round(sum(kms) / max(batches, 1), 4),
         "resident_adapters_end": st["resident_adapters"],
     }
-    pool.close()
+    return out
+
+
+def run_churn(args):
+    """cfg3: load/evict churn interleaved with decode batches; utilisation, H2D and kernel rates, once
+    with loads on demand only and once with threshold prefetching on a synthetic prediction."""
+    out = {"metric": "pool utilisation under churn + H2D prefetch GB/s + decode kernel GB/s + cold starts",
+           "workload": "cfg3", "passes": []}
+    pinned = None
+    for quality in (None, 0.86):
+        cfg, lay, ranks, scales, pool, pinned, trace = churn_setup("cfg3", pinned=pinned)
+        out["passes"].append(_churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality))
+        pool.close()
     print(json.dumps(out))
 
 

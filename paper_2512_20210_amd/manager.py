@@ -67,30 +67,30 @@ class ResidencyManager:
             out[i] = self.alpha * lru[i] + self.beta * self.count.get(i, 0) / cmax + self.gamma * ph
         return out
 
-    def request(self, aid):
-        """Make adapter `aid` resident. Returns True on a hit, False if a load was started."""
-        self._touch(aid)
-        if aid in self.last_use:
-            self.last_use[aid] = self.clock
-            self.hits += 1
-            return True
-        self.misses += 1
+    def _on_evict(self, vid):
+        """Hook for subclasses: adapter `vid` has just been evicted."""
+
+    def _load(self, aid, may_evict=None, stream=None):
+        """Loads `aid` (on `stream`, else on the manager's copy stream), evicting residents in ascending
+        score order while the pool is out of pages (only those for which may_evict(id) holds, if given).
+        Returns False if no room could be made."""
         victims = None
+        stream = self.copy_stream if stream is None else stream
         while True:
             try:
-                if self.copy_stream is None:
+                if stream is None:
                     self.pool.load(aid, int(self.ranks[aid]), float(self.scales[aid]), self.blob_of(aid))
                 else:
-                    self.pool.load(aid, int(self.ranks[aid]), float(self.scales[aid]), self.blob_of(aid), self.copy_stream)
+                    self.pool.load(aid, int(self.ranks[aid]), float(self.scales[aid]), self.blob_of(aid), stream)
                 self.log.append(("load", aid))
                 self.last_use[aid] = self.clock
-                return False
+                return True
             except Exception as e:  # pool error object with .code
                 if getattr(e, "code", None) != ERR_NOMEM:
                     raise
             if victims is None:
                 sc = self.scores()
-                victims = sorted(sc, key=lambda i: (sc[i], i))
+                victims = sorted((i for i in sc if may_evict is None or may_evict(i)), key=lambda i: (sc[i], i))
             evicted = False
             while victims:
                 vid = victims.pop(0)
@@ -104,8 +104,20 @@ class ResidencyManager:
                 del self.last_use[vid]
                 self.log.append(("evict", vid))
                 self.evictions += 1
+                self._on_evict(vid)
                 evicted = True
                 break
             if not evicted:
-                self.failed += 1
                 return False
+
+    def request(self, aid):
+        """Make adapter `aid` resident. Returns True on a hit, False if a load was started (or failed)."""
+        self._touch(aid)
+        if aid in self.last_use:
+            self.last_use[aid] = self.clock
+            self.hits += 1
+            return True
+        self.misses += 1
+        if not self._load(aid):
+            self.failed += 1
+        return False

@@ -14,27 +14,52 @@ from helpers import TOL_V, TOL_Y, raw_to_torch, rel_err, torch_to_raw
 pytestmark = pytest.mark.gpu
 
 
-def test_churn_tables_utilisation_and_decode(oracle_mod):
+@pytest.mark.parametrize("quality", [None, 0.86])
+def test_churn_tables_utilisation_and_decode(oracle_mod, quality):
+    """quality None: loads on demand only; 0.86: threshold prefetching on a synthetic prediction before
+    every window, with a decode batch after every window while copies may still be in flight."""
     import torch
     import bench
-    from paper_2512_20210_amd.manager import ResidencyManager
+    from paper_2512_20210_amd.prefetch import PrefetchManager, SyntheticPredictor
     cfg, lay, ranks, scales, pool, pinned, trace = bench.churn_setup("cfg3", blobs_per_rank=3)
     pop = cfg["population"]
     kb = 3
     blob = lambda i: pinned[(int(ranks[i]), i % kb)]
-    copy_stream = torch.cuda.Stream()
+    copy_stream, prefetch_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    stream = torch.cuda.current_stream().cuda_stream
     pm = bench._PoolForManager(pool, lay)
-    mgr = ResidencyManager(pm, ranks, scales, blob, copy_stream=copy_stream.cuda_stream)
+    mgr = PrefetchManager(pm, ranks, scales, blob, copy_stream=copy_stream.cuda_stream,
+                          prefetch_stream=prefetch_stream.cuda_stream)
+    popularity = zipf_probs(pop, 1.0)
+    pred = SyntheticPredictor(pop, popularity, quality, seed=2) if quality is not None else None
+    rng0 = np.random.default_rng(6)
+    Tw = 64
+    xw = [raw_to_torch(make_act(rng0, Tw, d, lay.dtype), "cuda") for d in lay.d_in]
+    yw = [raw_to_torch(make_act(rng0, Tw, d, lay.dtype), "cuda") for d in lay.d_out]
+    vw = [torch.empty((Tw, cfg["max_rank"]), device="cuda") for _ in lay.d_in]
     n = 0
     for win in trace:
+        if pred is not None:
+            mgr.begin_interval(pred.predict(win))
         for aid in win:
             mgr.request(int(aid))
             n += 1
+        if pred is not None:  # a decode batch over this window's adapters, some of them still being copied
+            ids = np.unique(win)
+            ids = ids[np.isin(ids, np.fromiter(mgr.resident(), dtype=np.int32))]
+            t2a = ids[rng0.integers(0, len(ids), size=Tw)].astype(np.int32)
+            b = pool.batch_begin(t2a, stream)
+            pool.shrink(b, 0, xw, vw, stream)
+            pool.expand(b, 0, vw, yw, stream)
+            pool.batch_end(b)
         if n >= 3000:
             break
     torch.cuda.synchronize()
     print("requests", n, "hits", mgr.hits, "misses", mgr.misses, "evictions", mgr.evictions, flush=True)
     assert mgr.evictions > 200 and mgr.failed == 0
+    if pred is not None:
+        print("prefetch loads", mgr.prefetch_loads, "useful", mgr.useful_prefetches, "wasted", mgr.wasted_prefetches, flush=True)
+        assert mgr.useful_prefetches > 0.7 * mgr.prefetch_loads
     assert min(pm.byte_util) >= 0.87, "utilisation fell to %.3f" % min(pm.byte_util)
 
     op = oracle_mod.OraclePool(cfg["page_bytes"], cfg["n_pages"], lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
@@ -53,7 +78,6 @@ def test_churn_tables_utilisation_and_decode(oracle_mod):
     T = 96
     p = zipf_probs(pop, 1.0)[res]
     t2a = res[rng.choice(len(res), size=T, p=p / p.sum())].astype(np.int32)
-    stream = torch.cuda.current_stream().cuda_stream
     b = pool.batch_begin(t2a, stream)
     perm, sa, ss = pool.batch_info(b)
     o_perm, o_sa, o_ss = op.translate(t2a)
