@@ -49,7 +49,7 @@ typedef enum {
 typedef enum { PLORA_F16 = 0, PLORA_BF16 = 1, PLORA_F32 = 2 } plora_dtype;
 
 typedef struct {
-  int32_t n_slots;      /* >= 1 */
+  int32_t n_slots;      /* 1 .. 32767 */
   const int32_t* d_in;  /* host, n_slots entries, each > 0 and a multiple of 8 */
   const int32_t* d_out; /* host, n_slots entries, each > 0 and a multiple of 8 */
   int32_t dtype;        /* plora_dtype of weights, x and y */
@@ -132,7 +132,9 @@ int plora_batch_info(const plora_batch* batch, int32_t* n_seg, int32_t* n_perm, 
  * x: host array of n_slots device pointers, x[q] -> n_tokens x d_in[slot0+q] elements, row-major,
  * 16-byte aligned.  v: host array of n_slots device pointers, v[q] -> n_tokens x max_rank floats,
  * 16-byte aligned.  Runs on `stream` (normally the stream given to plora_batch_begin; another stream
- * must be ordered after it by the caller). */
+ * must be ordered after it by the caller).  While plora_profile is off, plora_shrink and plora_expand
+ * allocate nothing and enqueue kernels only, so they may be recorded into a HIP graph on a capturing
+ * stream; the batch has to stay open, and x, v, y in place, for as long as the graph is replayed. */
 int plora_shrink(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const void* const* x,
                  float* const* v, plora_stream stream);
 

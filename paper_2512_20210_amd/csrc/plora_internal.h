@@ -61,6 +61,7 @@ struct SlotRec {
 struct SlotPtrs {
   const void* a[kMaxSlotsPerLaunch];  // shrink: x   expand: v
   void* b[kMaxSlotsPerLaunch];        // shrink: v   expand: y
+  int16_t slot[kMaxSlotsPerLaunch];   // absolute slot number of each entry
 };
 
 struct LaunchArgs {
@@ -71,7 +72,7 @@ struct LaunchArgs {
   const SlotRec* slots;   // indexed by absolute slot number
   int64_t elems_per_rank; // sum over all slots of (d_in + d_out)
   int32_t n_items;
-  int32_t slot0;
+  int32_t pad0;
   int32_t log2_page;
   int32_t v_stride;       // = max_rank
   int32_t slot_fastest;   // 1: grid = (slots, items, chunks); 0: grid = (items, chunks, slots)

@@ -837,7 +837,7 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
   __shared__ int32_t lds_pt[kPtWindow];
   const int blk = a.slot_fastest ? blockIdx.z : blockIdx.x;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
+  const SlotRec sl = a.slots[p.slot[q]];
   const uint8_t* x = (const uint8_t*)p.a[q];
   float* v = (float*)p.b[q];
   const ItemRec first = a.items[4 * blk];
@@ -863,7 +863,7 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
   const int blk = a.slot_fastest ? blockIdx.y : blockIdx.x;
   const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
+  const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
   const ItemRec first = a.items[4 * blk];
@@ -891,7 +891,7 @@ __global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, cons
   if (it.kind != 0) return;
   const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
+  const SlotRec sl = a.slots[p.slot[q]];
   expand_valu_item<DT>(a, it, sl, (const float*)p.a[q], (uint8_t*)p.b[q], lds_pg, chunk);
 }
 
@@ -901,7 +901,7 @@ __global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, cons
   const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
   if (it.kind != 0) return;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
-  const SlotRec sl = a.slots[a.slot0 + q];
+  const SlotRec sl = a.slots[p.slot[q]];
   shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
 }
 

@@ -196,7 +196,7 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
   if (!out || !lay || !lay->d_in || !lay->d_out) return PLORA_ERR_INVAL;
   if (page_bytes < 4096 || page_bytes > ((size_t)1 << 30) || (page_bytes & (page_bytes - 1))) return PLORA_ERR_INVAL;
   if (n_pages == 0 || n_pages > 0x7fffffffu) return PLORA_ERR_INVAL;
-  if (lay->n_slots < 1 || lay->dtype < 0 || lay->dtype > 2 || lay->max_adapters < 1) return PLORA_ERR_INVAL;
+  if (lay->n_slots < 1 || lay->n_slots > 32767 || lay->dtype < 0 || lay->dtype > 2 || lay->max_adapters < 1) return PLORA_ERR_INVAL;
   if (lay->max_rank < 1 || lay->max_rank > kMaxRank) return PLORA_ERR_INVAL;
   if (flags & ~PLORA_POOL_PLACEMENT_ONLY) return PLORA_ERR_INVAL;
   if (slab_or_null && ((uintptr_t)slab_or_null & 255)) return PLORA_ERR_INVAL;
@@ -677,23 +677,47 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
   a.v_stride = p->max_rank;
   a.elems_per_rank = p->C;
   const int vec = 16 / p->elt;
-  for (int q0 = 0; q0 < n_slots; q0 += kMaxSlotsPerLaunch) {
-    const int nq = std::min(kMaxSlotsPerLaunch, n_slots - q0);
+  const int op = is_shrink ? 0 : 1;
+  a.pad0 = 0;
+  a.pad = 0;
+  // Launch classes: an expand launch has one grid dimension for the 512-column chunks, so slots with
+  // different chunk counts go in launches of their own (no empty workgroups) ...; shrink has one class.
+  std::vector<std::pair<int, int>> order;  // (chunks, index within the call), stable by chunks
+  order.reserve(n_slots);
+  for (int q = 0; q < n_slots; ++q) {
+    const int d_out = (int)p->slots[slot0 + q].d_out;
+    order.emplace_back(is_shrink ? 1 : (d_out + kWave * vec - 1) / (kWave * vec), q);
+  }
+  std::stable_sort(order.begin(), order.end(), [](const auto& l, const auto& r) { return l.first < r.first; });
+  // ... but only when every class keeps a multiple of 8 slots (one slot per XCD, all XCDs alike):
+  // a short odd-sized launch costs more in ramp and tail than the empty workgroups it saves.
+  bool classes = true;
+  for (int q0 = 0; q0 < n_slots;) {
+    int nq = 1;
+    while (q0 + nq < n_slots && order[q0 + nq].first == order[q0].first) ++nq;
+    if (nq % kXcds) classes = false;
+    q0 += nq;
+  }
+  if (!classes) {  // one class in call order, with the largest chunk count
+    const int max_chunks = order.back().first;
+    for (int q = 0; q < n_slots; ++q) order[q] = {max_chunks, q};
+  }
+  for (int q0 = 0; q0 < n_slots;) {
+    int nq = 1;
+    while (q0 + nq < n_slots && nq < kMaxSlotsPerLaunch && order[q0 + nq].first == order[q0].first) ++nq;
     SlotPtrs ptrs;
-    int max_out = 0;
     for (int q = 0; q < nq; ++q) {
-      ptrs.a[q] = in[q0 + q];
-      ptrs.b[q] = outp[q0 + q];
-      max_out = std::max(max_out, (int)p->slots[slot0 + q0 + q].d_out);
+      const int qi = order[q0 + q].second;
+      ptrs.a[q] = in[qi];
+      ptrs.b[q] = outp[qi];
+      ptrs.slot[q] = (int16_t)(slot0 + qi);
     }
-    a.slot0 = slot0 + q0;
-    const int op = is_shrink ? 0 : 1;
+    const int chunks = order[q0].first;
+    q0 += nq;
     // slots fastest when that keeps every slot on one XCD and all XCDs equally loaded; else the
     // items are the fastest dimension and (optionally) come dealt into XCD queues
     a.slot_fastest = (p->slot_major == 1 || (p->slot_major < 0 && nq % kXcds == 0)) ? 1 : 0;
-    a.pad = 0;
     const int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
-    const int chunks = (max_out + kWave * vec - 1) / (kWave * vec);
     const ItemRec* list = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
     const int n_all = b->n_items[op][layout];
     if (n_all == 0) continue;

@@ -92,3 +92,7 @@ def test_cfg2_prefill_full_size(oracle_mod):
 
 def test_cfg4_decode_13b_layer_full_size(oracle_mod):
     _run(oracle_mod, "cfg4", 6, 10)
+
+
+def test_cfg5_decode_gqa_projections_full_size(oracle_mod):
+    _run(oracle_mod, "cfg5", 6, 10)

@@ -152,3 +152,19 @@ def test_many_small_adapters_64k_pages(oracle_mod):
     out = case.run(t2a, seed=1)
     print("small adapters err_v %.2g err_y %.2g" % (out[0]["err_v"], out[0]["err_y"]), flush=True)
     case.close()
+
+
+def test_slots_of_two_widths_in_one_call(oracle_mod):
+    """16 slots, 8 of them 512 columns wide and 8 of them 1536 (as with grouped-query k, v next to
+    q, o): the expand call runs one launch per width; plus a 12-slot call (classes of 6: one launch)."""
+    d_out = (512, 1536, 1536, 512) * 4
+    lay = Layout((256,) * 16, d_out, DT_BF16)
+    ranks = [8, 24, 64, 5]
+    case = Case(oracle_mod, lay, ranks, [16.0 / r for r in ranks], 16384, 512, seed=53)
+    rng = np.random.default_rng(8)
+    t2a = draw_tok2adapter(rng, 70, np.arange(len(ranks)), s=1.0, none_frac=0.1)
+    for mfma in (0, 4):
+        case.set_mfma(mfma)
+        case.run(t2a, seed=3)
+        case.run(t2a, slots=range(2, 14), seed=4)
+    case.close()

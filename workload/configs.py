@@ -1,4 +1,4 @@
-"""The five named workloads (shapes only; every draw is seeded)."""
+"""The named workloads (shapes only; every draw is seeded)."""
 from .gen import DT_BF16, DT_F16, Layout
 
 BASE_SEED = 20251220  # config k uses BASE_SEED + k
@@ -39,6 +39,11 @@ CONFIGS = {
                  slots=[(5120, 5120)] * 4 + [(5120, 13824), (13824, 5120)], tokens=1024, n_adapters=1000,
                  ranks=None, rank_choices=[16, 32, 64, 128], zipf=0.8, scale=None, page_bytes=128 * KIB,
                  n_pages=None, max_rank=128),
+    # Mistral-7B-shaped attention projections (grouped-query attention: q, o 4096->4096, k, v 4096->1024)
+    # x 32 layers; everything else as cfg1 (the second model of Sec. V-A)
+    "cfg5": dict(seed=BASE_SEED + 5, dtype=DT_BF16, slots=[(4096, 4096), (4096, 1024), (4096, 1024), (4096, 4096)] * 32,
+                 tokens=256, n_adapters=64, ranks=None, rank_choices=[8, 16, 32, 64], zipf=1.0, scale=None,
+                 page_bytes=64 * KIB, n_pages=None, max_rank=64),
 }
 
 
