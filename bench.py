@@ -202,9 +202,21 @@ def cpu_baseline(w, t2a, budget_s=15.0):
         done += 1
         if t_total > budget_s or (done >= 2 and t_total / done * (done + 1) > budget_s * 1.5):
             break
+    # the same loops on one thread, on the first slots only
+    t1, b1, n1 = 0.0, 0, 0
+    for s in range(min(2, lay.n_slots)):
+        x, y = w.host_x(s), w.host_y0(s).copy()
+        t0 = time.perf_counter()
+        v = op.shrink(s, x, t2a, threads=1)
+        op.expand(s, v, t2a, y, threads=1)
+        t1 += time.perf_counter() - t0
+        b1 += algorithmic_bytes(lay, w.ranks, t2a, [s])["total"]
+        n1 += 1
     op.close()
     per_slot = t_total / done
     return dict(value=bytes_total / t_total / 1e9, unit="GB/s", cores=threads, kind="oracle",
+                single_thread=dict(value=b1 / t1 / 1e9, unit="GB/s", slots=n1,
+                                   tokens_per_s=len(t2a) / (t1 / n1 * lay.n_slots)),
                 sample="%d of %d slots of one %d-token batch, shrink+expand, fp32 accumulators, OpenMP over tokens; "
                        "%.2f s per slot => %.1f tokens/s for the whole step" % (
                            done, lay.n_slots, len(t2a), per_slot, len(t2a) / (per_slot * lay.n_slots)),
@@ -372,6 +384,9 @@ def main():
     ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="plain token threshold of the matrix-core items in shrink (default: the library's work-based rule)")
     ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand")
     ap.add_argument("--xcd-remap", type=int, default=-1)
+    ap.add_argument("--coop-max-workgroups", type=int, default=-1,
+                    help="calls of at most this many workgroups use the cooperative kernels (library defaults 192 for "
+                         "shrink, 1024 for expand; 0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--same-batch", action="store_true", help="reuse one token->adapter draw for every step")
@@ -392,6 +407,9 @@ def main():
 
     w = GpuWorkload(args.workload, verbose=args.verbose, scatter=args.scatter)
     cfg, lay = w.cfg, w.lay
+    if args.coop_max_workgroups >= 0:
+        w.pool.set_option("coop_max_workgroups_shrink", args.coop_max_workgroups)
+        w.pool.set_option("coop_max_workgroups_expand", args.coop_max_workgroups)
     if args.mfma_min_tokens >= 0:   # a plain token threshold: the work condition is switched off
         w.pool.set_option("mfma_min_tokens", args.mfma_min_tokens)
         w.pool.set_option("mfma_min_work", 1 << 30)

@@ -162,7 +162,11 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * "xcd_remap" (1 = for launches whose fastest dimension is the work item, neighbouring work items
  * share an XCD), "split_shrink" / "split_expand" (1 = when slots are the fastest dimension, launch the
  * matrix-core blocks in the 256-thread kernel and then the vector-ALU items one per single-wavefront
- * workgroup, instead of one mixed launch; defaults 0 / 0).  INVAL for an unknown key or a value out of range. */
+ * workgroup, instead of one mixed launch; defaults 0 / 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
+ * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound
+ * by its longest chain of dependent loads; it runs the cooperative kernels instead, in which the four
+ * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 1024, 0 = never; take effect for
+ * batches begun afterwards).  INVAL for an unknown key or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand bracket

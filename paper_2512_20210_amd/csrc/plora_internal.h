@@ -81,14 +81,15 @@ struct LaunchArgs {
 
 // Launchers (plora_kernels.hip).  Both take a list of blocks of 4 records (one matrix-core item +
 // 3 padding records, or up to 4 vector-ALU items) and run one 256-thread workgroup per block, slot
-// and (expand) 512-column chunk.  With single = true the list must hold vector-ALU records only
-// and every record gets a single-wavefront workgroup of its own.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
+// and (expand) 512-column chunk.  mode 1: the list holds vector-ALU records only
+// and every record gets a single-wavefront workgroup of its own; mode 2: likewise, but a 256-thread
+// workgroup whose four wavefronts share the record's work (for calls too small to fill the machine).  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
 // a.slot_fastest is set: consecutive workgroups go to consecutive XCDs, so with a slot count that
 // is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
 // slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row
 // of B (shrink: chunks = 1).
-hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, bool single, hipStream_t st);
-hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks, bool single,
+hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int mode, hipStream_t st);
+hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st);
 
 }  // namespace plora

@@ -905,9 +905,211 @@ __global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, cons
   shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
 }
 
+// ------------------------------------------------------------------------------------------
+// Cooperative forms for calls too small to fill the machine: one vector-ALU item per 256-thread
+// workgroup, its dependent chain of loads cut in four.  A call over a few slots is bounded by the
+// length of that chain (8 chunks of d_in, or r / 8 row blocks, each a round trip to memory), not by
+// bandwidth; here the four wavefronts take every fourth chunk (shrink) or every fourth block of 8
+// rows (expand) and add their partial sums through LDS in wavefront order, so the result does not
+// depend on timing.
+// ------------------------------------------------------------------------------------------
+template <int DT, int NT>
+__device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+                                                 const uint8_t* __restrict__ x, float* __restrict__ v,
+                                                 int32_t* lds_pt, float (*red)[kShrinkRows * kValuTok]) {
+  constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int r = it.rank;
+  const int d_in = sl.d_in;
+  const int vs = a.v_stride;
+  int64_t tok[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) tok[i] = it.tok[i];
+  if (it.j0 == 0 && wave == 0) {
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+      if (i < it.ntok)
+        for (int j = r + lane; j < vs; j += kWave) v[tok[i] * vs + j] = 0.f;
+  }
+  if (r == 0) return;  // uniform over the workgroup
+
+  const int nrows = imin(kShrinkRows, r - it.j0);
+  const uint64_t rowb = (uint64_t)d_in * EB;
+  const uint64_t base = (uint64_t)r * EB * (uint64_t)sl.cum + (uint64_t)it.j0 * rowb;
+  const int lp = a.log2_page;
+  const uint32_t win0 = (uint32_t)(base >> lp);
+  const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
+  const int32_t* ptg = a.pt + it.pt_off + win0;
+  for (uint32_t i = threadIdx.x; i < win_n; i += 256) lds_pt[i] = ptg[i];
+  __syncthreads();
+
+  float acc[kShrinkRows][NT];
+#pragma unroll
+  for (int jj = 0; jj < kShrinkRows; ++jj)
+#pragma unroll
+    for (int i = 0; i < NT; ++i) acc[jj][i] = 0.f;
+  constexpr int CH = kWave * VEC;
+  const int full = d_in / CH * CH;
+  for (int k0 = wave * CH; k0 < full; k0 += 4 * CH)
+    shrink_valu_chunk<DT, NT, kShrinkRows, false>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
+  if (full < d_in && ((full / CH) & 3) == wave)
+    shrink_valu_chunk<DT, NT, kShrinkRows, true>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
+#pragma unroll
+  for (int jj = 0; jj < kShrinkRows; ++jj)
+#pragma unroll
+    for (int i = 0; i < NT; ++i) {
+      const float sum = wave_sum(acc[jj][i]);
+      if (lane == 0) red[wave][jj * NT + i] = sum;
+    }
+  __syncthreads();
+  if (wave == 0 && lane < kShrinkRows * NT) {
+    const int jj = lane / NT, i = lane % NT;
+    const float sum = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
+    const int ti = i == 1 ? it.tok[1] : i == 2 ? it.tok[2] : i == 3 ? it.tok[3] : it.tok[0];
+    if (jj < nrows && i < it.ntok) v[(int64_t)ti * vs + it.j0 + jj] = sum;
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_shrink_coop(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ int32_t lds_pt[kPtWindow / 4];
+  __shared__ float red[4][kShrinkRows * kValuTok];
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
+  if (it.kind != 0) return;  // uniform over the workgroup
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  const SlotRec sl = a.slots[p.slot[q]];
+  const uint8_t* x = (const uint8_t*)p.a[q];
+  float* v = (float*)p.b[q];
+  if (it.ntok <= 1) shrink_coop_body<DT, 1>(a, it, sl, x, v, lds_pt, red);
+  else if (it.ntok == 2) shrink_coop_body<DT, 2>(a, it, sl, x, v, lds_pt, red);
+  else shrink_coop_body<DT, kValuTok>(a, it, sl, x, v, lds_pt, red);
+}
+
+template <int DT, int NT>
+__device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+                                                 const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg,
+                                                 float* red, int chunk) {
+  constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
+  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int r = it.rank;
+  const int d_out = sl.d_out;
+  const int n0w = chunk * (kWave * VEC);
+  if (n0w >= d_out || r == 0) return;  // uniform over the workgroup
+  const int n = n0w + lane * VEC;
+  const bool ok = n < d_out;
+  const uint32_t lane_b = ok ? lane * 16 : 0;
+  const int vs = a.v_stride;
+  const int lp = a.log2_page;
+  const uint32_t pmask = (1u << lp) - 1;
+  const uint64_t rowb = (uint64_t)d_out * EB;
+  const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0w * EB;
+  {
+    const int n_pt = table_len(a, r, EB);
+    const int32_t* ptg = a.pt + it.pt_off;
+    for (int j = threadIdx.x; j < r; j += 256) {
+      const uint64_t vo = base + (uint64_t)j * rowb;
+      const uint32_t q0 = (uint32_t)(vo >> lp);
+      const uint32_t q1 = imin((int)((vo + kWave * 16 - 1) >> lp), n_pt - 1);
+      lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
+    }
+  }
+  // wavefront w finishes token w: its row of y is requested now
+  const bool fin = wave < it.ntok;
+  const int tokw = wave == 1 ? it.tok[1] : wave == 2 ? it.tok[2] : wave == 3 ? it.tok[3] : it.tok[0];  // no indexed array
+  uint8_t* yp = y + ((uint64_t)(fin ? tokw : it.tok[0]) * d_out + (ok ? n : n0w)) * EB;
+  uint4 yq = make_uint4(0, 0, 0, 0);
+  if (fin) yq = ld16(yp);
+  const float* vrow[NT];
+#pragma unroll
+  for (int i = 0; i < NT; ++i) vrow[i] = v + (int64_t)it.tok[i] * vs;
+  __syncthreads();
+
+  float acc[NT][VEC];
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[i][e] = 0.f;
+  constexpr int U = kExpandU;
+  const int nfull = r / U;  // whole blocks of U rows, dealt round robin; the ragged rest goes to the next wavefront
+  for (int blk = wave; blk < nfull; blk += 4) {
+    const int j = blk * U;
+    uint4 wq[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint64_t vo = base + (uint64_t)(j + u) * rowb;
+      const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
+      const int2 pp = lds_pg[j + u];
+      const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
+      wq[u] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      float wf[VEC];
+      unpack<DT>(wq[u], wf);
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const float vj = vrow[i][j + u];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[i][e] = __builtin_fmaf(vj, wf[e], acc[i][e]);
+      }
+    }
+  }
+  if ((nfull & 3) == wave) {
+    for (int j = nfull * U; j < r; ++j) {
+      const uint64_t vo = base + (uint64_t)j * rowb;
+      const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
+      const int2 pp = lds_pg[j];
+      const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
+      float wf[VEC];
+      unpack<DT>(ldw16(a.slab + (pg << lp) + (inpage & pmask)), wf);
+#pragma unroll
+      for (int i = 0; i < NT; ++i) {
+        const float vj = vrow[i][j];
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[i][e] = __builtin_fmaf(vj, wf[e], acc[i][e]);
+      }
+    }
+  }
+  // red[wave][token][e][lane]
+#pragma unroll
+  for (int i = 0; i < NT; ++i)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) red[((wave * kValuTok + i) * 8 + e) * kWave + lane] = acc[i][e];
+  __syncthreads();
+  if (fin && ok && wave < NT) {
+    float yf[VEC];
+    unpack<DT>(yq, yf);
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) {
+      const float s0 = red[((0 * kValuTok + wave) * 8 + e) * kWave + lane], s1 = red[((1 * kValuTok + wave) * 8 + e) * kWave + lane];
+      const float s2 = red[((2 * kValuTok + wave) * 8 + e) * kWave + lane], s3 = red[((3 * kValuTok + wave) * 8 + e) * kWave + lane];
+      yf[e] = yf[e] + it.scale * (((s0 + s1) + s2) + s3);
+    }
+    st16(yp, pack<DT>(yf));
+  }
+}
+
+template <int DT>
+__global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const SlotPtrs p) {
+  static_assert(kValuTok <= 4, "one finishing wavefront per token of the item");
+  __shared__ int2 lds_pg[kMaxRank];
+  __shared__ float red[4 * kValuTok * 8 * kWave];  // 32 KiB
+  const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
+  if (it.kind != 0) return;  // uniform over the workgroup
+  const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
+  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  const SlotRec sl = a.slots[p.slot[q]];
+  const float* v = (const float*)p.a[q];
+  uint8_t* y = (uint8_t*)p.b[q];
+  if (it.ntok <= 1) expand_coop_body<DT, 1>(a, it, sl, v, y, lds_pg, red, chunk);
+  else if (it.ntok == 2) expand_coop_body<DT, 2>(a, it, sl, v, y, lds_pg, red, chunk);
+  else expand_coop_body<DT, kValuTok>(a, it, sl, v, y, lds_pg, red, chunk);
+}
+
 }  // namespace
 
-hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, bool single, hipStream_t st) {
+hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int mode, hipStream_t st) {
+  const bool single = mode != 0;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
   if (!single && a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
   LaunchArgs a = a0;
@@ -919,7 +1121,11 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     a.items = a0.items + per * first;
     a.n_items = per * nb;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, nb) : dim3(nb, 1, n_slots);
-    if (single) {
+    if (mode == 2) {
+      if (dtype == 0) hipLaunchKernelGGL(k_shrink_coop<0>, grid, dim3(256), 0, st, a, p);
+      else if (dtype == 1) hipLaunchKernelGGL(k_shrink_coop<1>, grid, dim3(256), 0, st, a, p);
+      else hipLaunchKernelGGL(k_shrink_coop<2>, grid, dim3(256), 0, st, a, p);
+    } else if (single) {
       if (dtype == 0) hipLaunchKernelGGL(k_shrink_valu1<0>, grid, dim3(kWave), 0, st, a, p);
       else if (dtype == 1) hipLaunchKernelGGL(k_shrink_valu1<1>, grid, dim3(kWave), 0, st, a, p);
       else hipLaunchKernelGGL(k_shrink_valu1<2>, grid, dim3(kWave), 0, st, a, p);
@@ -930,8 +1136,9 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
   return hipGetLastError();
 }
 
-hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks, bool single,
+hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st) {
+  const bool single = mode != 0;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
   if ((!single && a0.n_items % 4) || max_chunks > 65535) return hipErrorInvalidValue;
   LaunchArgs a = a0;
@@ -943,7 +1150,11 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     a.items = a0.items + per * first;
     a.n_items = per * nb;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, nb, max_chunks) : dim3(nb, max_chunks, n_slots);
-    if (single) {
+    if (mode == 2) {
+      if (dtype == 0) hipLaunchKernelGGL(k_expand_coop<0>, grid, dim3(256), 0, st, a, p);
+      else if (dtype == 1) hipLaunchKernelGGL(k_expand_coop<1>, grid, dim3(256), 0, st, a, p);
+      else hipLaunchKernelGGL(k_expand_coop<2>, grid, dim3(256), 0, st, a, p);
+    } else if (single) {
       if (dtype == 0) hipLaunchKernelGGL(k_expand_valu1<0>, grid, dim3(kWave), 0, st, a, p);
       else if (dtype == 1) hipLaunchKernelGGL(k_expand_valu1<1>, grid, dim3(kWave), 0, st, a, p);
       else hipLaunchKernelGGL(k_expand_valu1<2>, grid, dim3(kWave), 0, st, a, p);

@@ -62,8 +62,9 @@ struct plora_batch {
   // work lists (blocks of 4 records): [op][layout], op 0 = shrink, 1 = expand; layout 0 = longest
   // first (for launches whose fastest grid dimension is the slot), 1 = dealt into 8 interleaved XCD
   // queues
-  size_t off_items[2][2] = {{0, 0}, {0, 0}};
-  int32_t n_items[2][2] = {{0, 0}, {0, 0}};
+  // 2 = every group as vector-ALU records, one record per workgroup (cooperative kernels of small calls)
+  size_t off_items[2][3] = {{0, 0, 0}, {0, 0, 0}};
+  int32_t n_items[2][3] = {{0, 0, 0}, {0, 0, 0}};
   int32_t n_heavy[2] = {0, 0};  // layout 0 only: records of the leading matrix-core blocks
   std::vector<int32_t> adapters;      // pinned adapters
   std::shared_ptr<Event> done;        // recorded by plora_batch_end; the images are reusable once it has passed
@@ -100,6 +101,8 @@ struct plora_pool {
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
                          // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
+  int64_t coop_max_workgroups[2] = {192, 1024};  // [shrink, expand]: calls whose ordinary launch would have at
+                                                 // most this many workgroups use the cooperative kernels (0 = never)
   int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
   // kernel timing (plora_profile)
   bool profiling = false;
@@ -421,6 +424,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     (k == "mfma_min_work" ? p->mfma_min_work : p->mfma_min_work_expand) = value;
     return PLORA_OK;
   }
+  if (k == "coop_max_workgroups_shrink" || k == "coop_max_workgroups_expand") {
+    if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    p->coop_max_workgroups[k == "coop_max_workgroups_expand"] = value;
+    return PLORA_OK;
+  }
   if (k == "xcd_remap") {
     if (value != 0 && value != 1) return PLORA_ERR_INVAL;
     p->xcd_remap = (int)value;
@@ -500,6 +508,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   // work items, grouped per adapter (tokens without adapter form one rank-0 group: shrink clears their v rows)
   const bool mfma_ok = p->dtype != PLORA_F32;  // matrix-core items exist for the 16-bit element types
   std::vector<Group> grp[2][2];  // [op][kind]
+  std::vector<ItemRec> coop[2];  // [op]
   size_t n_pt_total = 0;
   for (int32_t u = 0; u < n_seg; ++u) {
     const Adapter& a = p->ad[touched[u]];
@@ -545,8 +554,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
         grp[1][1].push_back(std::move(ge));
       }
     }
-    // Vector-ALU items.
-    if (!mf_s || !mf_e) {
+    // Vector-ALU items (every group has them in the cooperative lists).
+    {
       Group gs, ge;
       std::vector<ItemRec> tg;  // one record per token group
       for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
@@ -554,11 +563,17 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
         ItemRec it{0, nt, rank, 0, a.scale, pt_off, {0, 0, 0, 0}};
         for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
         tg.push_back(it);
+        coop[1].push_back(it);
         if (!mf_e) {
           ge.items.push_back(it);
           ge.cost += a.rank + 2 * nt;
         }
       }
+      for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
+        for (ItemRec it : tg) {
+          it.j0 = (int16_t)j0;
+          coop[0].push_back(it);
+        }
       // shrink: token groups innermost, so that the re-read of a row block by the next token
       // group follows closely and finds the rows in L2
       if (!mf_s)
@@ -579,14 +594,20 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       ItemRec it{0, nt, 0, 0, 0.f, 0, {0, 0, 0, 0}};
       for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[n_perm + t0 + std::min<int>(i, nt - 1)];
       gs.items.push_back(it);
+      coop[0].push_back(it);
       gs.cost += 0.1;
     }
     grp[0][0].push_back(std::move(gs));
   }
-  std::vector<ItemRec> lists[2][2];  // [op][layout]
-  for (int op = 0; op < 2; ++op)
+  std::vector<ItemRec> lists[2][3];  // [op][layout]
+  for (int op = 0; op < 2; ++op) {
     for (int lay = 0; lay < 2; ++lay)
       arrange_blocks(grp[op][1], grp[op][0], lay != 0, lists[op][lay], lay == 0 ? &b->n_heavy[op] : nullptr);
+    // longest chains first
+    std::stable_sort(coop[op].begin(), coop[op].end(), [](const ItemRec& x, const ItemRec& y) { return x.rank > y.rank; });
+    // (not needed when even one slot's ordinary launch is past the limit of the cooperative form)
+    if ((int64_t)(lists[op][0].size() / 4) <= p->coop_max_workgroups[op]) lists[op][2] = std::move(coop[op]);
+  }
   for (int32_t i : touched) p->count[i] = 0;
 
   // image layout
@@ -594,7 +615,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   b->off_perm = off; off = align_up(off + (size_t)T * 4, 256);
   b->off_pt = off; off = align_up(off + (n_pt_total + 1) * 4, 256);
   for (int op = 0; op < 2; ++op)
-    for (int k = 0; k < 2; ++k) {
+    for (int k = 0; k < 3; ++k) {
       b->off_items[op][k] = off; b->n_items[op][k] = (int32_t)lists[op][k].size();
       off = align_up(off + lists[op][k].size() * sizeof(ItemRec), 256);
     }
@@ -625,7 +646,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     *dst = 0;
   }
   for (int op = 0; op < 2; ++op)
-    for (int k = 0; k < 2; ++k)
+    for (int k = 0; k < 3; ++k)
       if (!lists[op][k].empty())
         std::memcpy(b->h_img + b->off_items[op][k], lists[op][k].data(), lists[op][k].size() * sizeof(ItemRec));
   b->perm.resize(n_perm);
@@ -717,16 +738,20 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     // slots fastest when that keeps every slot on one XCD and all XCDs equally loaded; else the
     // items are the fastest dimension and (optionally) come dealt into XCD queues
     a.slot_fastest = (p->slot_major == 1 || (p->slot_major < 0 && nq % kXcds == 0)) ? 1 : 0;
-    const int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
+    int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
+    // a call that cannot fill the machine is bound by its longest dependent chain: cooperative kernels
+    const bool coop = p->coop_max_workgroups[op] > 0 && b->n_items[op][2] > 0 &&
+                      (int64_t)nq * (b->n_items[op][layout] / 4) * chunks <= p->coop_max_workgroups[op];
+    if (coop) layout = 2;
     const ItemRec* list = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
     const int n_all = b->n_items[op][layout];
     if (n_all == 0) continue;
     // one launch over the whole block list, or (longest-first list only) the matrix-core blocks in the
     // 256-thread kernel followed by the vector-ALU records one per single-wavefront workgroup
     const bool split = layout == 0 && p->split[op] && n_all > b->n_heavy[op];
-    struct Part { const ItemRec* items; int n; bool single; };
-    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, false},
-                           {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, true}};
+    struct Part { const ItemRec* items; int n; int mode; };
+    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, coop ? 2 : 0},
+                           {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, 1}};
     plora_pool::ProfRec rec{op, nullptr, nullptr};
     if (p->profiling) {
       for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
@@ -740,8 +765,8 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
       a.items = part.items;
       a.n_items = part.n;
       hipError_t e;
-      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, part.single, (hipStream_t)s);
-      else e = launch_expand(p->dtype, a, ptrs, nq, chunks, part.single, (hipStream_t)s);
+      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, part.mode, (hipStream_t)s);
+      else e = launch_expand(p->dtype, a, ptrs, nq, chunks, part.mode, (hipStream_t)s);
       HIP_TRY(e);
     }
     if (p->profiling) {

@@ -88,7 +88,16 @@ class Case:
         xs = [make_act(rng, T, lay.d_in[s], lay.dtype, x_std) for s in slots]
         y0 = [np.zeros((T, lay.d_out[s]), RAW_DTYPE[lay.dtype]) if y0_zero else make_act(rng, T, lay.d_out[s], lay.dtype)
               for s in slots]
-        # GPU side
+        # GPU side: once with the ordinary kernels, once with the cooperative kernels of small calls
+        for coop in getattr(self, "coop_modes", (0, 1 << 30)):
+            self.gpool.set_option("coop_max_workgroups_shrink", coop)
+            self.gpool.set_option("coop_max_workgroups_expand", coop)
+            out = self._run_gpu(t2a, slots, xs, y0, check)
+        return out
+
+    def _run_gpu(self, t2a, slots, xs, y0, check):
+        torch, lay = self.torch, self.lay
+        T = len(t2a)
         batch = self.gpool.batch_begin(t2a, self.stream)
         perm, seg_adapter, seg_start = self.gpool.batch_info(batch)
         o_perm, o_sa, o_ss = self.opool.translate(t2a)
