@@ -37,12 +37,14 @@ constexpr int kMfmaRows = PLORA_MFMA_ROWS;      // rows of A per matrix-core shr
 constexpr int kMfmaCols = 128;          // columns of B per matrix-core expand pass
 constexpr int kPtWindow = 1024;         // page-table entries a shrink item may stage in LDS
 constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for (4 KiB of LDS)
+constexpr int kItemOnce = 0x100;        // flag in ItemRec::kind
 constexpr int kXcds = 8;                // consecutive workgroups go to consecutive XCDs
 
 // One wavefront's worth of work, self-contained so that a wavefront needs a single 32-byte read
 // before it can start fetching page-table entries, activations and weights.
 struct ItemRec {
-  int16_t kind;    // -1 = padding (nothing to do), 0 = vector-ALU item, 1 = matrix-core item
+  int16_t kind;    // -1 = padding (nothing to do), 0 = vector-ALU item, 1 = matrix-core item; + kItemOnce if no
+                   // other item of the batch reads this item's weights (they are then fetched with streaming loads)
   int16_t ntok;    // tokens of the item
   int16_t rank;    // rank of the adapter (0 = tokens without adapter: shrink only clears v)
   int16_t j0;      // shrink: first row of A;  expand: unused

@@ -39,8 +39,6 @@ template <int DT> struct Elt { static constexpr int B = 2, VEC = 8; };
 template <> struct Elt<2> { static constexpr int B = 4, VEC = 4; };
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
-// Weights are read once per batch: a streaming (non-temporal) load keeps them from pushing the
-// re-used x / y / v rows and page-table entries out of L2.
 // Minimum workgroups per CU the compiler must leave room for (bounds the VGPR budget).
 #ifndef PLORA_SHRINK_WG_PER_CU
 #define PLORA_SHRINK_WG_PER_CU 3
@@ -48,19 +46,51 @@ __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<
 #ifndef PLORA_EXPAND_WG_PER_CU
 #define PLORA_EXPAND_WG_PER_CU 3
 #endif
+// PLORA_NT_WEIGHTS: 0 = weight loads always cached, 1 = streaming (non-temporal) loads for items
+// whose weights no other item reads (record flag), 2 = streaming loads for every item.
 #ifndef PLORA_NT_WEIGHTS
-#define PLORA_NT_WEIGHTS 0
+#define PLORA_NT_WEIGHTS 1
 #endif
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+// Weights that are read once per batch by this item alone are fetched with streaming loads: they
+// then do not push the re-used x / v rows, page-table entries and other items' shared weight rows out
+// of the caches.  Weights that a neighbouring item reads again stay ordinary loads.
+template <bool NT>
 __device__ __forceinline__ uint4 ldw16(const void* p) {
-#if PLORA_NT_WEIGHTS
+  if constexpr (NT) {
+    const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    return make_uint4(q.x, q.y, q.z, q.w);
+  } else {
+    return *reinterpret_cast<const uint4*>(p);
+  }
+}
+// Record flag (bit 8 of a non-negative kind): no other item of the batch reads this item's weights.
+__device__ __forceinline__ int item_kind(const ItemRec& it) { return it.kind < 0 ? -1 : (it.kind & 0xff); }
+__device__ __forceinline__ bool item_once(const ItemRec& it) {
+  return PLORA_NT_WEIGHTS == 2 || (PLORA_NT_WEIGHTS == 1 && it.kind >= 0 && (it.kind & kItemOnce) != 0);
+}
+// y is read once and written once per step: streaming (non-temporal) accesses (bit 0: loads, bit 1:
+// stores), so that its lines neither stay in the caches nor wait there to be written back during
+// the next kernel.
+#ifndef PLORA_NT_Y
+#define PLORA_NT_Y 3
+#endif
+__device__ __forceinline__ uint4 ldy16(const void* p) {
+#if PLORA_NT_Y & 1
   const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(q.x, q.y, q.z, q.w);
 #else
   return *reinterpret_cast<const uint4*>(p);
 #endif
 }
-__device__ __forceinline__ void st16(void* p, uint4 q) { *reinterpret_cast<uint4*>(p) = q; }
+__device__ __forceinline__ void sty16(void* p, uint4 q) {
+#if PLORA_NT_Y & 2
+  u32x4_t t; t.x = q.x; t.y = q.y; t.z = q.z; t.w = q.w;
+  __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
+#else
+  *reinterpret_cast<uint4*>(p) = q;
+#endif
+}
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
   return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
@@ -144,7 +174,7 @@ __device__ __forceinline__ int lane_id() { return (int)(threadIdx.x & 63); }
 // ------------------------------------------------------------------------------------------
 // shrink, vector-ALU item
 // ------------------------------------------------------------------------------------------
-template <int DT, int NT, int ROWS, bool TAIL>
+template <int DT, int NT, int ROWS, bool TAIL, bool NTW>
 __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uint8_t* __restrict__ x, const int64_t* tok,
                                                   const int32_t* lds_pt, uint32_t win0, uint64_t base, uint64_t rowb,
                                                   int nrows, int d_in, int k0, float (*acc)[NT]) {
@@ -163,7 +193,7 @@ __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uin
     const int jr = imin(jj, nrows - 1);
     const uint64_t voff = base + (uint64_t)jr * rowb + (uint64_t)kk * EB;
     const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(voff >> lp) - win0];
-    wq[jj] = ldw16(a.slab + (pg << lp) + (voff & pmask));
+    wq[jj] = ldw16<NTW>(a.slab + (pg << lp) + (voff & pmask));
   }
 #pragma unroll
   for (int i = 0; i < NT; ++i)
@@ -197,7 +227,7 @@ __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uin
   }
 }
 
-template <int DT, int NT, int ROWS>
+template <int DT, int NT, int ROWS, bool NTW>
 __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt) {
@@ -238,8 +268,8 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
   constexpr int CH = kWave * VEC;
   const int full = d_in / CH * CH;
   for (int k0 = 0; k0 < full; k0 += CH)
-    shrink_valu_chunk<DT, NT, ROWS, false>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
-  if (full < d_in) shrink_valu_chunk<DT, NT, ROWS, true>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
+    shrink_valu_chunk<DT, NT, ROWS, false, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
+  if (full < d_in) shrink_valu_chunk<DT, NT, ROWS, true, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
 
 #pragma unroll
   for (int jj = 0; jj < ROWS; ++jj)
@@ -253,9 +283,15 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
 template <int DT>
 __device__ __forceinline__ void shrink_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
                                                  const uint8_t* x, float* v, int32_t* lds_pt) {
-  if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows>(a, it, sl, x, v, lds_pt);
-  else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows>(a, it, sl, x, v, lds_pt);
-  else shrink_valu_body<DT, kValuTok, kShrinkRows>(a, it, sl, x, v, lds_pt);
+  if (item_once(it)) {
+    if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows, true>(a, it, sl, x, v, lds_pt);
+    else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows, true>(a, it, sl, x, v, lds_pt);
+    else shrink_valu_body<DT, kValuTok, kShrinkRows, true>(a, it, sl, x, v, lds_pt);
+  } else {
+    if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows, false>(a, it, sl, x, v, lds_pt);
+    else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows, false>(a, it, sl, x, v, lds_pt);
+    else shrink_valu_body<DT, kValuTok, kShrinkRows, false>(a, it, sl, x, v, lds_pt);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -282,7 +318,7 @@ __device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const ItemR
   }
 }
 
-template <int DT, int NT>
+template <int DT, int NT, bool NTW>
 __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg,
                                                  int chunk) {
@@ -309,7 +345,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
   for (int i = 0; i < NT; ++i) {
     vrow[i] = v + (int64_t)it.tok[i] * vs;
     yp[i] = y + ((uint64_t)it.tok[i] * d_out + (ok ? n : n0w)) * EB;
-    yq[i] = ld16(yp[i]);  // requested now, used after the loop
+    yq[i] = ldy16(yp[i]);  // requested now, used after the loop
   }
   wave_sync();
   float acc[NT][VEC];
@@ -328,7 +364,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
       const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
       const int2 pp = lds_pg[j + u];
       const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-      wq[u] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+      wq[u] = ldw16<NTW>(a.slab + (pg << lp) + (inpage & pmask));
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -348,7 +384,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
     const int2 pp = lds_pg[j];
     const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
     float wf[VEC];
-    unpack<DT>(ldw16(a.slab + (pg << lp) + (inpage & pmask)), wf);
+    unpack<DT>(ldw16<NTW>(a.slab + (pg << lp) + (inpage & pmask)), wf);
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
       const float vj = vrow[i][j];
@@ -364,7 +400,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
       unpack<DT>(yq[i], yf);
 #pragma unroll
       for (int e = 0; e < VEC; ++e) yf[e] = yf[e] + it.scale * acc[i][e];
-      st16(yp[i], pack<DT>(yf));
+      sty16(yp[i], pack<DT>(yf));
     }
   }
 }
@@ -372,9 +408,15 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
 template <int DT>
 __device__ __forceinline__ void expand_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
                                                  const float* v, uint8_t* y, int2* lds_pg, int chunk) {
-  if (it.ntok <= 1) expand_valu_body<DT, 1>(a, it, sl, v, y, lds_pg, chunk);
-  else if (it.ntok == 2) expand_valu_body<DT, 2>(a, it, sl, v, y, lds_pg, chunk);
-  else expand_valu_body<DT, kValuTok>(a, it, sl, v, y, lds_pg, chunk);
+  if (item_once(it)) {
+    if (it.ntok <= 1) expand_valu_body<DT, 1, true>(a, it, sl, v, y, lds_pg, chunk);
+    else if (it.ntok == 2) expand_valu_body<DT, 2, true>(a, it, sl, v, y, lds_pg, chunk);
+    else expand_valu_body<DT, kValuTok, true>(a, it, sl, v, y, lds_pg, chunk);
+  } else {
+    if (it.ntok <= 1) expand_valu_body<DT, 1, false>(a, it, sl, v, y, lds_pg, chunk);
+    else if (it.ntok == 2) expand_valu_body<DT, 2, false>(a, it, sl, v, y, lds_pg, chunk);
+    else expand_valu_body<DT, kValuTok, false>(a, it, sl, v, y, lds_pg, chunk);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -413,7 +455,7 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
 constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16 pad per LDS row
 static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
-template <int DT>
+template <int DT, bool NTW>
 __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                   const uint8_t* __restrict__ x, float* __restrict__ v,
                                                   uint8_t (*tile)[2][kSmRows * kSmPitch], int32_t* lds_pt) {
@@ -478,7 +520,7 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
     for (int i = 0; i < 4; ++i) {
       const uint64_t vo = wrow[i] + kb;
       const uint64_t pg = (uint64_t)(uint32_t)lds_pt[(uint32_t)(vo >> lp) - win0];
-      wq[i] = ldw16(a.slab + (pg << lp) + (vo & pmask));
+      wq[i] = ldw16<NTW>(a.slab + (pg << lp) + (vo & pmask));
       xq[i] = ld16(xrow[i] + kb);
     }
     if (!ok) {
@@ -562,7 +604,7 @@ __device__ __forceinline__ void split_hi_lo(const float* f, uint4& hi, uint4& lo
 }
 
 // One K-step (32 rows of B) of the matrix-core expand for one 128-column pass.
-template <int DT, int MT, bool TAIL>
+template <int DT, int MT, bool TAIL, bool NTW>
 __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int2* lds_pg, const float* const* vrow,
                                                   uint64_t base, uint64_t rowb, uint32_t lane_b, int r, int jb,
                                                   f32x4 (*acc)[8]) {
@@ -593,7 +635,7 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
     const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
     const int2 pp = lds_pg[je];
     const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-    wr[jj] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+    wr[jj] = ldw16<NTW>(a.slab + (pg << lp) + (inpage & pmask));
   }
   if (TAIL) {
 #pragma unroll
@@ -626,7 +668,7 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
 // 512-column chunk and all MT token tiles, loads its tile of B straight into registers (each tile is
 // used by one wavefront only, so nothing is shared and there is no barrier after the page staging),
 // transposes and multiplies.
-template <int DT, int MT>
+template <int DT, int MT, bool NTW>
 __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                       const float* __restrict__ v, uint8_t* __restrict__ y,
                                                       const int2* lds_pg, int chunk, uint64_t base, uint64_t rowb) {
@@ -659,10 +701,10 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-    for (int i = 0; i < 4; ++i) yq[mt][i] = ld16(y + ((uint64_t)trow[mt][i] * d_out + nn) * EB);
+    for (int i = 0; i < 4; ++i) yq[mt][i] = ldy16(y + ((uint64_t)trow[mt][i] * d_out + nn) * EB);
   int jb = 0;
-  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
-  if (jb < r) expand_mfma_kstep<DT, MT, true>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+  if (jb < r) expand_mfma_kstep<DT, MT, true, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
   if (!ok) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -673,7 +715,7 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
         unpack<DT>(yq[mt][i], yf);
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
-        st16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
+        sty16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
       }
     }
   }
@@ -717,7 +759,8 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
   }
   if (kMfmaTokE <= kMfmaTokCols || it.ntok <= kMfmaTokCols) {  // uniform: few tokens -> split the columns, not the tokens
     __syncthreads();
-    expand_mfma_cols_body<DT, 1>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+    if (item_once(it)) expand_mfma_cols_body<DT, 1, true>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+    else expand_mfma_cols_body<DT, 1, false>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
     return;
   }
   if constexpr (kMfmaTokE > 32) {
@@ -754,7 +797,7 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
           const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
           const int2 pp = lds_pg[je];
           const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-          wr[jj] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+          wr[jj] = ldw16<false>(a.slab + (pg << lp) + (inpage & pmask));
         }
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj)
@@ -808,7 +851,7 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
         if (n < d_out) {
           uint4 yq[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) yq[i] = ld16(y + ((uint64_t)trow[i] * d_out + n) * EB);
+          for (int i = 0; i < 4; ++i) yq[i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             if (wave * 16 + g * 4 + i < it.ntok) {
@@ -816,7 +859,7 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
               unpack<DT>(yq[i], yf);
 #pragma unroll
               for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[ct][cc][i];
-              st16(y + ((uint64_t)trow[i] * d_out + n) * EB, pack<DT>(yf));
+              sty16(y + ((uint64_t)trow[i] * d_out + n) * EB, pack<DT>(yf));
             }
           }
         }
@@ -842,8 +885,9 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
   float* v = (float*)p.b[q];
   const ItemRec first = a.items[4 * blk];
   if constexpr (DT != 2) {
-    if (first.kind == 1) {
-      shrink_mfma4_body<DT>(a, first, sl, x, v, tile, lds_pt);
+    if (item_kind(first) == 1) {
+      if (item_once(first)) shrink_mfma4_body<DT, true>(a, first, sl, x, v, tile, lds_pt);
+      else shrink_mfma4_body<DT, false>(a, first, sl, x, v, tile, lds_pt);
       return;
     }
   }
@@ -868,7 +912,7 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
   uint8_t* y = (uint8_t*)p.b[q];
   const ItemRec first = a.items[4 * blk];
   if constexpr (DT != 2) {
-    if (first.kind == 1) {
+    if (item_kind(first) == 1) {
       expand_mfma4_body<DT>(a, first, sl, v, y, op, lds_pg, chunk);
       return;
     }
@@ -888,7 +932,7 @@ template <int DT>
 __global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int2 lds_pg[kMaxRank];
   const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
-  if (it.kind != 0) return;
+  if (item_kind(it) != 0) return;
   const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
@@ -899,7 +943,7 @@ template <int DT>
 __global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int32_t lds_pt[kPtWindow / 4];
   const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
-  if (it.kind != 0) return;
+  if (item_kind(it) != 0) return;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
   shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
@@ -913,7 +957,7 @@ __global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, cons
 // rows (expand) and add their partial sums through LDS in wavefront order, so the result does not
 // depend on timing.
 // ------------------------------------------------------------------------------------------
-template <int DT, int NT>
+template <int DT, int NT, bool NTW>
 __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt, float (*red)[kShrinkRows * kValuTok]) {
@@ -951,9 +995,9 @@ __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const Item
   constexpr int CH = kWave * VEC;
   const int full = d_in / CH * CH;
   for (int k0 = wave * CH; k0 < full; k0 += 4 * CH)
-    shrink_valu_chunk<DT, NT, kShrinkRows, false>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
+    shrink_valu_chunk<DT, NT, kShrinkRows, false, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
   if (full < d_in && ((full / CH) & 3) == wave)
-    shrink_valu_chunk<DT, NT, kShrinkRows, true>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
+    shrink_valu_chunk<DT, NT, kShrinkRows, true, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
 #pragma unroll
   for (int jj = 0; jj < kShrinkRows; ++jj)
 #pragma unroll
@@ -975,14 +1019,20 @@ __global__ __launch_bounds__(256) void k_shrink_coop(const LaunchArgs a, const S
   __shared__ int32_t lds_pt[kPtWindow / 4];
   __shared__ float red[4][kShrinkRows * kValuTok];
   const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
-  if (it.kind != 0) return;  // uniform over the workgroup
+  if (item_kind(it) != 0) return;  // uniform over the workgroup
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
   const uint8_t* x = (const uint8_t*)p.a[q];
   float* v = (float*)p.b[q];
-  if (it.ntok <= 1) shrink_coop_body<DT, 1>(a, it, sl, x, v, lds_pt, red);
-  else if (it.ntok == 2) shrink_coop_body<DT, 2>(a, it, sl, x, v, lds_pt, red);
-  else shrink_coop_body<DT, kValuTok>(a, it, sl, x, v, lds_pt, red);
+  if (item_once(it)) {
+    if (it.ntok <= 1) shrink_coop_body<DT, 1, true>(a, it, sl, x, v, lds_pt, red);
+    else if (it.ntok == 2) shrink_coop_body<DT, 2, true>(a, it, sl, x, v, lds_pt, red);
+    else shrink_coop_body<DT, kValuTok, true>(a, it, sl, x, v, lds_pt, red);
+  } else {
+    if (it.ntok <= 1) shrink_coop_body<DT, 1, false>(a, it, sl, x, v, lds_pt, red);
+    else if (it.ntok == 2) shrink_coop_body<DT, 2, false>(a, it, sl, x, v, lds_pt, red);
+    else shrink_coop_body<DT, kValuTok, false>(a, it, sl, x, v, lds_pt, red);
+  }
 }
 
 template <int DT, int NT>
@@ -1018,7 +1068,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
   const int tokw = wave == 1 ? it.tok[1] : wave == 2 ? it.tok[2] : wave == 3 ? it.tok[3] : it.tok[0];  // no indexed array
   uint8_t* yp = y + ((uint64_t)(fin ? tokw : it.tok[0]) * d_out + (ok ? n : n0w)) * EB;
   uint4 yq = make_uint4(0, 0, 0, 0);
-  if (fin) yq = ld16(yp);
+  if (fin) yq = ldy16(yp);
   const float* vrow[NT];
 #pragma unroll
   for (int i = 0; i < NT; ++i) vrow[i] = v + (int64_t)it.tok[i] * vs;
@@ -1040,7 +1090,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
       const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
       const int2 pp = lds_pg[j + u];
       const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-      wq[u] = ldw16(a.slab + (pg << lp) + (inpage & pmask));
+      wq[u] = ldw16<false>(a.slab + (pg << lp) + (inpage & pmask));
     }
 #pragma unroll
     for (int u = 0; u < U; ++u) {
@@ -1061,7 +1111,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
       const int2 pp = lds_pg[j];
       const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
       float wf[VEC];
-      unpack<DT>(ldw16(a.slab + (pg << lp) + (inpage & pmask)), wf);
+      unpack<DT>(ldw16<false>(a.slab + (pg << lp) + (inpage & pmask)), wf);
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
         const float vj = vrow[i][j];
@@ -1085,7 +1135,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
       const float s2 = red[((2 * kValuTok + wave) * 8 + e) * kWave + lane], s3 = red[((3 * kValuTok + wave) * 8 + e) * kWave + lane];
       yf[e] = yf[e] + it.scale * (((s0 + s1) + s2) + s3);
     }
-    st16(yp, pack<DT>(yf));
+    sty16(yp, pack<DT>(yf));
   }
 }
 
@@ -1095,7 +1145,7 @@ __global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const S
   __shared__ int2 lds_pg[kMaxRank];
   __shared__ float red[4 * kValuTok * 8 * kWave];  // 32 KiB
   const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
-  if (it.kind != 0) return;  // uniform over the workgroup
+  if (item_kind(it) != 0) return;  // uniform over the workgroup
   const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];

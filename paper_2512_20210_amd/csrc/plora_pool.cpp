@@ -96,7 +96,7 @@ struct plora_pool {
   // reaches min_work (min_tokens 0 = never).  Shrink: work = n * r.  Expand: work = n * r * (r / r
   // rounded up to 32), the second factor being the used part of the 32-row contraction tile.
   int mfma_min_tokens = 16, mfma_min_tokens_expand = 64;
-  int64_t mfma_min_work = 64, mfma_min_work_expand = 768;
+  int64_t mfma_min_work = 64, mfma_min_work_expand = 1536;
   int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
@@ -535,7 +535,9 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
         for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
           for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokS) {
             const int16_t nt = (int16_t)std::min(kMfmaTokS, b1 - t0);
-            gs.items.push_back(ItemRec{1, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+            // the rows of A are read by one item only when the group is a single token tile
+            const int16_t kind = (int16_t)(n <= kMfmaTokS ? 1 | kItemOnce : 1);
+            gs.items.push_back(ItemRec{kind, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
             gs.cost += std::min(kMfmaRows, a.rank - j0) + nt;
           }
         grp[0][1].push_back(std::move(gs));
@@ -547,7 +549,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
         for (int32_t t0 = b0; t0 < b1;) {
           const int32_t left = b1 - t0;
           const int16_t nt = (int16_t)std::min(left <= kMfmaColsMaxGroup ? kMfmaTokCols : kMfmaTokE, left);
-          ge.items.push_back(ItemRec{1, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+          const int16_t kind = (int16_t)(n <= kMfmaTokCols ? 1 | kItemOnce : 1);
+          ge.items.push_back(ItemRec{kind, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
           ge.cost += a.rank + 2 * nt;
           t0 += nt;
         }
@@ -560,7 +563,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       std::vector<ItemRec> tg;  // one record per token group
       for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
         const int16_t nt = (int16_t)std::min(kValuTok, n - t0);
-        ItemRec it{0, nt, rank, 0, a.scale, pt_off, {0, 0, 0, 0}};
+        // one token group: nobody else reads the group's weights
+        ItemRec it{(int16_t)(n <= kValuTok ? kItemOnce : 0), nt, rank, 0, a.scale, pt_off, {0, 0, 0, 0}};
         for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
         tg.push_back(it);
         coop[1].push_back(it);
