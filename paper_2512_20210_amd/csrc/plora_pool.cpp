@@ -96,7 +96,7 @@ struct plora_pool {
   // reaches min_work (min_tokens 0 = never).  Shrink: work = n * r.  Expand: work = n * r * (r / r
   // rounded up to 32), the second factor being the used part of the 32-row contraction tile.
   int mfma_min_tokens = 16, mfma_min_tokens_expand = 64;
-  int64_t mfma_min_work = 64, mfma_min_work_expand = 1536;
+  int64_t mfma_min_work = 64, mfma_min_work_expand = 384;
   int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
