@@ -1,20 +1,31 @@
 // gfx950 kernels of the paged multi-LoRA delta (Sec. II-A Eq. 1 over the page pool of Sec. III-C;
 // Sec. IV "Memory Manager": kernels that read adapter weights from non-contiguous pages).
 //
-// Work decomposition: one work item = one 64-lane wavefront = one workgroup.  Items come from the
-// batch translation (tokens grouped by adapter), so every weight byte a batch needs is fetched
-// from HBM once per group of tokens, not once per token.
+// Work decomposition.  Items come from the batch translation (tokens grouped by adapter), so every
+// weight byte a batch needs is fetched from HBM once per group of tokens, not once per token.  The
+// work list of a launch is a sequence of blocks of 4 records, one 256-thread workgroup per block:
+// either one matrix-core item that the 4 wavefronts share, or up to 4 vector-ALU items, one per
+// wavefront.
 //
 //   shrink, vector-ALU item : up to 8 rows of A x up to 4 tokens.  Lanes stride along d_in with
-//                             16-byte loads, accumulate in fp32 and finish with a wavefront
-//                             reduction.
-//   shrink, matrix-core item: 32 rows of A x up to 32 tokens, v_mfma_f32_16x16x32 (bf16 / f16), by a
-//                             workgroup of 4 wavefronts that split d_in; operands staged in LDS.
+//                             16-byte loads, accumulate in fp32 (packed dot products for 16-bit
+//                             elements) and finish with a wavefront reduction.
+//   shrink, matrix-core item: 32 rows of A x up to 32 tokens, v_mfma_f32_16x16x32 (bf16 / f16), by
+//                             4 wavefronts that split d_in; operands staged in LDS.
 //   expand, vector-ALU item : all rows of B x 64 lanes x 16 bytes of columns x up to 4 tokens;
 //                             no reduction, read-modify-write of y.
-//   expand, matrix-core item: all rows of B x 512 columns x up to 64 tokens by a workgroup of 4
-//                             wavefronts with B stationary in LDS; v is split into a high and a low
-//                             half so that fp32 v loses nothing that matters.
+//   expand, matrix-core item: all rows of B x 512 columns; up to 16 tokens: every wavefront its own
+//                             128 columns, B transposed in registers; 33 to 64 tokens: B stationary
+//                             in LDS, one 16-token tile per wavefront.  v is split into a high and a
+//                             low half so that fp32 v loses nothing that matters.
+//
+// Two more launch forms use the vector-ALU records alone: one record per single-wavefront workgroup,
+// and the cooperative kernels for calls too small to fill the machine (one record per 256-thread
+// workgroup whose wavefronts split the record's chain of loads).
+//
+// Cache policy: y (read once, written once) goes through streaming loads and stores, and so do the
+// weights of items whose rows no other item reads; x, v, page tables and weights that the token
+// groups of one adapter share stay ordinary accesses.
 //
 // Address translation: virtual byte o of an adapter is at slab + pt[o >> log2P] * P + (o & (P-1)).
 // A 16-byte vector never straddles a page (all offsets are multiples of 16).  Each item stages the
