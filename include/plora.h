@@ -158,9 +158,12 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * always) or when its work reaches "mfma_min_work" / "mfma_min_work_expand" (defaults 64 / 384; 1 ..
  * 2^30), where work = n * r for shrink and n * r * r / (r rounded up to a multiple of 32) for expand;
  * they take effect for batches begun afterwards.  "slot_major" (-1 =
- * slots are the fastest grid dimension when their count is a multiple of 8, 0 never, 1 always),
- * "xcd_remap" (1 = for launches whose fastest dimension is the work item, neighbouring work items
- * share an XCD), "split_shrink" / "split_expand" (1 = when slots are the fastest dimension, launch the
+ * slots are the fastest grid dimension when their count is a multiple of 8, 0 never, 1 always; for
+ * expand also 2 = the 512-column chunks of one work item are the fastest dimension, so that
+ * neighbouring workgroups read neighbouring pieces of the same rows of B) and "xcd_remap" (1 = for
+ * launches whose fastest dimension is not the slot, neighbouring work items share an XCD) set the
+ * launch geometry of both operations; with the suffix "_shrink" / "_expand" of one (defaults: shrink
+ * -1 and 1, expand 2 and 0).  "split_shrink" / "split_expand" (1 = when slots are the fastest dimension, launch the
  * matrix-core blocks in the 256-thread kernel and then the vector-ALU items one per single-wavefront
  * workgroup, instead of one mixed launch; defaults 0 / 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
  * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound

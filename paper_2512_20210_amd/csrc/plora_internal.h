@@ -77,7 +77,7 @@ struct LaunchArgs {
   int32_t pad0;
   int32_t log2_page;
   int32_t v_stride;       // = max_rank
-  int32_t slot_fastest;   // 1: grid = (slots, items, chunks); 0: grid = (items, chunks, slots)
+  int32_t slot_fastest;   // 1: grid = (slots, items, chunks); 0: grid = (items, chunks, slots); 2 (expand): (chunks, items, slots)
   int32_t pad;
 };
 

@@ -911,13 +911,19 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
 // Expand: same block structure as shrink (one matrix-core item per workgroup, or up to 4
 // independent vector-ALU items, one per wavefront); the column chunk (512 columns) comes from the
 // grid.
+// Grid coordinates of an expand workgroup: list position, 512-column chunk, slot entry.
+__device__ __forceinline__ void expand_coords(const LaunchArgs& a, int& pos, int& chunk, int& q) {
+  if (a.slot_fastest == 1) { q = blockIdx.x; pos = blockIdx.y; chunk = blockIdx.z; }
+  else if (a.slot_fastest == 2) { chunk = blockIdx.x; pos = blockIdx.y; q = blockIdx.z; }
+  else { pos = blockIdx.x; chunk = blockIdx.y; q = blockIdx.z; }
+}
+
 template <int DT>
 __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const LaunchArgs a, const SlotPtrs p) {
   __shared__ __align__(16) uint4 op[4][8][kWave];  // 4 staged tiles of B in MFMA operand order (32 KiB)
   __shared__ int2 lds_pg[kMaxRank];
-  const int blk = a.slot_fastest ? blockIdx.y : blockIdx.x;
-  const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
-  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
+  int blk, chunk, q;
+  expand_coords(a, blk, chunk, q);
   const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
@@ -942,10 +948,10 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
 template <int DT>
 __global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int2 lds_pg[kMaxRank];
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
+  int pos, chunk, q;
+  expand_coords(a, pos, chunk, q);
+  const ItemRec it = a.items[pos];
   if (item_kind(it) != 0) return;
-  const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
-  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
   expand_valu_item<DT>(a, it, sl, (const float*)p.a[q], (uint8_t*)p.b[q], lds_pg, chunk);
 }
@@ -1155,10 +1161,10 @@ __global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const S
   static_assert(kValuTok <= 4, "one finishing wavefront per token of the item");
   __shared__ int2 lds_pg[kMaxRank];
   __shared__ float red[4 * kValuTok * 8 * kWave];  // 32 KiB
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.y : blockIdx.x];
+  int pos, chunk, q;
+  expand_coords(a, pos, chunk, q);
+  const ItemRec it = a.items[pos];
   if (item_kind(it) != 0) return;  // uniform over the workgroup
-  const int chunk = a.slot_fastest ? blockIdx.z : blockIdx.y;
-  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
@@ -1210,7 +1216,8 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     const int nb = n_blocks - first < step ? n_blocks - first : step;
     a.items = a0.items + per * first;
     a.n_items = per * nb;
-    const dim3 grid = a.slot_fastest ? dim3(n_slots, nb, max_chunks) : dim3(nb, max_chunks, n_slots);
+    const dim3 grid = a.slot_fastest == 1 ? dim3(n_slots, nb, max_chunks)
+                    : a.slot_fastest == 2 ? dim3(max_chunks, nb, n_slots) : dim3(nb, max_chunks, n_slots);
     if (mode == 2) {
       if (dtype == 0) hipLaunchKernelGGL(k_expand_coop<0>, grid, dim3(256), 0, st, a, p);
       else if (dtype == 1) hipLaunchKernelGGL(k_expand_coop<1>, grid, dim3(256), 0, st, a, p);

@@ -97,13 +97,15 @@ struct plora_pool {
   // rounded up to 32), the second factor being the used part of the 32-row contraction tile.
   int mfma_min_tokens = 16, mfma_min_tokens_expand = 64;
   int64_t mfma_min_work = 64, mfma_min_work_expand = 384;
-  int xcd_remap = 1;  // item-fastest launches take the lists dealt into XCD queues
+  // launch geometry, [shrink, expand]
+  int xcd_remap[2] = {1, 0};  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
                          // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
   int64_t coop_max_workgroups[2] = {192, 1024};  // [shrink, expand]: calls whose ordinary launch would have at
                                                  // most this many workgroups use the cooperative kernels (0 = never)
-  int slot_major = -1; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always
+  int slot_major[2] = {-1, 2}; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always;
+                               // 2 (expand): the 512-column chunks are the fastest dimension
   // kernel timing (plora_profile)
   bool profiling = false;
   struct ProfRec { int cls; hipEvent_t e0, e1; };
@@ -429,9 +431,10 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->coop_max_workgroups[k == "coop_max_workgroups_expand"] = value;
     return PLORA_OK;
   }
-  if (k == "xcd_remap") {
+  if (k == "xcd_remap" || k == "xcd_remap_shrink" || k == "xcd_remap_expand") {
     if (value != 0 && value != 1) return PLORA_ERR_INVAL;
-    p->xcd_remap = (int)value;
+    if (k != "xcd_remap_expand") p->xcd_remap[0] = (int)value;
+    if (k != "xcd_remap_shrink") p->xcd_remap[1] = (int)value;
     return PLORA_OK;
   }
   if (k == "split_shrink" || k == "split_expand") {
@@ -439,9 +442,10 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->split[k == "split_expand"] = (int)value;
     return PLORA_OK;
   }
-  if (k == "slot_major") {
-    if (value < -1 || value > 1) return PLORA_ERR_INVAL;
-    p->slot_major = (int)value;
+  if (k == "slot_major" || k == "slot_major_shrink" || k == "slot_major_expand") {
+    if (value < -1 || value > (k == "slot_major_expand" ? 2 : 1)) return PLORA_ERR_INVAL;  // 2: chunks fastest
+    if (k != "slot_major_expand") p->slot_major[0] = (int)value;
+    if (k != "slot_major_shrink") p->slot_major[1] = (int)value;
     return PLORA_OK;
   }
   return PLORA_ERR_INVAL;
@@ -741,8 +745,8 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     q0 += nq;
     // slots fastest when that keeps every slot on one XCD and all XCDs equally loaded; else the
     // items are the fastest dimension and (optionally) come dealt into XCD queues
-    a.slot_fastest = (p->slot_major == 1 || (p->slot_major < 0 && nq % kXcds == 0)) ? 1 : 0;
-    int layout = (!a.slot_fastest && p->xcd_remap) ? 1 : 0;
+    a.slot_fastest = p->slot_major[op] == 2 ? 2 : (p->slot_major[op] == 1 || (p->slot_major[op] < 0 && nq % kXcds == 0)) ? 1 : 0;
+    int layout = (a.slot_fastest != 1 && p->xcd_remap[op]) ? 1 : 0;
     // a call that cannot fill the machine is bound by its longest dependent chain: cooperative kernels
     const bool coop = p->coop_max_workgroups[op] > 0 && b->n_items[op][2] > 0 &&
                       (int64_t)nq * (b->n_items[op][layout] / 4) * chunks <= p->coop_max_workgroups[op];

@@ -18,7 +18,8 @@ def test_cfg0_small_workload(oracle_mod):
     print("cfg0 t2a", t2a.tolist(), flush=True)
     for mfma, major, remap, split in ((0, -1, 1, 0), (1, 0, 1, 1), (4, 1, 1, 1), (2, 0, 0, 0), (1, 1, 0, 0)):
         case.set_mfma(mfma, 0 if mfma == 4 else mfma)
-        case.gpool.set_option("slot_major", major)
+        if major >= 0:  # -1: the library's own geometry (shrink: slots fastest if a multiple of 8, expand: chunks fastest)
+            case.gpool.set_option("slot_major", major)
         case.gpool.set_option("xcd_remap", remap)
         case.gpool.set_option("split_shrink", split)
         case.gpool.set_option("split_expand", 1 - split if major == 1 else split)
@@ -40,7 +41,8 @@ def test_ragged_multi_slot(oracle_mod, dtype, mfma, major):
     scales = [16.0 / r for r in ranks]
     case = Case(oracle_mod, lay, ranks, scales, 4096, 1024, seed=77, load_order=[4, 0, 6, 2, 1, 7, 3, 5],
                 mfma_min_tokens=mfma)
-    case.gpool.set_option("slot_major", major)
+    if major >= 0:
+        case.gpool.set_option("slot_major", major)
     case.gpool.set_option("split_shrink", 1 if mfma == 3 else 0)
     # scatter: evict two adapters and reload them so that their pages interleave
     case.evict(0)
@@ -135,7 +137,8 @@ def test_large_groups_panels_and_odd_strides(oracle_mod, dtype):
     t2a = np.concatenate([np.full(n, a, np.int32) for a, n in zip(range(5), (260, 70, 33, 7, 1))])
     rng.shuffle(t2a)
     for major in (-1, 1):
-        case.gpool.set_option("slot_major", major)
+        if major >= 0:  # first pass: the library's own geometry
+            case.gpool.set_option("slot_major", major)
         out = case.run(t2a, seed=3)
         print("panels dtype", dtype, "slot_major", major, "err_v", ["%.2g" % o["err_v"] for o in out],
               "err_y", ["%.2g" % o["err_y"] for o in out], flush=True)
