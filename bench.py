@@ -377,8 +377,8 @@ def run_churn(args):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=500)
+    ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
     ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="plain token threshold of the matrix-core items in shrink (default: the library's work-based rule)")
