@@ -172,8 +172,9 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * batches begun afterwards).  INVAL for an unknown key or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
-/* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand bracket
- * every kernel launch with a pair of HIP events on the launch stream; plora_profile(pool, 0) stops.
+/* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand attach a
+ * pair of HIP events to the kernel dispatches of every call (start of its first kernel, end of its
+ * last; nothing extra is queued on the stream); plora_profile(pool, 0) stops.
  * plora_profile_read waits for the recorded events and returns, per kernel (0 shrink, 1 expand), the
  * summed duration in ms and the number of launches since the last read, then clears the record.
  * ms and launches: host, 2 entries each. */

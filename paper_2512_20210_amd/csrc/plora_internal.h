@@ -90,8 +90,11 @@ struct LaunchArgs {
 // is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
 // slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row
 // of B (shrink: chunks = 1).
-hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int mode, hipStream_t st);
+// e0 / e1 (optional): events that take the start timestamp of the first and the end timestamp of the
+// last kernel of the call.
+hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int mode, hipStream_t st,
+                         hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
-                         hipStream_t st);
+                         hipStream_t st, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 
 }  // namespace plora

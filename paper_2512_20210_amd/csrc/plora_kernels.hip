@@ -38,6 +38,7 @@
 // 64-lane chunks carry no predicates, so that all loads of an iteration are in flight together; a
 // ragged last chunk goes through a predicated copy of the same code.
 #include "plora_internal.h"
+#include <hip/hip_ext.h>
 
 namespace plora {
 namespace {
@@ -1175,10 +1176,24 @@ __global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const S
 
 }  // namespace
 
-hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int mode, hipStream_t st) {
+// Launch with optional timing events attached to the dispatch itself (start / stop timestamps of
+// this kernel; no extra packets in the queue).
+typedef void (*KernelFn)(const LaunchArgs, const SlotPtrs);
+static void launch(KernelFn k, dim3 grid, dim3 block, hipStream_t st, hipEvent_t e0, hipEvent_t e1, const LaunchArgs& a,
+                   const SlotPtrs& p) {
+  if (e0 || e1) hipExtLaunchKernelGGL(k, grid, block, 0, st, e0, e1, 0, a, p);
+  else hipLaunchKernelGGL(k, grid, block, 0, st, a, p);
+}
+
+hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int mode, hipStream_t st,
+                         hipEvent_t e0, hipEvent_t e1) {
   const bool single = mode != 0;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
   if (!single && a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
+  static const KernelFn table[3][3] = {{k_shrink<0>, k_shrink<1>, k_shrink<2>},
+                                       {k_shrink_valu1<0>, k_shrink_valu1<1>, k_shrink_valu1<2>},
+                                       {k_shrink_coop<0>, k_shrink_coop<1>, k_shrink_coop<2>}};
+  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;
@@ -1188,26 +1203,21 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     a.items = a0.items + per * first;
     a.n_items = per * nb;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, nb) : dim3(nb, 1, n_slots);
-    if (mode == 2) {
-      if (dtype == 0) hipLaunchKernelGGL(k_shrink_coop<0>, grid, dim3(256), 0, st, a, p);
-      else if (dtype == 1) hipLaunchKernelGGL(k_shrink_coop<1>, grid, dim3(256), 0, st, a, p);
-      else hipLaunchKernelGGL(k_shrink_coop<2>, grid, dim3(256), 0, st, a, p);
-    } else if (single) {
-      if (dtype == 0) hipLaunchKernelGGL(k_shrink_valu1<0>, grid, dim3(kWave), 0, st, a, p);
-      else if (dtype == 1) hipLaunchKernelGGL(k_shrink_valu1<1>, grid, dim3(kWave), 0, st, a, p);
-      else hipLaunchKernelGGL(k_shrink_valu1<2>, grid, dim3(kWave), 0, st, a, p);
-    } else if (dtype == 0) hipLaunchKernelGGL(k_shrink<0>, grid, dim3(256), 0, st, a, p);
-    else if (dtype == 1) hipLaunchKernelGGL(k_shrink<1>, grid, dim3(256), 0, st, a, p);
-    else hipLaunchKernelGGL(k_shrink<2>, grid, dim3(256), 0, st, a, p);
+    launch(table[mode][dtype], grid, dim3(mode == 1 ? kWave : 256), st, first == 0 ? e0 : nullptr,
+           first + step >= n_blocks ? e1 : nullptr, a, p);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
-                         hipStream_t st) {
+                         hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
   const bool single = mode != 0;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
   if ((!single && a0.n_items % 4) || max_chunks > 65535) return hipErrorInvalidValue;
+  static const KernelFn table[3][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
+                                       {k_expand_valu1<0>, k_expand_valu1<1>, k_expand_valu1<2>},
+                                       {k_expand_coop<0>, k_expand_coop<1>, k_expand_coop<2>}};
+  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;
@@ -1218,17 +1228,8 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     a.n_items = per * nb;
     const dim3 grid = a.slot_fastest == 1 ? dim3(n_slots, nb, max_chunks)
                     : a.slot_fastest == 2 ? dim3(max_chunks, nb, n_slots) : dim3(nb, max_chunks, n_slots);
-    if (mode == 2) {
-      if (dtype == 0) hipLaunchKernelGGL(k_expand_coop<0>, grid, dim3(256), 0, st, a, p);
-      else if (dtype == 1) hipLaunchKernelGGL(k_expand_coop<1>, grid, dim3(256), 0, st, a, p);
-      else hipLaunchKernelGGL(k_expand_coop<2>, grid, dim3(256), 0, st, a, p);
-    } else if (single) {
-      if (dtype == 0) hipLaunchKernelGGL(k_expand_valu1<0>, grid, dim3(kWave), 0, st, a, p);
-      else if (dtype == 1) hipLaunchKernelGGL(k_expand_valu1<1>, grid, dim3(kWave), 0, st, a, p);
-      else hipLaunchKernelGGL(k_expand_valu1<2>, grid, dim3(kWave), 0, st, a, p);
-    } else if (dtype == 0) hipLaunchKernelGGL(k_expand<0>, grid, dim3(256), 0, st, a, p);
-    else if (dtype == 1) hipLaunchKernelGGL(k_expand<1>, grid, dim3(256), 0, st, a, p);
-    else hipLaunchKernelGGL(k_expand<2>, grid, dim3(256), 0, st, a, p);
+    launch(table[mode][dtype], grid, dim3(mode == 1 ? kWave : 256), st, first == 0 ? e0 : nullptr,
+           first + step >= n_blocks ? e1 : nullptr, a, p);
   }
   return hipGetLastError();
 }

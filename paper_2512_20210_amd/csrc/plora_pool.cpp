@@ -766,21 +766,22 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
         if (!p->prof_free.empty()) { *ev = p->prof_free.back(); p->prof_free.pop_back(); }
         else HIP_TRY(hipEventCreate(ev));
       }
-      HIP_TRY(hipEventRecord(rec.e0, (hipStream_t)s));
     }
-    for (const Part& part : parts) {
+    const int last_part = parts[1].n > 0 ? 1 : 0;
+    for (int k = 0; k < 2; ++k) {
+      const Part& part = parts[k];
       if (part.n == 0) continue;
       a.items = part.items;
       a.n_items = part.n;
+      // the events ride on the dispatches: start of the first kernel, end of the last
+      const hipEvent_t e0 = (k == 0 || parts[0].n == 0) ? rec.e0 : nullptr;
+      const hipEvent_t e1 = k == last_part ? rec.e1 : nullptr;
       hipError_t e;
-      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, part.mode, (hipStream_t)s);
-      else e = launch_expand(p->dtype, a, ptrs, nq, chunks, part.mode, (hipStream_t)s);
+      if (is_shrink) e = launch_shrink(p->dtype, a, ptrs, nq, part.mode, (hipStream_t)s, e0, e1);
+      else e = launch_expand(p->dtype, a, ptrs, nq, chunks, part.mode, (hipStream_t)s, e0, e1);
       HIP_TRY(e);
     }
-    if (p->profiling) {
-      HIP_TRY(hipEventRecord(rec.e1, (hipStream_t)s));
-      p->prof.push_back(rec);
-    }
+    if (p->profiling) p->prof.push_back(rec);
   }
   return PLORA_OK;
 }

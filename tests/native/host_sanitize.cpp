@@ -13,8 +13,8 @@
 #include "plora_internal.h"
 
 namespace plora {
-hipError_t launch_shrink(int, const LaunchArgs&, const SlotPtrs&, int, int, hipStream_t) { return hipSuccess; }
-hipError_t launch_expand(int, const LaunchArgs&, const SlotPtrs&, int, int, int, hipStream_t) { return hipSuccess; }
+hipError_t launch_shrink(int, const LaunchArgs&, const SlotPtrs&, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
+hipError_t launch_expand(int, const LaunchArgs&, const SlotPtrs&, int, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 }  // namespace plora
 
 #define CHECK(c) do { if (!(c)) { std::printf("CHECK failed at line %d: %s\n", __LINE__, #c); std::exit(1); } } while (0)
