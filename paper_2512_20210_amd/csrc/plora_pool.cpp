@@ -44,6 +44,22 @@ struct Adapter {
   std::shared_ptr<Event> last_use;
 };
 
+// Work items of one operation in flat storage: the records of group g (one adapter's items that
+// share x rows, v rows or a piece of B and should meet in one XCD's L2) are items[first[g] ..
+// first[g + 1]).  The vectors live in the pool and keep their capacity from batch to batch.
+struct ItemGroups {
+  std::vector<ItemRec> items;
+  std::vector<uint32_t> first;  // size groups + 1 once closed
+  std::vector<double> cost;
+  void clear() { items.clear(); first.assign(1, 0); cost.clear(); }
+  void close_group(double c) {
+    if (items.size() == first.back()) return;  // empty group
+    first.push_back((uint32_t)items.size());
+    cost.push_back(c);
+  }
+  size_t groups() const { return cost.size(); }
+};
+
 }  // namespace
 
 struct plora_batch {
@@ -91,6 +107,11 @@ struct plora_pool {
   std::vector<plora_batch*> batches;               // all batch objects ever made (recycled)
   int open_batches = 0;
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
+  // scratch of the work-list construction (capacity kept from batch to batch)
+  ItemGroups wl[2][2];                             // [op][0 vector-ALU | 1 matrix-core]
+  std::vector<ItemRec> wl_lists[2][3], wl_tg;
+  std::vector<uint32_t> wl_bucket;
+  std::vector<int32_t> wl_touched;
   // tunables
   // A group of n tokens on a rank-r adapter takes matrix-core items when n >= min_tokens or its work
   // reaches min_work (min_tokens 0 = never).  Shrink: work = n * r.  Expand: work = n * r * (r / r
@@ -134,59 +155,72 @@ int poll_ready(plora_pool* p, Adapter& a) {
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// Items of one adapter group that share data (x rows, v rows or a piece of B) and should meet in
-// one XCD's L2.
-struct Group {
-  std::vector<ItemRec> items;
-  double cost = 0.0;
-  bool heavy = false;
-};
+// Appends the records idx[0 .. n) of `src`, longest first: a stable counting sort by rank,
+// descending (equal ranks keep their order, so the token groups of one adapter stay neighbours).
+void append_by_rank(const std::vector<ItemRec>& src, const uint32_t* idx, size_t n, std::vector<ItemRec>& out,
+                    std::vector<uint32_t>& bucket) {
+  bucket.assign(kMaxRank + 2, 0);
+  for (size_t i = 0; i < n; ++i) bucket[kMaxRank - src[idx ? idx[i] : i].rank + 1]++;
+  for (int r = 0; r <= kMaxRank; ++r) bucket[r + 1] += bucket[r];
+  const size_t base = out.size();
+  out.resize(base + n);
+  for (size_t i = 0; i < n; ++i) {
+    const ItemRec& it = src[idx ? idx[i] : i];
+    out[base + bucket[kMaxRank - it.rank]++] = it;
+  }
+}
 
 // Work list of a kernel: blocks of 4 records, one 256-thread workgroup each.  Workgroup i of a launch
-// runs on XCD i % 8.  A matrix-core item fills a
-// block alone (3 padding records); vector-ALU items go four to a block, one per wavefront.
+// runs on XCD i % 8.  A matrix-core item fills a block alone (3 padding records); vector-ALU items go
+// four to a block, one per wavefront: the 4 wavefronts of a block hold their workgroup's resources
+// until the last one ends, so items of similar length (rank) are put together, longest first.
 // Matrix-core blocks first (their dependent chains are the long ones).  With xcd_aware the groups
 // are dealt into 8 queues (longest first, each to the least loaded queue) and the queues are
 // interleaved block by block; queues that run out are padded with empty blocks.
-void arrange_blocks(const std::vector<Group>& heavy, const std::vector<Group>& light, bool xcd_aware,
-                    std::vector<ItemRec>& out, int32_t* n_heavy_records = nullptr) {
+void arrange_blocks(const ItemGroups& heavy, const ItemGroups& light, bool xcd_aware, std::vector<ItemRec>& out,
+                    std::vector<uint32_t>& bucket, int32_t* n_heavy_records = nullptr) {
   out.clear();
   ItemRec pad{};
   pad.kind = -1;
-  const int nq = xcd_aware ? kXcds : 1;
-  std::vector<std::vector<ItemRec>> qh(nq), ql(nq);
-  std::vector<double> load(nq, 0.0);
-  auto deal = [&](const std::vector<Group>& groups, std::vector<std::vector<ItemRec>>& dst) {
-    std::vector<const Group*> order;
-    for (const Group& g : groups) if (!g.items.empty()) order.push_back(&g);
-    if (xcd_aware)
-      std::stable_sort(order.begin(), order.end(), [](const Group* a, const Group* b) { return a->cost > b->cost; });
-    for (const Group* g : order) {
+  if (!xcd_aware) {
+    out.reserve(4 * heavy.items.size() + light.items.size() + 4);
+    for (const ItemRec& it : heavy.items) { out.push_back(it); out.insert(out.end(), 3, pad); }
+    append_by_rank(light.items, nullptr, light.items.size(), out, bucket);
+    while (out.size() % 4) out.push_back(pad);
+    if (n_heavy_records) *n_heavy_records = (int32_t)(4 * heavy.items.size());
+    return;
+  }
+  if (n_heavy_records) *n_heavy_records = 0;
+  constexpr int nq = kXcds;
+  std::vector<uint32_t> qh[nq], ql[nq];  // record indices per queue
+  double load[nq] = {0, 0, 0, 0, 0, 0, 0, 0};
+  std::vector<uint32_t> order;
+  auto deal = [&](const ItemGroups& g, std::vector<uint32_t>* dst) {
+    order.resize(g.groups());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = (uint32_t)i;
+    std::stable_sort(order.begin(), order.end(), [&](uint32_t x, uint32_t y) { return g.cost[x] > g.cost[y]; });
+    for (uint32_t gi : order) {
       int best = 0;
       for (int k = 1; k < nq; ++k) if (load[k] < load[best]) best = k;
-      dst[best].insert(dst[best].end(), g->items.begin(), g->items.end());
-      load[best] += g->cost;
+      for (uint32_t i = g.first[gi]; i < g.first[gi + 1]; ++i) dst[best].push_back(i);
+      load[best] += g.cost[gi];
     }
   };
   deal(heavy, qh);
   deal(light, ql);
-  // The 4 wavefronts of a block hold their workgroup's resources until the last one ends: put items
-  // of similar length together (longest first; equal ranks keep their order, so the token groups of
-  // one adapter stay neighbours).
-  for (int k = 0; k < nq; ++k)
-    std::stable_sort(ql[k].begin(), ql[k].end(), [](const ItemRec& x, const ItemRec& y) { return x.rank > y.rank; });
-  std::vector<std::vector<ItemRec>> blocks(nq);  // per queue, 4 records per block
+  std::vector<ItemRec> blocks[nq];  // per queue, 4 records per block
   size_t longest = 0;
   for (int k = 0; k < nq; ++k) {
-    for (const ItemRec& it : qh[k]) { blocks[k].push_back(it); blocks[k].insert(blocks[k].end(), 3, pad); }
-    blocks[k].insert(blocks[k].end(), ql[k].begin(), ql[k].end());
+    blocks[k].reserve(4 * qh[k].size() + ql[k].size() + 4);
+    for (uint32_t i : qh[k]) { blocks[k].push_back(heavy.items[i]); blocks[k].insert(blocks[k].end(), 3, pad); }
+    append_by_rank(light.items, ql[k].data(), ql[k].size(), blocks[k], bucket);
     while (blocks[k].size() % 4) blocks[k].push_back(pad);
     longest = std::max(longest, blocks[k].size() / 4);
   }
+  out.reserve(longest * 4 * nq);
   for (size_t i = 0; i < longest; ++i)
     for (int k = 0; k < nq; ++k)
       for (int w = 0; w < 4; ++w) out.push_back(4 * i + w < blocks[k].size() ? blocks[k][4 * i + w] : pad);
-  if (n_heavy_records) *n_heavy_records = nq == 1 ? (int32_t)(4 * qh[0].size()) : 0;
 }
 
 }  // namespace
@@ -511,8 +545,21 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
 
   // work items, grouped per adapter (tokens without adapter form one rank-0 group: shrink clears their v rows)
   const bool mfma_ok = p->dtype != PLORA_F32;  // matrix-core items exist for the 16-bit element types
-  std::vector<Group> grp[2][2];  // [op][kind]
-  std::vector<ItemRec> coop[2];  // [op]
+  ItemGroups(&wl)[2][2] = p->wl;               // [op][0 vector-ALU | 1 matrix-core]
+  for (int op = 0; op < 2; ++op)
+    for (int k = 0; k < 2; ++k) wl[op][k].clear();
+  std::vector<ItemRec>& tg = p->wl_tg;  // one vector-ALU record per token group of the current adapter
+  // the vector-ALU records of one adapter group: token groups of kValuTok tokens
+  auto token_groups = [&](int16_t rank, float scale, int32_t pt_off, int32_t start, int32_t n) {
+    tg.clear();
+    for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
+      const int16_t nt = (int16_t)std::min(kValuTok, n - t0);
+      // one token group: nobody else reads the group's weights
+      ItemRec it{(int16_t)(n <= kValuTok ? kItemOnce : 0), nt, rank, 0, scale, pt_off, {0, 0, 0, 0}};
+      for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
+      tg.push_back(it);
+    }
+  };
   size_t n_pt_total = 0;
   for (int32_t u = 0; u < n_seg; ++u) {
     const Adapter& a = p->ad[touched[u]];
@@ -534,87 +581,91 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     for (int32_t b0 = 0; b0 < n && (mf_s || mf_e); b0 += kTokBlock) {
       const int32_t b1 = std::min(n, b0 + kTokBlock);
       if (mf_s) {
-        Group gs;
-        gs.heavy = true;
+        double cost = 0.0;
+        // the rows of A are read by one item only when the group is a single token tile
+        const int16_t kind = (int16_t)(n <= kMfmaTokS ? 1 | kItemOnce : 1);
         for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
           for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokS) {
             const int16_t nt = (int16_t)std::min(kMfmaTokS, b1 - t0);
-            // the rows of A are read by one item only when the group is a single token tile
-            const int16_t kind = (int16_t)(n <= kMfmaTokS ? 1 | kItemOnce : 1);
-            gs.items.push_back(ItemRec{kind, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
-            gs.cost += std::min(kMfmaRows, a.rank - j0) + nt;
+            wl[0][1].items.push_back(ItemRec{kind, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+            cost += std::min(kMfmaRows, a.rank - j0) + nt;
           }
-        grp[0][1].push_back(std::move(gs));
+        wl[0][1].close_group(cost);
       }
       if (mf_e) {
-        Group ge;
-        ge.heavy = true;
+        double cost = 0.0;
+        const int16_t kind = (int16_t)(n <= kMfmaTokCols ? 1 | kItemOnce : 1);
         // a remainder of at most kMfmaColsMaxGroup tokens goes as column-split items of one token tile
         for (int32_t t0 = b0; t0 < b1;) {
           const int32_t left = b1 - t0;
           const int16_t nt = (int16_t)std::min(left <= kMfmaColsMaxGroup ? kMfmaTokCols : kMfmaTokE, left);
-          const int16_t kind = (int16_t)(n <= kMfmaTokCols ? 1 | kItemOnce : 1);
-          ge.items.push_back(ItemRec{kind, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
-          ge.cost += a.rank + 2 * nt;
+          wl[1][1].items.push_back(ItemRec{kind, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
+          cost += a.rank + 2 * nt;
           t0 += nt;
         }
-        grp[1][1].push_back(std::move(ge));
+        wl[1][1].close_group(cost);
       }
     }
-    // Vector-ALU items (every group has them in the cooperative lists).
-    {
-      Group gs, ge;
-      std::vector<ItemRec> tg;  // one record per token group
-      for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
-        const int16_t nt = (int16_t)std::min(kValuTok, n - t0);
-        // one token group: nobody else reads the group's weights
-        ItemRec it{(int16_t)(n <= kValuTok ? kItemOnce : 0), nt, rank, 0, a.scale, pt_off, {0, 0, 0, 0}};
-        for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
-        tg.push_back(it);
-        coop[1].push_back(it);
-        if (!mf_e) {
-          ge.items.push_back(it);
-          ge.cost += a.rank + 2 * nt;
-        }
+    // Vector-ALU items.
+    if (!mf_s || !mf_e) {
+      token_groups(rank, a.scale, pt_off, start, n);
+      if (!mf_e) {
+        double cost = 0.0;
+        for (const ItemRec& it : tg) { wl[1][0].items.push_back(it); cost += a.rank + 2 * it.ntok; }
+        wl[1][0].close_group(cost);
       }
-      for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
-        for (ItemRec it : tg) {
-          it.j0 = (int16_t)j0;
-          coop[0].push_back(it);
-        }
       // shrink: token groups innermost, so that the re-read of a row block by the next token
       // group follows closely and finds the rows in L2
-      if (!mf_s)
+      if (!mf_s) {
+        double cost = 0.0;
         for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
           for (ItemRec it : tg) {
             it.j0 = (int16_t)j0;
-            gs.items.push_back(it);
-            gs.cost += std::min(kShrinkRows, a.rank - j0) + it.ntok;
+            wl[0][0].items.push_back(it);
+            cost += std::min(kShrinkRows, a.rank - j0) + it.ntok;
           }
-      if (!gs.items.empty()) grp[0][0].push_back(std::move(gs));
-      if (!ge.items.empty()) grp[1][0].push_back(std::move(ge));
+        wl[0][0].close_group(cost);
+      }
     }
   }
-  if (n_none > 0) {
-    Group gs;
+  // tokens without adapter: one rank-0 group of shrink items
+  auto none_groups = [&](std::vector<ItemRec>& dst) {
     for (int32_t t0 = 0; t0 < n_none; t0 += kValuTok) {
       const int16_t nt = (int16_t)std::min(kValuTok, n_none - t0);
       ItemRec it{0, nt, 0, 0, 0.f, 0, {0, 0, 0, 0}};
       for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[n_perm + t0 + std::min<int>(i, nt - 1)];
-      gs.items.push_back(it);
-      coop[0].push_back(it);
-      gs.cost += 0.1;
+      dst.push_back(it);
     }
-    grp[0][0].push_back(std::move(gs));
+  };
+  if (n_none > 0) {
+    none_groups(wl[0][0].items);
+    wl[0][0].close_group(0.1 * ((n_none + kValuTok - 1) / kValuTok));
   }
-  std::vector<ItemRec> lists[2][3];  // [op][layout]
+  std::vector<ItemRec>(&lists)[2][3] = p->wl_lists;  // [op][layout]
   for (int op = 0; op < 2; ++op) {
-    for (int lay = 0; lay < 2; ++lay)
-      arrange_blocks(grp[op][1], grp[op][0], lay != 0, lists[op][lay], lay == 0 ? &b->n_heavy[op] : nullptr);
-    // longest chains first
-    std::stable_sort(coop[op].begin(), coop[op].end(), [](const ItemRec& x, const ItemRec& y) { return x.rank > y.rank; });
-    // (not needed when even one slot's ordinary launch is past the limit of the cooperative form)
-    if ((int64_t)(lists[op][0].size() / 4) <= p->coop_max_workgroups[op]) lists[op][2] = std::move(coop[op]);
+    arrange_blocks(wl[op][1], wl[op][0], false, lists[op][0], p->wl_bucket, &b->n_heavy[op]);
+    // the XCD-dealt form only if launches may ask for it
+    if (p->xcd_remap[op]) arrange_blocks(wl[op][1], wl[op][0], true, lists[op][1], p->wl_bucket);
+    else lists[op][1].clear();
+    // Cooperative form (calls too small to fill the machine): every group as vector-ALU records, one per
+    // workgroup, longest chains first.  Not needed when even one slot's ordinary launch is past its limit.
+    lists[op][2].clear();
+    if (p->coop_max_workgroups[op] > 0 && (int64_t)(lists[op][0].size() / 4) <= p->coop_max_workgroups[op]) {
+      std::vector<ItemRec>& all = wl[op][1].items;  // reused as scratch: the matrix-core records are arranged already
+      all.clear();
+      size_t pt_run = 0;
+      for (int32_t u = 0; u < n_seg; ++u) {
+        const Adapter& a = p->ad[touched[u]];
+        token_groups((int16_t)a.rank, a.scale, (int32_t)pt_run, b->seg_start[u], p->count[touched[u]]);
+        pt_run += a.pt.size();
+        if (op == 1) all.insert(all.end(), tg.begin(), tg.end());
+        else
+          for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
+            for (ItemRec it : tg) { it.j0 = (int16_t)j0; all.push_back(it); }
+      }
+      if (op == 0 && n_none > 0) none_groups(all);
+      append_by_rank(all, nullptr, all.size(), lists[op][2], p->wl_bucket);
+    }
   }
   for (int32_t i : touched) p->count[i] = 0;
 
@@ -746,7 +797,7 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     // slots fastest when that keeps every slot on one XCD and all XCDs equally loaded; else the
     // items are the fastest dimension and (optionally) come dealt into XCD queues
     a.slot_fastest = p->slot_major[op] == 2 ? 2 : (p->slot_major[op] == 1 || (p->slot_major[op] < 0 && nq % kXcds == 0)) ? 1 : 0;
-    int layout = (a.slot_fastest != 1 && p->xcd_remap[op]) ? 1 : 0;
+    int layout = (a.slot_fastest != 1 && p->xcd_remap[op] && b->n_items[op][1] > 0) ? 1 : 0;
     // a call that cannot fill the machine is bound by its longest dependent chain: cooperative kernels
     const bool coop = p->coop_max_workgroups[op] > 0 && b->n_items[op][2] > 0 &&
                       (int64_t)nq * (b->n_items[op][layout] / 4) * chunks <= p->coop_max_workgroups[op];
