@@ -89,7 +89,7 @@ class Case:
         y0 = [np.zeros((T, lay.d_out[s]), RAW_DTYPE[lay.dtype]) if y0_zero else make_act(rng, T, lay.d_out[s], lay.dtype)
               for s in slots]
         # GPU side: once with the ordinary kernels, once with the cooperative kernels of small calls
-        for coop in getattr(self, "coop_modes", (0, 1 << 30)):
+        for coop in getattr(self, "coop_modes", (1 << 30, 0)):  # the ordinary kernels last: their outputs are returned
             self.gpool.set_option("coop_max_workgroups_shrink", coop)
             self.gpool.set_option("coop_max_workgroups_expand", coop)
             out = self._run_gpu(t2a, slots, xs, y0, check)

@@ -171,3 +171,20 @@ def test_slots_of_two_widths_in_one_call(oracle_mod):
         case.run(t2a, seed=3)
         case.run(t2a, slots=range(2, 14), seed=4)
     case.close()
+
+
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F32])
+def test_maximum_rank(oracle_mod, dtype):
+    """Ranks up to the library's limit of 512 (the expand stages one page pair per row of B), with
+    groups small and large enough for every kind of item."""
+    lay = Layout((136, 64), (72, 520), dtype)
+    ranks = [512, 300, 509, 8]
+    case = Case(oracle_mod, lay, ranks, [16.0 / r for r in ranks], 8192, 1024, seed=61, max_rank=512)
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in zip(range(4), (70, 3, 18, 1))])
+    np.random.default_rng(2).shuffle(t2a)
+    for mfma in (0, 2):
+        case.set_mfma(mfma)
+        out = case.run(t2a, seed=7)
+        print("max rank dtype", dtype, "mfma", mfma, "err_v", ["%.2g" % o["err_v"] for o in out],
+              "err_y", ["%.2g" % o["err_y"] for o in out], flush=True)
+    case.close()
