@@ -386,7 +386,7 @@ def main():
     ap.add_argument("--xcd-remap", type=int, default=-1)
     ap.add_argument("--coop-max-workgroups", type=int, default=-1,
                     help="calls of at most this many workgroups use the cooperative kernels (library defaults 192 for "
-                         "shrink, 1024 for expand; 0 = never)")
+                         "shrink, 400 for expand; 0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--same-batch", action="store_true", help="reuse one token->adapter draw for every step")

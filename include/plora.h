@@ -168,7 +168,7 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * workgroup, instead of one mixed launch; defaults 0 / 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
  * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound
  * by its longest chain of dependent loads; it runs the cooperative kernels instead, in which the four
- * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 1024, 0 = never; take effect for
+ * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 400, 0 = never; take effect for
  * batches begun afterwards).  INVAL for an unknown key or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
