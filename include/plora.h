@@ -169,7 +169,11 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound
  * by its longest chain of dependent loads; it runs the cooperative kernels instead, in which the four
  * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 400, 0 = never; take effect for
- * batches begun afterwards).  INVAL for an unknown key or a value out of range. */
+ * batches begun afterwards).  "batches_per_marker" (1..64, default 4: plora_batch_end puts one completion
+ * event on the stream per this many batches instead of one per batch; the library records a pending
+ * one itself whenever an eviction, a load or the reuse of a batch object has to order against it, so
+ * the value changes only how long pages and batch objects may stay held, never results).
+ * INVAL for an unknown key or a value out of range. */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand attach a

@@ -27,8 +27,14 @@ static thread_local int g_last_hip = 0;
 
 namespace {
 
-struct Event {  // shared completion marker of a batch
+// Completion marker of one or more batches that ended on the same stream.  It is recorded lazily:
+// an event recorded later on the stream still implies that the batches' kernels have finished, and
+// one record per few batches keeps the extra packet out of most steps' queues.
+struct Event {
   hipEvent_t ev = nullptr;
+  hipStream_t stream = nullptr;
+  bool recorded = false;
+  int users = 0;  // batches that ended under this marker so far
   ~Event() { if (ev) (void)hipEventDestroy(ev); }
 };
 
@@ -104,6 +110,8 @@ struct plora_pool {
   uint32_t hint_word = 0;  // no free bit below this word
   std::vector<Adapter> ad;
   std::vector<std::shared_ptr<Event>> reuse_wait;  // batches that last read pages since freed
+  std::shared_ptr<Event> cur_done;                 // marker of the batches ended since the last record
+  int batches_per_marker = 4;                      // record the marker once this many batches share it
   std::vector<plora_batch*> batches;               // all batch objects ever made (recycled)
   int open_batches = 0;
   std::vector<int32_t> count, cursor;              // per-adapter scratch of the counting sort
@@ -154,6 +162,27 @@ int poll_ready(plora_pool* p, Adapter& a) {
 }
 
 size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// Records the marker on its stream if that has not happened yet.
+int record_now(Event& e) {
+  if (e.recorded) return PLORA_OK;
+  if (!e.ev) HIP_TRY(hipEventCreateWithFlags(&e.ev, hipEventDisableTiming));
+  HIP_TRY(hipEventRecord(e.ev, e.stream));
+  e.recorded = true;
+  return PLORA_OK;
+}
+
+// 1 = the marker has passed, 0 = not yet (it is recorded first if need be), < 0 = error.
+int marker_passed(Event& e) {
+  const int rc = record_now(e);
+  if (rc != PLORA_OK) return rc;
+  const hipError_t q = hipEventQuery(e.ev);
+  if (q == hipSuccess) return 1;
+  (void)hipGetLastError();
+  if (q == hipErrorNotReady) return 0;
+  g_last_hip = (int)q;
+  return PLORA_ERR_HIP;
+}
 
 // Appends the records idx[0 .. n) of `src`, longest first: a stable counting sort by rank,
 // descending (equal ranks keep their order, so the token groups of one adapter stay neighbours).
@@ -339,7 +368,11 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
       HIP_TRY(hipEventCreate(&a.ev_ready));
     }
     // copies into reused pages must not overtake kernels of batches that read them
-    for (auto& w : p->reuse_wait) HIP_TRY(hipStreamWaitEvent(st, w->ev, 0));
+    for (auto& w : p->reuse_wait) {
+      const int rc = record_now(*w);
+      if (rc != PLORA_OK) return rc;
+      HIP_TRY(hipStreamWaitEvent(st, w->ev, 0));
+    }
     p->reuse_wait.clear();
   }
   // first fit: the m lowest-numbered free pages, ascending
@@ -417,12 +450,10 @@ int plora_evict(plora_pool* p, int32_t id) {
     if (rdy < 0) return rdy;
     if (rdy == 0) return PLORA_ERR_BUSY;
     if (a.last_use) {
-      hipError_t e = hipEventQuery(a.last_use->ev);
-      if (e == hipErrorNotReady) {
-        (void)hipGetLastError();
-        if (std::find(p->reuse_wait.begin(), p->reuse_wait.end(), a.last_use) == p->reuse_wait.end())
-          p->reuse_wait.push_back(a.last_use);
-      } else if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return PLORA_ERR_HIP; }
+      const int passed = marker_passed(*a.last_use);
+      if (passed < 0) return passed;
+      if (passed == 0 && std::find(p->reuse_wait.begin(), p->reuse_wait.end(), a.last_use) == p->reuse_wait.end())
+        p->reuse_wait.push_back(a.last_use);
     }
   }
   for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
@@ -458,6 +489,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
   if (k == "mfma_min_work" || k == "mfma_min_work_expand") {
     if (value < 1 || value > (1 << 30)) return PLORA_ERR_INVAL;
     (k == "mfma_min_work" ? p->mfma_min_work : p->mfma_min_work_expand) = value;
+    return PLORA_OK;
+  }
+  if (k == "batches_per_marker") {
+    if (value < 1 || value > 64) return PLORA_ERR_INVAL;
+    p->batches_per_marker = (int)value;
     return PLORA_OK;
   }
   if (k == "coop_max_workgroups_shrink" || k == "coop_max_workgroups_expand") {
@@ -510,17 +546,20 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   const int32_t n_perm = T - n_none;
 
   plora_batch* b = nullptr;
+  bool unrecorded = false;
   for (plora_batch* c : p->batches) {
     if (c->open) continue;
     if (c->done) {  // its last copy and kernels may still be in flight
-      const hipError_t e = hipEventQuery(c->done->ev);
-      if (e != hipSuccess) { (void)hipGetLastError(); continue; }
+      if (!c->done->recorded) { unrecorded = true; continue; }
+      if (marker_passed(*c->done) != 1) continue;
       c->done.reset();
     }
     b = c;
     break;
   }
   if (!b) {
+    // nothing to recycle: make sure the closed batches' marker is on its way, and take a new object
+    if (unrecorded && p->cur_done) (void)record_now(*p->cur_done);
     b = new (std::nothrow) plora_batch;
     if (!b) { for (int32_t i : touched) p->count[i] = 0; return PLORA_ERR_NOMEM; }
     b->pool = p;
@@ -873,9 +912,19 @@ int plora_batch_end(plora_pool* p, plora_batch* b) {
   if (!p || !b || !b->open || b->pool != p) return PLORA_ERR_INVAL;
   std::shared_ptr<Event> done;
   if (!p->placement_only) {
-    done = std::make_shared<Event>();
-    HIP_TRY(hipEventCreateWithFlags(&done->ev, hipEventDisableTiming));
-    HIP_TRY(hipEventRecord(done->ev, b->stream));
+    if (!p->cur_done || p->cur_done->recorded || p->cur_done->stream != b->stream) {
+      if (p->cur_done && !p->cur_done->recorded) {  // another stream takes over: close the old marker
+        const int rc = record_now(*p->cur_done);
+        if (rc != PLORA_OK) return rc;
+      }
+      p->cur_done = std::make_shared<Event>();
+      p->cur_done->stream = b->stream;
+    }
+    done = p->cur_done;
+    if (++done->users >= p->batches_per_marker) {
+      const int rc = record_now(*done);
+      if (rc != PLORA_OK) return rc;
+    }
   }
   for (int32_t i : b->adapters) {
     Adapter& a = p->ad[i];
