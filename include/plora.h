@@ -91,8 +91,9 @@ uint64_t plora_adapter_bytes(const plora_pool* pool, int32_t rank);
 /* Place adapter `id` and start filling its pages (Sec. III-B: load from host memory to GPU;
  * Sec. III-C: ceil(S/P) pages).  pinned_host_ptr: host, page-locked, S bytes, must stay valid and
  * unchanged until the adapter is ready.  The copies are issued on copy_stream, one per run of
- * physically consecutive pages, after that stream has been made to wait for every batch that last
- * read the pages being reused.  page_table_out / n_pages_out (either may be NULL): the adapter's
+ * physically consecutive pages, after that stream has been made to wait for every batch, on whatever
+ * stream it ran, that read since-freed pages and has not finished (copy streams may differ from
+ * load to load).  page_table_out / n_pages_out (either may be NULL): the adapter's
  * page table, a host pointer into pool-owned memory that stays valid until plora_evict(id).
  * Returns at once; the adapter becomes usable by batches immediately (they wait on its ready event).
  * INVAL (bad id / rank / pointer not page-locked), EXISTS, NOMEM (nothing allocated). */

@@ -47,7 +47,7 @@ struct Adapter {
   hipEvent_t ev_start = nullptr, ev_ready = nullptr;  // created on first use, reused
   bool copy_pending = false;                          // ready event not yet observed complete
   int pins = 0;
-  std::shared_ptr<Event> last_use;
+  std::vector<std::shared_ptr<Event>> last_use;  // completion markers of the last batches that read it: one per stream
 };
 
 // Work items of one operation in flat storage: the records of group g (one adapter's items that
@@ -109,7 +109,10 @@ struct plora_pool {
   uint32_t n_free = 0;
   uint32_t hint_word = 0;  // no free bit below this word
   std::vector<Adapter> ad;
-  std::vector<std::shared_ptr<Event>> reuse_wait;  // batches that last read pages since freed
+  // Markers of batches that last read pages since freed, each with the copy streams that already wait
+  // for it: any stream that copies into free pages has to be ordered after them, until they have passed.
+  struct ReuseWait { std::shared_ptr<Event> m; std::vector<hipStream_t> waited; };
+  std::vector<ReuseWait> reuse_wait;
   std::shared_ptr<Event> cur_done;                 // marker of the batches ended since the last record
   int batches_per_marker = 4;                      // record the marker once this many batches share it
   std::vector<plora_batch*> batches;               // all batch objects ever made (recycled)
@@ -368,12 +371,17 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
       HIP_TRY(hipEventCreate(&a.ev_ready));
     }
     // copies into reused pages must not overtake kernels of batches that read them
-    for (auto& w : p->reuse_wait) {
-      const int rc = record_now(*w);
-      if (rc != PLORA_OK) return rc;
-      HIP_TRY(hipStreamWaitEvent(st, w->ev, 0));
+    for (size_t k = 0; k < p->reuse_wait.size();) {
+      auto& w = p->reuse_wait[k];
+      const int passed = marker_passed(*w.m);
+      if (passed < 0) return passed;
+      if (passed) { p->reuse_wait.erase(p->reuse_wait.begin() + k); continue; }
+      if (std::find(w.waited.begin(), w.waited.end(), st) == w.waited.end()) {
+        HIP_TRY(hipStreamWaitEvent(st, w.m->ev, 0));
+        w.waited.push_back(st);
+      }
+      ++k;
     }
-    p->reuse_wait.clear();
   }
   // first fit: the m lowest-numbered free pages, ascending
   a.pt.clear();
@@ -416,7 +424,7 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
     a.copy_pending = true;
     p->h2d_bytes += S;
   }
-  a.present = true; a.rank = rank; a.scale = scale; a.bytes = S; a.pins = 0; a.last_use.reset();
+  a.present = true; a.rank = rank; a.scale = scale; a.bytes = S; a.pins = 0; a.last_use.clear();
   p->loads++; p->resident_adapters++; p->resident_bytes += S;
   if (pt_out) *pt_out = a.pt.data();
   if (n_out) *n_out = (uint32_t)m;
@@ -449,11 +457,12 @@ int plora_evict(plora_pool* p, int32_t id) {
     const int rdy = poll_ready(p, a);
     if (rdy < 0) return rdy;
     if (rdy == 0) return PLORA_ERR_BUSY;
-    if (a.last_use) {
-      const int passed = marker_passed(*a.last_use);
+    for (auto& m : a.last_use) {
+      const int passed = marker_passed(*m);
       if (passed < 0) return passed;
-      if (passed == 0 && std::find(p->reuse_wait.begin(), p->reuse_wait.end(), a.last_use) == p->reuse_wait.end())
-        p->reuse_wait.push_back(a.last_use);
+      if (passed == 0 && std::none_of(p->reuse_wait.begin(), p->reuse_wait.end(),
+                                      [&](const plora_pool::ReuseWait& w) { return w.m == m; }))
+        p->reuse_wait.push_back({m, {}});
     }
   }
   for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
@@ -461,7 +470,7 @@ int plora_evict(plora_pool* p, int32_t id) {
   if (!a.pt.empty()) p->hint_word = std::min<uint32_t>(p->hint_word, (uint32_t)a.pt[0] >> 6);
   p->resident_adapters--; p->resident_bytes -= a.bytes; p->evictions++;
   a.pt.clear(); a.pt.shrink_to_fit();
-  a.present = false; a.rank = 0; a.scale = 0.f; a.bytes = 0; a.last_use.reset();
+  a.present = false; a.rank = 0; a.scale = 0.f; a.bytes = 0; a.last_use.clear();
   return PLORA_OK;
 }
 
@@ -929,7 +938,13 @@ int plora_batch_end(plora_pool* p, plora_batch* b) {
   for (int32_t i : b->adapters) {
     Adapter& a = p->ad[i];
     a.pins--;
-    if (done) a.last_use = done;
+    if (done && (a.last_use.empty() || a.last_use.back() != done)) {
+      // a later marker of the same stream covers the earlier one; readers on other streams stay listed
+      auto& lu = a.last_use;
+      lu.erase(std::remove_if(lu.begin(), lu.end(), [&](const std::shared_ptr<Event>& m) { return m->stream == done->stream; }),
+               lu.end());
+      lu.push_back(done);
+    }
   }
   b->adapters.clear();
   b->done = done;

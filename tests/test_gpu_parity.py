@@ -188,3 +188,61 @@ def test_maximum_rank(oracle_mod, dtype):
         print("max rank dtype", dtype, "mfma", mfma, "err_v", ["%.2g" % o["err_v"] for o in out],
               "err_y", ["%.2g" % o["err_y"] for o in out], flush=True)
     case.close()
+
+
+@pytest.mark.parametrize("per_marker", [1, 4, 64])
+def test_pages_freed_behind_queued_batches_are_rewritten_only_after_their_kernels(oracle_mod, per_marker):
+    """Three batches that read adapter 0 are queued, the adapter is evicted and another one is loaded
+    onto the same pages without any synchronisation in between: the copy has to wait for the batches'
+    kernels whether or not their completion event had been put on the stream yet."""
+    import torch
+    from workload import from_elt, make_act
+    from helpers import TOL_Y, raw_to_torch, rel_err, torch_to_raw
+    lay = Layout((4096,) * 8, (4096,) * 8, DT_BF16)
+    ranks = [64, 64]
+    case = Case(oracle_mod, lay, ranks, [0.5, 2.0], 65536, 2 * 128 + 8, seed=21, load_order=[0])
+    g, o = case.gpool, case.opool
+    g.set_option("batches_per_marker", per_marker)
+    T, rng = 512, np.random.default_rng(8)
+    slots = list(range(lay.n_slots))
+    runs = []
+    for k in range(4):  # three batches over adapter 0, then one over adapter 1
+        xs = [make_act(rng, T, lay.d_in[s], lay.dtype) for s in slots]
+        y0 = [make_act(rng, T, lay.d_out[s], lay.dtype) for s in slots]
+        runs.append(dict(xs=xs, y0=y0, xd=[raw_to_torch(a, "cuda") for a in xs], yd=[raw_to_torch(a, "cuda") for a in y0],
+                         vd=[torch.empty((T, 64), device="cuda") for _ in slots]))
+    torch.cuda.synchronize()
+    t2a0, t2a1 = np.zeros(T, np.int32), np.ones(T, np.int32)
+    sel = np.arange(0, T, 37, dtype=np.int32)
+
+    def reference(r, t2a):
+        r["ref"] = []
+        for s in slots:
+            v_ref = o.shrink(s, r["xs"][s], t2a, acc64=True, tok_sel=sel)
+            r["ref"].append(o.expand(s, v_ref, t2a, r["y0"][s].copy(), acc64=True, tok_sel=sel))
+
+    def gpu(r, t2a):
+        b = g.batch_begin(t2a, case.stream)
+        g.shrink(b, 0, r["xd"], r["vd"], case.stream)
+        g.expand(b, 0, r["vd"], r["yd"], case.stream)
+        g.batch_end(b)
+
+    for r in runs[:3]:
+        reference(r, t2a0)
+    print("per_marker", per_marker, "queueing three batches, evict, load, one batch", flush=True)
+    for r in runs[:3]:
+        gpu(r, t2a0)
+    pt0 = o.page_table(0).tolist()
+    case.evict(0)
+    pt1 = case.load(1)
+    assert pt1.tolist() == pt0, "the new adapter did not land on the freed pages"
+    gpu(runs[3], t2a1)
+    torch.cuda.synchronize()
+    reference(runs[3], t2a1)
+    for k, r in enumerate(runs):
+        for s in slots:
+            got = torch_to_raw(r["yd"][s], lay.dtype)
+            err = rel_err(from_elt(got[sel], lay.dtype), from_elt(r["ref"][s][sel], lay.dtype))
+            assert err <= TOL_Y[lay.dtype], "batch %d slot %d: y error %.3g" % (k, s, err)
+    assert g.stats()["used_pages"] == 128
+    case.close()
