@@ -361,15 +361,75 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
     return out
 
 
+def run_load_study(args):
+    """H2D rate of plora_load_adapter into fragmented pools, direct (one copy per run of consecutive
+    pages) against staged (one copy + scatter kernel): cfg3's one-layer slots and 64 KiB pages, free
+    space made of holes of h pages, 32 rank-64 adapters (4 MiB = 64 pages each) loaded back to back."""
+    import torch
+    import paper_2512_20210_amd as P
+    from workload import make_adapter
+    cfg, lay, _, _, page_bytes, _ = workload_params("cfg3")
+    rng = np.random.default_rng(cfg["seed"] + 2000)
+    big_rank, n_big = 64, 32
+    big_pages = lay.adapter_elems(big_rank) * 2 // page_bytes
+    unit_rank = page_bytes // (lay.adapter_elems(1) * 2)          # rank whose blob is exactly one page
+    assert unit_rank * lay.adapter_elems(1) * 2 == page_bytes
+
+    def pinned_blob(r):
+        t = torch.empty(lay.adapter_elems(r), dtype=torch.int16, pin_memory=True)
+        make_adapter(rng, lay, r, out=t.numpy().view(np.uint16))
+        return t
+    big = [pinned_blob(big_rank) for _ in range(4)]
+    copy_stream = torch.cuda.Stream()
+    rows = []
+    for hole in (1, 2, 4, 16, 32, 0):   # 0: an empty pool, every adapter lands on consecutive pages
+        n_fill = 0 if hole == 0 else 2 * (n_big * big_pages // hole)
+        n_pages = n_fill * max(hole, 1) + n_big * big_pages
+        pool = P.PagedLoraPool(page_bytes, n_pages, lay.d_in, lay.d_out, lay.dtype, n_fill + n_big, 128)
+        if hole:
+            filler = pinned_blob(hole * unit_rank)
+            for i in range(n_fill):
+                pool.load(i, hole * unit_rank, 1.0, filler, copy_stream.cuda_stream)
+            torch.cuda.synchronize()
+            for i in range(0, n_fill, 2):
+                pool.evict(i)
+        row = {"hole_pages": hole or None, "runs_per_adapter": None}
+        for mode in ("direct", "staged", "direct", "staged"):   # the second round is the one reported
+            pool.set_option("staging_bytes", lay.adapter_elems(big_rank) * 2 if mode == "staged" else 0)
+            c0 = pool.stats()["h2d_copies"]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for k in range(n_big):
+                pool.load(n_fill + k, big_rank, 0.25, big[k % len(big)], copy_stream.cuda_stream)
+            t_issue = time.perf_counter() - t0
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            st = pool.stats()
+            row["runs_per_adapter"] = (st["h2d_copies"] - c0) / n_big if mode == "direct" else row["runs_per_adapter"]
+            row[mode + "_gbs"] = round(n_big * lay.adapter_elems(big_rank) * 2 / dt / 1e9, 2)
+            row[mode + "_host_issue_ms"] = round(t_issue * 1e3, 2)
+            for k in range(n_big):
+                pool.evict(n_fill + k)
+        row["staged_loads"] = pool.stats()["staged_loads"]
+        rows.append(row)
+        pool.close()
+    print(json.dumps({"metric": "H2D GB/s of adapter loads into fragmented pools, direct vs staged", "workload": "load_study",
+                      "adapter_bytes": lay.adapter_elems(big_rank) * 2, "adapters": n_big, "page_bytes": page_bytes, "rows": rows}))
+
+
 def run_churn(args):
     """cfg3: load/evict churn interleaved with decode batches; utilisation, H2D and kernel rates, once
     with loads on demand only and once with threshold prefetching on a synthetic prediction."""
     out = {"metric": "pool utilisation under churn + H2D prefetch GB/s + decode kernel GB/s + cold starts",
            "workload": "cfg3", "passes": []}
     pinned = None
-    for quality in (None, 0.86):
+    for quality, staged in ((None, False), (0.86, False), (0.86, True)):
         cfg, lay, ranks, scales, pool, pinned, trace = churn_setup("cfg3", pinned=pinned)
-        out["passes"].append(_churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality))
+        if staged:  # every blob of two or more runs of pages goes through a staging buffer
+            pool.set_option("staging_bytes", lay.adapter_elems(cfg["max_rank"]) * 2)
+        res = _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality)
+        res["staged_loads"] = pool.stats()["staged_loads"]
+        out["passes"].append(res)
         pool.close()
     print(json.dumps(out))
 
@@ -379,7 +439,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "load_study"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
     ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="plain token threshold of the matrix-core items in shrink (default: the library's work-based rule)")
     ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand")
@@ -403,6 +463,9 @@ def main():
     torch.cuda.set_device(0)
     if args.workload == "cfg3":
         run_churn(args)
+        return
+    if args.workload == "load_study":
+        run_load_study(args)
         return
 
     w = GpuWorkload(args.workload, verbose=args.verbose, scatter=args.scatter)

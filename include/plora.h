@@ -71,6 +71,7 @@ typedef struct {
   uint64_t h2d_bytes;  /* bytes handed to the copy engine by plora_load_adapter */
   uint64_t h2d_copies; /* number of copy calls (one per run of physically consecutive pages) */
   double h2d_ms;       /* summed first-copy-start -> last-copy-end time of completed loads */
+  uint64_t staged_loads; /* loads that went through a staging buffer and the scatter kernel */
 } plora_stats;
 
 /* Pool of n_pages pages of page_bytes each (Sec. III-C "Page Structure"; the paper's default page is
@@ -91,7 +92,8 @@ uint64_t plora_adapter_bytes(const plora_pool* pool, int32_t rank);
 /* Place adapter `id` and start filling its pages (Sec. III-B: load from host memory to GPU;
  * Sec. III-C: ceil(S/P) pages).  pinned_host_ptr: host, page-locked, S bytes, must stay valid and
  * unchanged until the adapter is ready.  The copies are issued on copy_stream, one per run of
- * physically consecutive pages, after that stream has been made to wait for every batch, on whatever
+ * physically consecutive pages (or, with the option "staging_bytes", one copy into a staging buffer
+ * and a kernel that moves the pages into place), after that stream has been made to wait for every batch, on whatever
  * stream it ran, that read since-freed pages and has not finished (copy streams may differ from
  * load to load).  page_table_out / n_pages_out (either may be NULL): the adapter's
  * page table, a host pointer into pool-owned memory that stays valid until plora_evict(id).
@@ -174,7 +176,14 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * event on the stream per this many batches instead of one per batch; the library records a pending
  * one itself whenever an eviction, a load or the reuse of a batch object has to order against it, so
  * the value changes only how long pages and batch objects may stay held, never results).
- * INVAL for an unknown key or a value out of range. */
+ * "staging_bytes" (0 .. 2^36, default 0 = off) and "staging_min_runs" (>= 1, default 3: with two runs the direct copies are as fast): staged loads
+ * (Sec. III-B: loaded adapters arrive in a staging area before they are moved into place).  With
+ * staging on, plora_load_adapter sends a blob of at most staging_bytes whose pages form at least
+ * staging_min_runs runs of consecutive pages in ONE copy into one of two device staging buffers of
+ * staging_bytes each (allocated by this call, which synchronises the device when it has to grow
+ * them) and lets a kernel on copy_stream move the pages into place; that copy does not have to wait
+ * for earlier readers of the freed pages, only the kernel does.  Other blobs keep the direct path.
+ * INVAL for an unknown key or a value out of range (staging_bytes: also for a placement-only pool). */
 int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand attach a

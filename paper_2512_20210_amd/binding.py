@@ -38,7 +38,7 @@ class _Layout(C.Structure):
 class _Stats(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("page_bytes", "n_pages", "used_pages", "free_pages", "resident_adapters",
                                           "resident_bytes", "internal_frag_bytes", "loads", "evictions",
-                                          "nomem_failures", "h2d_bytes", "h2d_copies")] + [("h2d_ms", C.c_double)]
+                                          "nomem_failures", "h2d_bytes", "h2d_copies")] + [("h2d_ms", C.c_double), ("staged_loads", C.c_uint64)]
 
 
 _vp, _i32, _u32, _u64, _f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_float

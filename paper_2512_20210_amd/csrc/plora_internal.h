@@ -81,6 +81,17 @@ struct LaunchArgs {
   int32_t pad;
 };
 
+// Runs of physically consecutive pages of one adapter, for the staged load's scatter kernel: run k
+// covers the virtual pages first_vpage[k] .. (first_vpage[k+1] or the launch's end) and starts at
+// physical page phys_page[k].
+constexpr int kScatterRuns = 240;
+constexpr int kScatterPiece = 16384;  // bytes one workgroup moves
+struct ScatterRuns {
+  int32_t n_runs;
+  int32_t first_vpage[kScatterRuns];
+  int32_t phys_page[kScatterRuns];
+};
+
 // Launchers (plora_kernels.hip).  Both take a list of blocks of 4 records (one matrix-core item +
 // 3 padding records, or up to 4 vector-ALU items) and run one 256-thread workgroup per block, slot
 // and (expand) 512-column chunk.  mode 1: the list holds vector-ALU records only
@@ -96,5 +107,11 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int 
                          hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+
+// Copies `bytes` bytes that lie contiguous at `staging` (device) into the pages pt[0 .. n_pages) (host
+// array, ascending) of the slab, in virtual order; (n_pages - 1) pages < bytes <= n_pages pages,
+// bytes a multiple of 16.
+hipError_t launch_scatter(const uint8_t* staging, uint8_t* slab, int log2_page, uint64_t bytes, const int32_t* pt,
+                          uint32_t n_pages, hipStream_t st);
 
 }  // namespace plora

@@ -1174,6 +1174,38 @@ __global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const S
   else expand_coop_body<DT, kValuTok>(a, it, sl, v, y, lds_pg, red, chunk);
 }
 
+// Staged load (Sec. III-B: adapters arrive in a staging area and are then moved into their pages):
+// the blob lies contiguous in `staging`; workgroup (piece, page) copies one 16 KiB piece of one
+// virtual page to the physical page that the run table names.  Streaming loads and stores: neither
+// side is read again before the next batch.
+__global__ __launch_bounds__(256) void k_scatter_pages(const uint8_t* __restrict__ staging, uint8_t* __restrict__ slab,
+                                                       const ScatterRuns runs, const int log2_page,
+                                                       const uint64_t bytes, const int vpage0) {
+  const int vpage = vpage0 + (int)blockIdx.y;
+  int lo = 0, hi = runs.n_runs - 1;  // last run that starts at or before vpage
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (runs.first_vpage[mid] <= vpage) lo = mid; else hi = mid - 1;
+  }
+  const uint64_t page = (uint64_t)(runs.phys_page[lo] + (vpage - runs.first_vpage[lo]));
+  const uint64_t in_page = (uint64_t)blockIdx.x * kScatterPiece;
+  const uint64_t src0 = ((uint64_t)vpage << log2_page) + in_page;
+  if (src0 >= bytes) return;
+  uint64_t left = bytes - src0;  // to the end of the blob, of the page and of the piece
+  const uint64_t page_left = ((uint64_t)1 << log2_page) - in_page;
+  if (page_left < left) left = page_left;
+  const uint32_t n = (uint32_t)(left < (uint64_t)kScatterPiece ? left : (uint64_t)kScatterPiece);
+  const uint8_t* src = staging + src0;
+  uint8_t* dst = slab + (page << log2_page) + in_page;
+#pragma unroll
+  for (uint32_t o = threadIdx.x * 16u; o < (uint32_t)kScatterPiece; o += 256u * 16u) {
+    if (o < n) {
+      const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src + o));
+      __builtin_nontemporal_store(q, reinterpret_cast<u32x4_t*>(dst + o));
+    }
+  }
+}
+
 }  // namespace
 
 // Launch with optional timing events attached to the dispatch itself (start / stop timestamps of
@@ -1230,6 +1262,35 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
                     : a.slot_fastest == 2 ? dim3(max_chunks, nb, n_slots) : dim3(nb, max_chunks, n_slots);
     launch(table[mode][dtype], grid, dim3(mode == 1 ? kWave : 256), st, first == 0 ? e0 : nullptr,
            first + step >= n_blocks ? e1 : nullptr, a, p);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_scatter(const uint8_t* staging, uint8_t* slab, int log2_page, uint64_t bytes, const int32_t* pt,
+                          uint32_t n_pages, hipStream_t st) {
+  if (bytes == 0 || n_pages == 0) return hipSuccess;
+  if (!staging || !slab || !pt || log2_page < 12 || (bytes & 15) || bytes > ((uint64_t)n_pages << log2_page) ||
+      bytes <= ((uint64_t)(n_pages - 1) << log2_page))
+    return hipErrorInvalidValue;
+  const uint64_t P = (uint64_t)1 << log2_page;
+  const unsigned pieces = (unsigned)((P + kScatterPiece - 1) / kScatterPiece);
+  uint32_t l = 0;
+  while (l < n_pages) {  // one launch per kScatterRuns runs of consecutive physical pages
+    ScatterRuns runs;
+    runs.n_runs = 0;
+    const uint32_t vpage0 = l;
+    while (l < n_pages && runs.n_runs < kScatterRuns) {
+      uint32_t h = l + 1;
+      while (h < n_pages && pt[h] == pt[h - 1] + 1) ++h;
+      runs.first_vpage[runs.n_runs] = (int32_t)l;
+      runs.phys_page[runs.n_runs] = pt[l];
+      ++runs.n_runs;
+      l = h;
+    }
+    for (uint32_t v0 = vpage0; v0 < l; v0 += 65535u) {  // grid.y is limited to 65535
+      const uint32_t nv = l - v0 < 65535u ? l - v0 : 65535u;
+      hipLaunchKernelGGL(k_scatter_pages, dim3(pieces, nv), dim3(256), 0, st, staging, slab, runs, log2_page, bytes, (int)v0);
+    }
   }
   return hipGetLastError();
 }

@@ -138,6 +138,15 @@ struct plora_pool {
                                                  // most this many workgroups use the cooperative kernels (0 = never)
   int slot_major[2] = {-1, 2}; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always;
                                // 2 (expand): the 512-column chunks are the fastest dimension
+  // staged loads: two device buffers that take a blob in one copy before a kernel moves it into its pages
+  uint64_t staging_cap = 0;       // largest blob that goes staged (0 = loads copy straight into the pages)
+  uint64_t stage_bytes = 0;       // bytes allocated per buffer
+  int staging_min_runs = 3;       // a placement of at least this many runs of consecutive pages goes staged
+  uint8_t* stage[2] = {nullptr, nullptr};
+  hipEvent_t stage_free[2] = {nullptr, nullptr};  // recorded after the scatter that last read the buffer
+  bool stage_used[2] = {false, false};
+  int stage_next = 0;
+  uint64_t staged_loads = 0;
   // kernel timing (plora_profile)
   bool profiling = false;
   struct ProfRec { int cls; hipEvent_t e0, e1; };
@@ -257,6 +266,23 @@ void arrange_blocks(const ItemGroups& heavy, const ItemGroups& light, bool xcd_a
 
 }  // namespace
 
+// Copies into reused pages must not overtake kernels of batches that read them: `st` is made to wait
+// for every listed marker that has not passed yet (once per stream and marker).
+static int wait_for_earlier_readers(plora_pool* p, hipStream_t st) {
+  for (size_t k = 0; k < p->reuse_wait.size();) {
+    auto& w = p->reuse_wait[k];
+    const int passed = marker_passed(*w.m);
+    if (passed < 0) return passed;
+    if (passed) { p->reuse_wait.erase(p->reuse_wait.begin() + k); continue; }
+    if (std::find(w.waited.begin(), w.waited.end(), st) == w.waited.end()) {
+      HIP_TRY(hipStreamWaitEvent(st, w.m->ev, 0));
+      w.waited.push_back(st);
+    }
+    ++k;
+  }
+  return PLORA_OK;
+}
+
 extern "C" {
 
 int plora_version(void) { return 100; }
@@ -337,6 +363,10 @@ int plora_pool_destroy(plora_pool* p) {
     for (auto& r : p->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
     for (hipEvent_t e : p->prof_free) (void)hipEventDestroy(e);
   }
+  for (int i = 0; i < 2; ++i) {
+    if (p->stage[i]) (void)hipFree(p->stage[i]);
+    if (p->stage_free[i]) (void)hipEventDestroy(p->stage_free[i]);
+  }
   for (plora_batch* b : p->batches) {
     if (b->h_img) { if (p->placement_only) ::operator delete(b->h_img); else (void)hipHostFree(b->h_img); }
     if (b->d_img) (void)hipFree(b->d_img);
@@ -370,18 +400,6 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
       HIP_TRY(hipEventCreate(&a.ev_start));
       HIP_TRY(hipEventCreate(&a.ev_ready));
     }
-    // copies into reused pages must not overtake kernels of batches that read them
-    for (size_t k = 0; k < p->reuse_wait.size();) {
-      auto& w = p->reuse_wait[k];
-      const int passed = marker_passed(*w.m);
-      if (passed < 0) return passed;
-      if (passed) { p->reuse_wait.erase(p->reuse_wait.begin() + k); continue; }
-      if (std::find(w.waited.begin(), w.waited.end(), st) == w.waited.end()) {
-        HIP_TRY(hipStreamWaitEvent(st, w.m->ev, 0));
-        w.waited.push_back(st);
-      }
-      ++k;
-    }
   }
   // first fit: the m lowest-numbered free pages, ascending
   a.pt.clear();
@@ -402,25 +420,49 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
   p->n_free -= (uint32_t)m;
 
   if (!p->placement_only) {
-    hipError_t e = hipEventRecord(a.ev_start, st);
-    uint64_t l = 0;
-    while (e == hipSuccess && l < m) {  // one copy per run of consecutive physical pages
-      uint64_t h = l + 1;
-      while (h < m && a.pt[h] == a.pt[h - 1] + 1) ++h;
-      const uint64_t lo = l * p->P, hi = std::min<uint64_t>(h * p->P, S);
-      e = hipMemcpyAsync(p->slab + (uint64_t)a.pt[l] * p->P, (const uint8_t*)host + lo, hi - lo, hipMemcpyHostToDevice, st);
+    uint64_t runs = 1;
+    for (uint64_t l = 1; l < m; ++l) runs += a.pt[l] != a.pt[l - 1] + 1;
+    const bool staged = p->staging_cap >= S && runs >= (uint64_t)p->staging_min_runs;
+    hipError_t e = hipSuccess;
+    int rc = PLORA_OK;
+    if (staged) {
+      // one copy into a staging buffer (it may run while earlier readers of the freed pages still do),
+      // then a kernel that moves the pages into place
+      const int k = p->stage_next;
+      p->stage_next ^= 1;
+      if (p->stage_used[k]) e = hipStreamWaitEvent(st, p->stage_free[k], 0);
+      if (e == hipSuccess) e = hipEventRecord(a.ev_start, st);
+      if (e == hipSuccess) e = hipMemcpyAsync(p->stage[k], host, S, hipMemcpyHostToDevice, st);
       p->h2d_copies++;
-      l = h;
+      if (e == hipSuccess) rc = wait_for_earlier_readers(p, st);
+      if (e == hipSuccess && rc == PLORA_OK) e = launch_scatter(p->stage[k], p->slab, p->log2P, S, a.pt.data(), (uint32_t)m, st);
+      if (e == hipSuccess && rc == PLORA_OK) {
+        e = hipEventRecord(p->stage_free[k], st);
+        p->stage_used[k] = true;
+      }
+    } else {
+      rc = wait_for_earlier_readers(p, st);
+      if (rc == PLORA_OK) e = hipEventRecord(a.ev_start, st);
+      uint64_t l = 0;
+      while (rc == PLORA_OK && e == hipSuccess && l < m) {  // one copy per run of consecutive physical pages
+        uint64_t h = l + 1;
+        while (h < m && a.pt[h] == a.pt[h - 1] + 1) ++h;
+        const uint64_t lo = l * p->P, hi = std::min<uint64_t>(h * p->P, S);
+        e = hipMemcpyAsync(p->slab + (uint64_t)a.pt[l] * p->P, (const uint8_t*)host + lo, hi - lo, hipMemcpyHostToDevice, st);
+        p->h2d_copies++;
+        l = h;
+      }
     }
-    if (e == hipSuccess) e = hipEventRecord(a.ev_ready, st);
-    if (e != hipSuccess) {  // undo the placement
-      g_last_hip = (int)e; (void)hipGetLastError();
+    if (e == hipSuccess && rc == PLORA_OK) e = hipEventRecord(a.ev_ready, st);
+    if (e != hipSuccess || rc != PLORA_OK) {  // undo the placement
+      if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); rc = PLORA_ERR_HIP; }
       for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
       p->n_free += (uint32_t)m;
       p->hint_word = std::min<uint32_t>(p->hint_word, a.pt.empty() ? p->hint_word : (uint32_t)a.pt[0] >> 6);
       a.pt.clear();
-      return PLORA_ERR_HIP;
+      return rc;
     }
+    if (staged) p->staged_loads++;
     a.copy_pending = true;
     p->h2d_bytes += S;
   }
@@ -483,7 +525,7 @@ int plora_pool_stats(plora_pool* p, plora_stats* o) {
   o->resident_adapters = p->resident_adapters; o->resident_bytes = p->resident_bytes;
   o->internal_frag_bytes = o->used_pages * p->P - p->resident_bytes;
   o->loads = p->loads; o->evictions = p->evictions; o->nomem_failures = p->nomem;
-  o->h2d_bytes = p->h2d_bytes; o->h2d_copies = p->h2d_copies; o->h2d_ms = p->h2d_ms;
+  o->h2d_bytes = p->h2d_bytes; o->h2d_copies = p->h2d_copies; o->h2d_ms = p->h2d_ms; o->staged_loads = p->staged_loads;
   return PLORA_OK;
 }
 
@@ -498,6 +540,34 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
   if (k == "mfma_min_work" || k == "mfma_min_work_expand") {
     if (value < 1 || value > (1 << 30)) return PLORA_ERR_INVAL;
     (k == "mfma_min_work" ? p->mfma_min_work : p->mfma_min_work_expand) = value;
+    return PLORA_OK;
+  }
+  if (k == "staging_min_runs") {
+    if (value < 1 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    p->staging_min_runs = (int)value;
+    return PLORA_OK;
+  }
+  if (k == "staging_bytes") {
+    if (value < 0 || value > ((int64_t)1 << 36) || p->placement_only) return PLORA_ERR_INVAL;
+    if (value == 0) { p->staging_cap = 0; return PLORA_OK; }  // the buffers stay: copies may be in flight
+    const uint64_t want = align_up((uint64_t)value, 256);
+    uint64_t have = 0;
+    if (p->stage[0] && p->stage[1]) have = p->stage_bytes;
+    if (want > have) {
+      HIP_TRY(hipDeviceSynchronize());
+      for (int i = 0; i < 2; ++i) {
+        if (p->stage[i]) { HIP_TRY(hipFree(p->stage[i])); p->stage[i] = nullptr; }
+        p->stage_used[i] = false;
+      }
+      p->staging_cap = 0;
+      p->stage_bytes = 0;
+      for (int i = 0; i < 2; ++i) {
+        HIP_TRY(hipMalloc((void**)&p->stage[i], want));
+        if (!p->stage_free[i]) HIP_TRY(hipEventCreateWithFlags(&p->stage_free[i], hipEventDisableTiming));
+      }
+      p->stage_bytes = want;
+    }
+    p->staging_cap = (uint64_t)value;
     return PLORA_OK;
   }
   if (k == "batches_per_marker") {

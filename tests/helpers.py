@@ -42,7 +42,7 @@ class Case:
     """Oracle pool + GPU pool holding the same adapters (loaded in the same order)."""
 
     def __init__(self, oracle_mod, layout, ranks, scales, page_bytes, n_pages, seed, max_adapters=None,
-                 max_rank=None, load_order=None, mfma_min_tokens=None, blobs=None):
+                 max_rank=None, load_order=None, mfma_min_tokens=None, blobs=None, slab=None):
         import torch
         import paper_2512_20210_amd as P
         self.P, self.torch, self.lay = P, torch, layout
@@ -52,7 +52,7 @@ class Case:
         self.blobs = blobs if blobs is not None else make_adapters(seed, layout, ranks)
         self.pinned = [raw_to_torch(b, pin=True) for b in self.blobs]
         self.opool = oracle_mod.OraclePool(page_bytes, n_pages, layout.d_in, layout.d_out, layout.dtype, na, self.max_rank)
-        self.gpool = P.PagedLoraPool(page_bytes, n_pages, layout.d_in, layout.d_out, layout.dtype, na, self.max_rank)
+        self.gpool = P.PagedLoraPool(page_bytes, n_pages, layout.d_in, layout.d_out, layout.dtype, na, self.max_rank, slab=slab)
         if mfma_min_tokens is not None:
             self.set_mfma(mfma_min_tokens)
         self.stream = torch.cuda.current_stream().cuda_stream

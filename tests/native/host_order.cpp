@@ -8,6 +8,7 @@
 //     overtook a queued kernel, a kernel that overtook its adapter's copy, or a batch object reused
 //     under a queued kernel all show up as a foreign or missing tag.
 // With the runtime's waits switched off the same histories must produce violations (the check has teeth).
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -20,7 +21,7 @@
 #include "plora_internal.h"
 
 namespace {
-long g_violations = 0, g_kernels_run = 0, g_pages_checked = 0;
+long g_violations = 0, g_kernels_run = 0, g_pages_checked = 0, g_staged_loads = 0;
 bool g_verbose = true;
 std::shared_ptr<std::set<uint64_t>> g_expect;  // (adapter + 1) << 24 | load generation, of the batch being queued
 int g_elt = 2;
@@ -79,6 +80,19 @@ hipError_t launch_expand(int, const LaunchArgs& a, const SlotPtrs&, int, int, in
   fakehip::enqueue_kernel(st, [a, expect] { kernel_body(a, expect); });
   return hipSuccess;
 }
+// The scatter of a staged load, done for real when the stream reaches it (device memory is host memory here).
+hipError_t launch_scatter(const uint8_t* staging, uint8_t* slab, int log2_page, uint64_t bytes, const int32_t* pt,
+                          uint32_t n_pages, hipStream_t st) {
+  std::vector<int32_t> table(pt, pt + n_pages);
+  fakehip::enqueue_kernel(st, [=] {
+    const uint64_t P = (uint64_t)1 << log2_page;
+    for (uint32_t l = 0; l < table.size(); ++l) {
+      const uint64_t lo = l * P, hi = std::min<uint64_t>(lo + P, bytes);
+      std::memcpy(slab + (uint64_t)table[l] * P, staging + lo, hi - lo);
+    }
+  });
+  return hipSuccess;
+}
 }  // namespace plora
 
 #define CHECK(c) do { if (!(c)) { std::printf("CHECK failed at line %d: %s\n", __LINE__, #c); std::exit(1); } } while (0)
@@ -86,7 +100,7 @@ hipError_t launch_expand(int, const LaunchArgs& a, const SlotPtrs&, int, int, in
 static uint64_t rnd(uint64_t& s) { s ^= s >> 12; s ^= s << 25; s ^= s >> 27; return s * 0x2545F4914F6CDD1DULL; }
 
 // One random history; returns the number of violations the kernels saw.
-static long history(uint64_t seed, int per_marker, bool ignore_waits) {
+static long history(uint64_t seed, int per_marker, bool ignore_waits, int staging) {
   g_violations = 0;
   fakehip::set_ignore_waits(ignore_waits);
   uint64_t rng = seed * 0x9E3779B97F4A7C15ULL + 1;
@@ -97,6 +111,10 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits) {
   plora_pool* p = nullptr;
   CHECK(plora_pool_create(P, 24, &lay, nullptr, 0, &p) == PLORA_OK);
   CHECK(plora_pool_set_option(p, "batches_per_marker", per_marker) == PLORA_OK);
+  if (staging) {  // every load of at most 4 pages' worth goes through the staging buffers, larger ones directly
+    CHECK(plora_pool_set_option(p, "staging_bytes", 4 * 4096) == PLORA_OK);
+    CHECK(plora_pool_set_option(p, "staging_min_runs", staging) == PLORA_OK);
+  }
   hipStream_t compute[2], copy[2];
   for (auto* s : {&compute[0], &compute[1], &copy[0], &copy[1]}) CHECK(hipStreamCreateWithFlags(s, hipStreamNonBlocking) == hipSuccess);
   const std::vector<hipStream_t> prefer{copy[0], copy[1]};
@@ -158,6 +176,10 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits) {
     fakehip::pump_random(rng, (int)(rnd(rng) % 7), prefer);
   }
   fakehip::drain();
+  plora_stats stats;
+  CHECK(plora_pool_stats(p, &stats) == PLORA_OK);
+  CHECK(staging == 0 ? stats.staged_loads == 0 : staging == 1 ? stats.staged_loads > 10 : true);
+  g_staged_loads += (long)stats.staged_loads;
   CHECK(plora_pool_destroy(p) == PLORA_OK);
   for (void* bl : blobs) CHECK(hipHostFree(bl) == hipSuccess);
   CHECK(hipFree(x) == hipSuccess && hipFree(v) == hipSuccess && hipFree(y) == hipSuccess);
@@ -170,16 +192,22 @@ int main() {
   long total_kernels = 0;
   for (int per_marker : {1, 4, 64})
     for (uint64_t seed = 1; seed <= 40; ++seed) {
-      const long bad = history(seed, per_marker, false);
-      if (bad) { std::printf("seed %llu, a completion event per %d batches: %ld violations\n", (unsigned long long)seed, per_marker, bad); return 1; }
+      for (int staging : {0, 1, 2}) {  // off; every small blob staged; only those in at least two runs
+        const long bad = history(seed, per_marker, false, staging);
+        if (bad) {
+          std::printf("seed %llu, a completion event per %d batches, staging %d: %ld violations\n", (unsigned long long)seed,
+                      per_marker, staging, bad);
+          return 1;
+        }
+      }
     }
   total_kernels = g_kernels_run;
-  CHECK(total_kernels > 10000 && g_pages_checked > 10000);
+  CHECK(total_kernels > 10000 && g_pages_checked > 10000 && g_staged_loads > 1000);
   // the same histories without the runtime honouring waits: the kernels must notice
   g_verbose = false;
   int caught = 0;
-  for (uint64_t seed = 1; seed <= 10; ++seed) caught += history(seed, 4, true) > 0;
+  for (uint64_t seed = 1; seed <= 10; ++seed) caught += history(seed, 4, true, (int)(seed % 3)) > 0;
   CHECK(caught == 10);
-  std::printf("host order run OK (%ld kernels, %ld pages checked)\n", total_kernels, g_pages_checked);
+  std::printf("host order run OK (%ld kernels, %ld pages checked, %ld staged loads)\n", total_kernels, g_pages_checked, g_staged_loads);
   return 0;
 }

@@ -14,15 +14,19 @@ from helpers import TOL_V, TOL_Y, raw_to_torch, rel_err, torch_to_raw
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("quality", [None, 0.86])
-def test_churn_tables_utilisation_and_decode(oracle_mod, quality):
+@pytest.mark.parametrize("quality,staged", [(None, False), (0.86, False), (0.86, True)])
+def test_churn_tables_utilisation_and_decode(oracle_mod, quality, staged):
     """quality None: loads on demand only; 0.86: threshold prefetching on a synthetic prediction before
-    every window, with a decode batch after every window while copies may still be in flight."""
+    every window, with a decode batch after every window while copies may still be in flight; staged:
+    blobs whose pages are scattered go through a staging buffer and the scatter kernel."""
     import torch
     import bench
     from paper_2512_20210_amd.prefetch import PrefetchManager, SyntheticPredictor
     cfg, lay, ranks, scales, pool, pinned, trace = bench.churn_setup("cfg3", blobs_per_rank=3)
     pop = cfg["population"]
+    if staged:
+        pool.set_option("staging_bytes", lay.adapter_elems(cfg["max_rank"]) * 2)
+        pool.set_option("staging_min_runs", 2)
     kb = 3
     blob = lambda i: pinned[(int(ranks[i]), i % kb)]
     copy_stream, prefetch_stream = torch.cuda.Stream(), torch.cuda.Stream()
@@ -61,6 +65,7 @@ def test_churn_tables_utilisation_and_decode(oracle_mod, quality):
         print("prefetch loads", mgr.prefetch_loads, "useful", mgr.useful_prefetches, "wasted", mgr.wasted_prefetches, flush=True)
         assert mgr.useful_prefetches > 0.7 * mgr.prefetch_loads
     assert min(pm.byte_util) >= 0.87, "utilisation fell to %.3f" % min(pm.byte_util)
+    assert (pool.stats()["staged_loads"] > 100) == staged
 
     op = oracle_mod.OraclePool(cfg["page_bytes"], cfg["n_pages"], lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
     for what, aid in mgr.log:

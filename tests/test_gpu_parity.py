@@ -246,3 +246,56 @@ def test_pages_freed_behind_queued_batches_are_rewritten_only_after_their_kernel
             assert err <= TOL_Y[lay.dtype], "batch %d slot %d: y error %.3g" % (k, s, err)
     assert g.stats()["used_pages"] == 128
     case.close()
+
+
+@pytest.mark.parametrize("page_bytes,dims,filler_rank,big_ranks", [
+    (16384, ((4096,), (4096,)), 1, (64, 512, 200)),      # 64, 512 (three scatter launches) and 200 single-page runs
+    (65536, ((1024, 1024), (1024, 1024)), 8, (24, 51)),   # last page partly filled: one and a half 16 KiB pieces
+    (4096, ((64,), (64,)), 16, (100, 7)),                 # pages smaller than the piece one workgroup moves
+])
+def test_staged_loads_put_the_same_bytes_in_the_same_pages(oracle_mod, page_bytes, dims, filler_rank, big_ranks):
+    """Staged load (one copy into a staging buffer + scatter kernel) on a pool whose free pages are
+    single-page holes: page tables as the oracle's, slab bytes through the tables identical to the
+    blobs, and a batch over the staged adapters matches the oracle."""
+    import torch
+    lay = Layout(dims[0], dims[1], DT_BF16)
+    C = sum(dims[0]) + sum(dims[1])
+    pages_of = lambda r: -(-(r * 2 * C) // page_bytes)
+    assert pages_of(filler_rank) == 1
+    need = sum(pages_of(r) for r in big_ranks)
+    n_fill = 2 * need + 2
+    ranks = [filler_rank] * n_fill + list(big_ranks)
+    n_pages = n_fill + 8
+    slab = torch.zeros(n_pages * page_bytes, dtype=torch.uint8, device="cuda")
+    case = Case(oracle_mod, lay, ranks, [16.0 / r for r in ranks], page_bytes, n_pages, seed=31,
+                load_order=list(range(n_fill)), max_rank=max(ranks), slab=slab)
+    g = case.gpool
+    g.set_option("staging_bytes", max(big_ranks) * 2 * C)
+    for i in range(0, n_fill, 2):
+        case.evict(i)
+    for k, r in enumerate(big_ranks):
+        aid = n_fill + k
+        print("staged load of rank", r, "=", pages_of(r), "pages of", page_bytes, flush=True)
+        pt = case.load(aid)  # asserts that the table equals the oracle's
+        assert len(pt) == pages_of(r)
+    torch.cuda.synchronize()
+    # the last adapter may have found the contiguous tail of the pool: count what went staged
+    st = g.stats()
+    assert st["staged_loads"] >= len(big_ranks) - 1, st
+    pages = slab.view(n_pages, page_bytes).cpu().numpy()
+    for k, r in enumerate(big_ranks):
+        aid = n_fill + k
+        S = r * 2 * C
+        pt = case.opool.page_table(aid)
+        got = pages[pt].reshape(-1)[:S]
+        assert (got == case.blobs[aid].view(np.uint8).reshape(-1)).all(), "slab bytes of adapter %d differ from its blob" % aid
+    # untouched neighbours: the fillers that stayed keep their bytes
+    for i in range(1, n_fill, 2):
+        pt = case.opool.page_table(i)
+        S = filler_rank * 2 * C
+        assert (pages[pt].reshape(-1)[:S] == case.blobs[i].view(np.uint8).reshape(-1)).all()
+    rng = np.random.default_rng(4)
+    ids = np.array([n_fill + k for k in range(len(big_ranks))] + [1, 3], dtype=np.int32)
+    t2a = ids[rng.integers(0, len(ids), size=24)].astype(np.int32)
+    case.run(t2a, seed=9)
+    case.close()
