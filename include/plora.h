@@ -176,6 +176,11 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * event on the stream per this many batches instead of one per batch; the library records a pending
  * one itself whenever an eviction, a load or the reuse of a batch object has to order against it, so
  * the value changes only how long pages and batch objects may stay held, never results).
+ * "panel_min_blocks" (>= 0, default 8): expand cuts the large adapter groups of a batch into blocks of
+ * 64 tokens and runs them in a kernel that holds a panel of B in LDS when the batch has at least this
+ * many such blocks (prefill); other batches (decode: a hot adapter or two) cut them into items of 16
+ * tokens for the ordinary kernel instead (0 = always).  "mfma_cols_max_group" (default 32): in a
+ * batch of the first kind, a group's last <= this many tokens still go as 16-token items.
  * "staging_bytes" (0 .. 2^36, default 0 = off) and "staging_min_runs" (>= 1, default 3: with two runs the direct copies are as fast): staged loads
  * (Sec. III-B: loaded adapters arrive in a staging area before they are moved into place).  With
  * staging on, plora_load_adapter sends a blob of at most staging_bytes whose pages form at least

@@ -55,6 +55,9 @@ __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<
 #ifndef PLORA_SHRINK_WG_PER_CU
 #define PLORA_SHRINK_WG_PER_CU 3
 #endif
+#ifndef PLORA_PANEL_WG_PER_CU
+#define PLORA_PANEL_WG_PER_CU 3
+#endif
 #ifndef PLORA_EXPAND_WG_PER_CU
 #define PLORA_EXPAND_WG_PER_CU 3
 #endif
@@ -131,6 +134,16 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
   if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
   return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
+// Two fp32 -> one register of two bf16, round to nearest even, in one instruction (v_cvt_pk_bf16_f32).
+#ifndef PLORA_HW_BF16_CVT
+#define PLORA_HW_BF16_CVT 1
+#endif
+typedef __bf16 bf16x2_cvt_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_cvt_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+  const f32x2_cvt_t f = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_cvt_t));
+}
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
   return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
 }
@@ -141,10 +154,15 @@ __device__ __forceinline__ uint4 pack(const float* f) {
   if constexpr (DT == 2) {
     q.x = __float_as_uint(f[0]); q.y = __float_as_uint(f[1]); q.z = __float_as_uint(f[2]); q.w = __float_as_uint(f[3]);
   } else if constexpr (DT == 1) {
+#if PLORA_HW_BF16_CVT
+    q.x = f32x2_to_bf16x2(f[0], f[1]); q.y = f32x2_to_bf16x2(f[2], f[3]);
+    q.z = f32x2_to_bf16x2(f[4], f[5]); q.w = f32x2_to_bf16x2(f[6], f[7]);
+#else
     q.x = f32_to_bf16_bits(f[0]) | (f32_to_bf16_bits(f[1]) << 16);
     q.y = f32_to_bf16_bits(f[2]) | (f32_to_bf16_bits(f[3]) << 16);
     q.z = f32_to_bf16_bits(f[4]) | (f32_to_bf16_bits(f[5]) << 16);
     q.w = f32_to_bf16_bits(f[6]) | (f32_to_bf16_bits(f[7]) << 16);
+#endif
   } else {
     q.x = f32_to_f16_bits(f[0]) | (f32_to_f16_bits(f[1]) << 16);
     q.y = f32_to_f16_bits(f[2]) | (f32_to_f16_bits(f[3]) << 16);
@@ -600,6 +618,19 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
 // Splits 8 fp32 values into a high and a low 16-bit part: hi = round(v), lo = round(v - hi).
 template <int DT>
 __device__ __forceinline__ void split_hi_lo(const float* f, uint4& hi, uint4& lo) {
+#if PLORA_HW_BF16_CVT
+  if constexpr (DT == 1) {
+    uint32_t hp[4], lp[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      hp[e] = f32x2_to_bf16x2(f[2 * e], f[2 * e + 1]);
+      lp[e] = f32x2_to_bf16x2(f[2 * e] - __uint_as_float(hp[e] << 16), f[2 * e + 1] - __uint_as_float(hp[e] & 0xffff0000u));
+    }
+    hi = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+    lo = make_uint4(lp[0], lp[1], lp[2], lp[3]);
+    return;
+  }
+#endif
   uint32_t h[8], l[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
@@ -733,21 +764,56 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
   }
 }
 
-// expand, matrix-core item: D[token, col] += V[token, j] * B[j, col] for up to 64 tokens x 512
-// columns, by a workgroup of 4 wavefronts with B held stationary in LDS.  The 512 columns are done as
-// two halves of 256; rows of B in panels of 64.  For a panel the 4 wavefronts each fetch one
-// 32-row x 128-column tile of B (8 loads of 16 bytes per lane: lane (g, c) gets the 8x8 block rows
-// 8 g .. 8 g + 7 x columns 8 c .. 8 c + 7), transpose it in registers into eight 8-value K-vectors
-// (one per column offset cc) and park them in LDS in MFMA operand order.  Then wavefront w multiplies
-// token tile w (16 tokens) against all four tiles: MFMA cc of a tile yields the real columns
-// 8 c + cc, so a lane ends with 8 consecutive columns of y for each of its 4 token rows and updates
-// y with 16-byte read-modify-writes.  B is read once per 64 tokens; v goes in as hi + lo 16-bit
-// halves (two MFMAs) so that fp32 v loses nothing that matters.  Items of at most 32 tokens take the
-// column-split form above instead.
-static_assert(kMfmaTokE == 64 || kMfmaTokE == 32 || kMfmaTokE == 16, "host work items must match the kernel's tiles");
+// Page pairs of every row's 1 KiB piece of the 512-column chunk, staged in LDS by all 256 threads
+// (a piece may straddle one page boundary).
+__device__ __forceinline__ void expand_stage_pages(const LaunchArgs& a, const ItemRec& it, int2* lds_pg, uint64_t base,
+                                                   uint64_t rowb, int EB) {
+  const int r = it.rank, lp = a.log2_page;
+  const int n_pt = table_len(a, r, EB);
+  const int32_t* ptg = a.pt + it.pt_off;
+  for (int j = threadIdx.x; j < r; j += 256) {
+    const uint64_t vo = base + (uint64_t)j * rowb;
+    const uint32_t q0 = (uint32_t)(vo >> lp);
+    const uint32_t q1 = imin((int)((vo + 1023) >> lp), n_pt - 1);
+    lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
+  }
+}
+
+// expand, matrix-core item of at most kMfmaTokCols tokens, by a workgroup of 4 wavefronts: stage the
+// page pairs, then every wavefront takes its 128 columns (column-split form above).
+template <int DT>
+__device__ __forceinline__ void expand_mfma_cols_item(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+                                                      const float* __restrict__ v, uint8_t* __restrict__ y,
+                                                      int2* lds_pg, int chunk) {
+  constexpr int EB = 2;
+  const int n0i = chunk * 512;
+  if (n0i >= sl.d_out) return;  // uniform over the workgroup
+  const uint64_t rowb = (uint64_t)sl.d_out * EB;
+  const uint64_t base = (uint64_t)it.rank * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0i * EB;
+  expand_stage_pages(a, it, lds_pg, base, rowb, EB);
+  __syncthreads();
+  if (item_once(it)) expand_mfma_cols_body<DT, 1, true>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+  else expand_mfma_cols_body<DT, 1, false>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+}
+
+// expand, matrix-core item of 17 .. 64 tokens (batches with many large groups: prefill):
+// D[token, col] += V[token, j] * B[j, col] for up to 64 tokens x 512 columns, by a workgroup of 4
+// wavefronts with B held stationary in LDS.  The 512 columns are done as two halves of 256; rows of
+// B in panels of 64.  For a panel the 4 wavefronts each fetch one 32-row x 128-column tile of B
+// (8 loads of 16 bytes per lane: lane (g, c) gets the 8x8 block rows 8 g .. 8 g + 7 x columns
+// 8 c .. 8 c + 7), transpose it in registers into eight 8-value K-vectors (one per column offset cc)
+// and park them in LDS in MFMA operand order.  Then wavefront w multiplies token tile w (16 tokens)
+// against all four tiles: MFMA cc of a tile yields the real columns 8 c + cc, so a lane ends with 8
+// consecutive columns of y for each of its 4 token rows and updates y with 16-byte
+// read-modify-writes.  B is read once per 64 tokens; v goes in as hi + lo 16-bit halves (two MFMAs)
+// so that fp32 v loses nothing that matters.  Per panel, the tile of B and the rows of v are
+// requested together.  (Requesting the half's rows of y up front as well costs more in registers,
+// hence resident workgroups, than the overlap returns; strips of 128 columns per workgroup instead of
+// 512 are slower too: v is then re-read four times as often.)
+static_assert(kMfmaTokE == 64, "host work items must match the kernel's tiles");
 
 template <int DT>
-__device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
+__device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                   const float* __restrict__ v, uint8_t* __restrict__ y,
                                                   uint4 (*op)[8][kWave], int2* lds_pg, int chunk) {
   constexpr int EB = 2;
@@ -759,23 +825,7 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
   const uint32_t pmask = (1u << lp) - 1;
   const uint64_t rowb = (uint64_t)d_out * EB;
   const uint64_t base = (uint64_t)r * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0i * EB;
-  {  // page pairs of every row's 1 KiB piece, by all 256 threads
-    const int n_pt = table_len(a, r, EB);
-    const int32_t* ptg = a.pt + it.pt_off;
-    for (int j = tid; j < r; j += 256) {
-      const uint64_t vo = base + (uint64_t)j * rowb;
-      const uint32_t q0 = (uint32_t)(vo >> lp);
-      const uint32_t q1 = imin((int)((vo + 1023) >> lp), n_pt - 1);
-      lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
-    }
-  }
-  if (kMfmaTokE <= kMfmaTokCols || it.ntok <= kMfmaTokCols) {  // uniform: few tokens -> split the columns, not the tokens
-    __syncthreads();
-    if (item_once(it)) expand_mfma_cols_body<DT, 1, true>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
-    else expand_mfma_cols_body<DT, 1, false>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
-    return;
-  }
-  if constexpr (kMfmaTokE > 32) {
+  expand_stage_pages(a, it, lds_pg, base, rowb, EB);
   const int32_t* perm = a.perm + it.tok[0];
   const bool has_tok = wave * 16 < it.ntok;            // this wavefront owns token tile `wave`
   const int tc = perm[imin(wave * 16 + c, it.ntok - 1)];  // token of operand row c
@@ -789,6 +839,7 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
   for (int half = 0; half < 2; ++half) {
     const int nh0 = n0i + half * 256;
     if (nh0 >= d_out) break;
+    uint4 yq[2][4];
     f32x4 acc[2][8];
 #pragma unroll
     for (int ct = 0; ct < 2; ++ct)
@@ -796,6 +847,7 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
       for (int cc = 0; cc < 8; ++cc) acc[ct][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     for (int j0 = 0; j0 < r; j0 += 64) {
+      float vf[2][8];  // this wavefront's rows of v for the panel, requested together with the tile of B
       {  // stage tile (ks_w, ct_w) of this panel
         const int ncol = nh0 + ct_w * 128 + 8 * c;
         const bool okc = ncol < d_out;
@@ -810,6 +862,21 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
           const int2 pp = lds_pg[je];
           const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
           wr[jj] = ldw16<false>(a.slab + (pg << lp) + (inpage & pmask));
+        }
+        if (has_tok) {
+#pragma unroll
+          for (int ks = 0; ks < 2; ++ks) {
+            const int jv = j0 + ks * 32 + 8 * g;
+            if (jv + 8 <= r && (vs & 3) == 0) {
+              const float4 va = *reinterpret_cast<const float4*>(vrow + jv);
+              const float4 vb = *reinterpret_cast<const float4*>(vrow + jv + 4);
+              vf[ks][0] = va.x; vf[ks][1] = va.y; vf[ks][2] = va.z; vf[ks][3] = va.w;
+              vf[ks][4] = vb.x; vf[ks][5] = vb.y; vf[ks][6] = vb.z; vf[ks][7] = vb.w;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) vf[ks][e] = (jv + e < r) ? vrow[jv + e] : 0.f;
+            }
+          }
         }
 #pragma unroll
         for (int jj = 0; jj < 8; ++jj)
@@ -830,19 +897,9 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
       if (has_tok) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
-          const int jv = j0 + ks * 32 + 8 * g;
           if (j0 + ks * 32 < r) {  // uniform
-            float vf[8];
-            if (jv + 8 <= r && (vs & 3) == 0) {
-              const float4 va = *reinterpret_cast<const float4*>(vrow + jv);
-              const float4 vb = *reinterpret_cast<const float4*>(vrow + jv + 4);
-              vf[0] = va.x; vf[1] = va.y; vf[2] = va.z; vf[3] = va.w; vf[4] = vb.x; vf[5] = vb.y; vf[6] = vb.z; vf[7] = vb.w;
-            } else {
-#pragma unroll
-              for (int e = 0; e < 8; ++e) vf[e] = (jv + e < r) ? vrow[jv + e] : 0.f;
-            }
             uint4 vhi, vlo;
-            split_hi_lo<DT>(vf, vhi, vlo);
+            split_hi_lo<DT>(vf[ks], vhi, vlo);
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
 #pragma unroll
@@ -861,14 +918,13 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
       for (int ct = 0; ct < 2; ++ct) {
         const int n = nh0 + ct * 128 + 8 * c;
         if (n < d_out) {
-          uint4 yq[4];
 #pragma unroll
-          for (int i = 0; i < 4; ++i) yq[i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
+          for (int i = 0; i < 4; ++i) yq[ct][i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             if (wave * 16 + g * 4 + i < it.ntok) {
               float yf[8];
-              unpack<DT>(yq[i], yf);
+              unpack<DT>(yq[ct][i], yf);
 #pragma unroll
               for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[ct][cc][i];
               sty16(y + ((uint64_t)trow[i] * d_out + n) * EB, pack<DT>(yf));
@@ -878,7 +934,6 @@ __device__ __forceinline__ void expand_mfma4_body(const LaunchArgs& a, const Ite
       }
     }
   }
-  }  // kMfmaTokE > 32
 }
 
 // Shrink: workgroups of 4 wavefronts.  The work list is a sequence of blocks of 4 records: either
@@ -913,16 +968,19 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
 // independent vector-ALU items, one per wavefront); the column chunk (512 columns) comes from the
 // grid.
 // Grid coordinates of an expand workgroup: list position, 512-column chunk, slot entry.
+// (Plain selects: assigning through the three references in branches makes the compiler route the
+// block indices through a stack array, and everything indexed by them stops being wavefront-uniform.)
 __device__ __forceinline__ void expand_coords(const LaunchArgs& a, int& pos, int& chunk, int& q) {
-  if (a.slot_fastest == 1) { q = blockIdx.x; pos = blockIdx.y; chunk = blockIdx.z; }
-  else if (a.slot_fastest == 2) { chunk = blockIdx.x; pos = blockIdx.y; q = blockIdx.z; }
-  else { pos = blockIdx.x; chunk = blockIdx.y; q = blockIdx.z; }
+  const int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z, sf = a.slot_fastest;
+  q = sf == 1 ? bx : bz;
+  pos = sf == 0 ? bx : by;
+  chunk = sf == 1 ? bz : (sf == 2 ? bx : by);
 }
 
 template <int DT>
 __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const LaunchArgs a, const SlotPtrs p) {
-  __shared__ __align__(16) uint4 op[4][8][kWave];  // 4 staged tiles of B in MFMA operand order (32 KiB)
-  __shared__ int2 lds_pg[kMaxRank];
+  __shared__ int2 my_pg[4 * kMaxRank];  // page pairs: one part per wavefront (vector-ALU items) ...
+  int2* lds_pg = my_pg;                 // ... or the first part for the workgroup's matrix-core item
   int blk, chunk, q;
   expand_coords(a, blk, chunk, q);
   const SlotRec sl = a.slots[p.slot[q]];
@@ -930,17 +988,32 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
   uint8_t* y = (uint8_t*)p.b[q];
   const ItemRec first = a.items[4 * blk];
   if constexpr (DT != 2) {
-    if (item_kind(first) == 1) {
-      expand_mfma4_body<DT>(a, first, sl, v, y, op, lds_pg, chunk);
+    if (item_kind(first) == 1) {  // at most kMfmaTokCols tokens: larger items go to k_expand_panel
+      expand_mfma_cols_item<DT>(a, first, sl, v, y, lds_pg, chunk);
       return;
     }
   }
   const int wave = threadIdx.x >> 6;
   const ItemRec it = a.items[4 * blk + wave];
   if (it.kind < 0) return;  // this path has no workgroup barrier: a wavefront may leave alone
-  // each wavefront stages its row pages in its own part of LDS: the operand tiles are unused here
-  int2* my_pg = reinterpret_cast<int2*>(&op[wave][0][0]);
-  expand_valu_item<DT>(a, it, sl, v, y, my_pg, chunk);
+  expand_valu_item<DT>(a, it, sl, v, y, my_pg + wave * kMaxRank, chunk);
+}
+
+// The matrix-core blocks of a batch with many large adapter groups (prefill): one item of up to 64
+// tokens per workgroup; the list holds matrix-core blocks only (first record of each block of 4).
+template <int DT>
+__global__ __launch_bounds__(256, PLORA_PANEL_WG_PER_CU) void k_expand_panel(const LaunchArgs a, const SlotPtrs p) {
+  __shared__ __align__(16) uint4 op[4][8][kWave];  // 4 staged tiles of B in MFMA operand order (32 KiB)
+  __shared__ int2 lds_pg[kMaxRank];
+  int blk, chunk, q;
+  expand_coords(a, blk, chunk, q);
+  const ItemRec it = a.items[4 * blk];
+  if (item_kind(it) != 1) return;  // uniform
+  const SlotRec sl = a.slots[p.slot[q]];
+  const float* v = (const float*)p.a[q];
+  uint8_t* y = (uint8_t*)p.b[q];
+  if (it.ntok <= kMfmaTokCols) expand_mfma_cols_item<DT>(a, it, sl, v, y, lds_pg, chunk);
+  else expand_panel_item<DT>(a, it, sl, v, y, op, lds_pg, chunk);
 }
 
 // One vector-ALU item per single-wavefront workgroup: record i of the list is item i (padding
@@ -1243,13 +1316,14 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
 
 hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
-  const bool single = mode != 0;  // one record per workgroup
+  const bool single = mode == 1 || mode == 2;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
   if ((!single && a0.n_items % 4) || max_chunks > 65535) return hipErrorInvalidValue;
-  static const KernelFn table[3][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
+  static const KernelFn table[4][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
                                        {k_expand_valu1<0>, k_expand_valu1<1>, k_expand_valu1<2>},
-                                       {k_expand_coop<0>, k_expand_coop<1>, k_expand_coop<2>}};
-  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
+                                       {k_expand_coop<0>, k_expand_coop<1>, k_expand_coop<2>},
+                                       {k_expand_panel<0>, k_expand_panel<1>, nullptr}};
+  if (mode < 0 || mode > 3 || dtype < 0 || dtype > 2 || !table[mode][dtype]) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;

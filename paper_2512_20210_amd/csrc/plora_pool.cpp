@@ -71,6 +71,7 @@ struct ItemGroups {
 struct plora_batch {
   plora_pool* pool = nullptr;
   bool open = false;
+  bool panel = false;  // expand: the matrix-core blocks go to the panel kernel
   hipStream_t stream = nullptr;
   int32_t n_tokens = 0, n_seg = 0, n_perm = 0;
   // host copies for plora_batch_info
@@ -114,6 +115,10 @@ struct plora_pool {
   struct ReuseWait { std::shared_ptr<Event> m; std::vector<hipStream_t> waited; };
   std::vector<ReuseWait> reuse_wait;
   std::shared_ptr<Event> cur_done;                 // marker of the batches ended since the last record
+  int cols_max_group = kMfmaColsMaxGroup;          // expand, panel batches: (remainders of) groups of at most this many tokens go as column-split items
+  int panel_min_blocks = 8;  // expand: a batch with at least this many 64-token blocks of large groups (prefill) sends its
+                             // matrix-core blocks to the panel kernel; other batches cut every large group into
+                             // column-split items (0 = never)
   int batches_per_marker = 4;                      // record the marker once this many batches share it
   std::vector<plora_batch*> batches;               // all batch objects ever made (recycled)
   int open_batches = 0;
@@ -570,6 +575,16 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->staging_cap = (uint64_t)value;
     return PLORA_OK;
   }
+  if (k == "panel_min_blocks") {
+    if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    p->panel_min_blocks = (int)value;
+    return PLORA_OK;
+  }
+  if (k == "mfma_cols_max_group") {
+    if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    p->cols_max_group = (int)value;
+    return PLORA_OK;
+  }
   if (k == "batches_per_marker") {
     if (value < 1 || value > 64) return PLORA_ERR_INVAL;
     p->batches_per_marker = (int)value;
@@ -678,6 +693,24 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       tg.push_back(it);
     }
   };
+  constexpr int kTokBlock = 128;
+  auto expand_on_matrix_cores = [&](const Adapter& a, int32_t n) {
+    const int64_t r32 = ((int64_t)a.rank + 31) / 32 * 32;
+    return mfma_ok && p->mfma_min_tokens_expand > 0 &&
+           (n >= p->mfma_min_tokens_expand || (int64_t)n * a.rank * a.rank >= p->mfma_min_work_expand * r32);
+  };
+  // How the large groups' expand work is cut: a batch with many 64-token blocks (prefill) keeps them
+  // (B is then staged once per 64 tokens) and runs them in the panel kernel; a batch with few
+  // (decode: at most a hot adapter or two) cuts them into column-split items of one token tile.
+  int64_t panel_blocks = 0;
+  for (int32_t u = 0; u < n_seg && p->panel_min_blocks > 0; ++u) {
+    const int32_t n = p->count[touched[u]];
+    if (!expand_on_matrix_cores(p->ad[touched[u]], n)) continue;
+    for (int32_t b0 = 0; b0 < n; b0 += kTokBlock)
+      for (int32_t left = std::min(n - b0, kTokBlock); left > p->cols_max_group; left -= kMfmaTokE) ++panel_blocks;
+  }
+  b->panel = p->panel_min_blocks > 0 && panel_blocks >= p->panel_min_blocks;
+  const int32_t cols_max_group = b->panel ? p->cols_max_group : kTokBlock;
   size_t n_pt_total = 0;
   for (int32_t u = 0; u < n_seg; ++u) {
     const Adapter& a = p->ad[touched[u]];
@@ -686,16 +719,13 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     const int32_t pt_off = (int32_t)n_pt_total;
     n_pt_total += a.pt.size();
     const int16_t rank = (int16_t)a.rank;
-    const int64_t r32 = ((int64_t)a.rank + 31) / 32 * 32;
     const bool mf_s = mfma_ok && p->mfma_min_tokens > 0 &&
                       (n >= p->mfma_min_tokens || (int64_t)n * a.rank >= p->mfma_min_work);
-    const bool mf_e = mfma_ok && p->mfma_min_tokens_expand > 0 &&
-                      (n >= p->mfma_min_tokens_expand || (int64_t)n * a.rank * a.rank >= p->mfma_min_work_expand * r32);
+    const bool mf_e = expand_on_matrix_cores(a, n);
     // Matrix-core items.  Large groups (prefill) are cut into blocks of kTokBlock tokens: a block is
     // the unit that is dealt to an XCD, and inside a block the shrink items go row group by row
     // group with the token groups innermost, so a tile of A is re-read back to back and the block's
     // x tiles (at most kTokBlock rows) stay in L2 for the next row group.
-    constexpr int kTokBlock = 128;
     for (int32_t b0 = 0; b0 < n && (mf_s || mf_e); b0 += kTokBlock) {
       const int32_t b1 = std::min(n, b0 + kTokBlock);
       if (mf_s) {
@@ -713,10 +743,10 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       if (mf_e) {
         double cost = 0.0;
         const int16_t kind = (int16_t)(n <= kMfmaTokCols ? 1 | kItemOnce : 1);
-        // a remainder of at most kMfmaColsMaxGroup tokens goes as column-split items of one token tile
+        // a remainder of at most cols_max_group tokens goes as column-split items of one token tile
         for (int32_t t0 = b0; t0 < b1;) {
           const int32_t left = b1 - t0;
-          const int16_t nt = (int16_t)std::min(left <= kMfmaColsMaxGroup ? kMfmaTokCols : kMfmaTokE, left);
+          const int16_t nt = (int16_t)std::min(left <= cols_max_group ? kMfmaTokCols : kMfmaTokE, left);
           wl[1][1].items.push_back(ItemRec{kind, nt, rank, 0, a.scale, pt_off, {start + t0, 0, 0, 0}});
           cost += a.rank + 2 * nt;
           t0 += nt;
@@ -915,9 +945,12 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     // slots fastest when that keeps every slot on one XCD and all XCDs equally loaded; else the
     // items are the fastest dimension and (optionally) come dealt into XCD queues
     a.slot_fastest = p->slot_major[op] == 2 ? 2 : (p->slot_major[op] == 1 || (p->slot_major[op] < 0 && nq % kXcds == 0)) ? 1 : 0;
-    int layout = (a.slot_fastest != 1 && p->xcd_remap[op] && b->n_items[op][1] > 0) ? 1 : 0;
+    // a batch whose matrix-core expand blocks go to the panel kernel uses the longest-first list: the
+    // matrix-core blocks are its first part
+    const bool panel = op == 1 && b->panel && b->n_heavy[1] > 0;
+    int layout = (!panel && a.slot_fastest != 1 && p->xcd_remap[op] && b->n_items[op][1] > 0) ? 1 : 0;
     // a call that cannot fill the machine is bound by its longest dependent chain: cooperative kernels
-    const bool coop = p->coop_max_workgroups[op] > 0 && b->n_items[op][2] > 0 &&
+    const bool coop = !panel && p->coop_max_workgroups[op] > 0 && b->n_items[op][2] > 0 &&
                       (int64_t)nq * (b->n_items[op][layout] / 4) * chunks <= p->coop_max_workgroups[op];
     if (coop) layout = 2;
     const ItemRec* list = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
@@ -925,10 +958,10 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     if (n_all == 0) continue;
     // one launch over the whole block list, or (longest-first list only) the matrix-core blocks in the
     // 256-thread kernel followed by the vector-ALU records one per single-wavefront workgroup
-    const bool split = layout == 0 && p->split[op] && n_all > b->n_heavy[op];
+    const bool split = layout == 0 && (panel || (p->split[op] && n_all > b->n_heavy[op]));
     struct Part { const ItemRec* items; int n; int mode; };
-    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, coop ? 2 : 0},
-                           {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, 1}};
+    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, panel ? 3 : coop ? 2 : 0},
+                           {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, (panel && !p->split[op]) ? 0 : 1}};
     plora_pool::ProfRec rec{op, nullptr, nullptr};
     if (p->profiling) {
       for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
