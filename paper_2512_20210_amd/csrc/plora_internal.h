@@ -63,7 +63,7 @@ struct SlotRec {
 struct SlotPtrs {
   const void* a[kMaxSlotsPerLaunch];  // shrink: x   expand: v
   void* b[kMaxSlotsPerLaunch];        // shrink: v   expand: y
-  int16_t slot[kMaxSlotsPerLaunch];   // absolute slot number of each entry
+  int32_t slot[kMaxSlotsPerLaunch];   // absolute slot number of each entry (a dword: scalar loads have no 16-bit form)
 };
 
 struct LaunchArgs {

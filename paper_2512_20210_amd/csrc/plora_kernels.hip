@@ -79,6 +79,27 @@ __device__ __forceinline__ uint4 ldw16(const void* p) {
     return *reinterpret_cast<const uint4*>(p);
   }
 }
+// A work record at a wavefront-uniform position, fetched as eight whole dwords (one scalar load) and
+// taken apart in registers: field-by-field reads of its 16-bit members would be separate vector loads,
+// the later ones issued only after the first has been tested.
+__device__ __forceinline__ ItemRec load_item(const ItemRec* __restrict__ rec) {
+  const uint32_t* w = reinterpret_cast<const uint32_t*>(rec);
+  uint32_t d[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) d[i] = w[i];
+  ItemRec it;
+  it.kind = (int16_t)(d[0] & 0xffffu);
+  it.ntok = (int16_t)(d[0] >> 16);
+  it.rank = (int16_t)(d[1] & 0xffffu);
+  it.j0 = (int16_t)(d[1] >> 16);
+  it.scale = __uint_as_float(d[2]);
+  it.pt_off = (int32_t)d[3];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) it.tok[i] = (int32_t)d[4 + i];
+  return it;
+}
+// Index of the wavefront in its workgroup, as a scalar.
+__device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 // Record flag (bit 8 of a non-negative kind): no other item of the batch reads this item's weights.
 __device__ __forceinline__ int item_kind(const ItemRec& it) { return it.kind < 0 ? -1 : (it.kind & 0xff); }
 __device__ __forceinline__ bool item_once(const ItemRec& it) {
@@ -491,7 +512,7 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
                                                   uint8_t (*tile)[2][kSmRows * kSmPitch], int32_t* lds_pt) {
   constexpr int EB = 2;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_id(), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;   // MFMA coordinates
   const int lr = lane >> 3, lp8 = lane & 7; // staging coordinates: row within a group of 8, 16-byte piece
   const int r = it.rank, d_in = sl.d_in, vs = a.v_stride, lp = a.log2_page;
@@ -716,7 +737,7 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
                                                       const float* __restrict__ v, uint8_t* __restrict__ y,
                                                       const int2* lds_pg, int chunk, uint64_t base, uint64_t rowb) {
   constexpr int EB = 2;
-  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int wave = wave_id(), lane = lane_id();
   const int g = lane >> 4, c = lane & 15;
   const int r = it.rank, d_out = sl.d_out, vs = a.v_stride;
   const int n0 = chunk * 512 + wave * kMfmaCols;
@@ -817,7 +838,7 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
                                                   const float* __restrict__ v, uint8_t* __restrict__ y,
                                                   uint4 (*op)[8][kWave], int2* lds_pg, int chunk) {
   constexpr int EB = 2;
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = wave_id(), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
   const int r = it.rank, d_out = sl.d_out, vs = a.v_stride, lp = a.log2_page;
   const int n0i = chunk * 512;
@@ -950,7 +971,7 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
   const SlotRec sl = a.slots[p.slot[q]];
   const uint8_t* x = (const uint8_t*)p.a[q];
   float* v = (float*)p.b[q];
-  const ItemRec first = a.items[4 * blk];
+  const ItemRec first = load_item(a.items + (4 * blk));
   if constexpr (DT != 2) {
     if (item_kind(first) == 1) {
       if (item_once(first)) shrink_mfma4_body<DT, true>(a, first, sl, x, v, tile, lds_pt);
@@ -958,8 +979,8 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
       return;
     }
   }
-  const int wave = threadIdx.x >> 6;
-  const ItemRec it = a.items[4 * blk + wave];
+  const int wave = wave_id();
+  const ItemRec it = load_item(a.items + (4 * blk + wave));
   if (it.kind < 0) return;  // this path has no workgroup barrier: a wavefront may leave alone
   shrink_valu_item<DT>(a, it, sl, x, v, lds_pt + wave * (kPtWindow / 4));
 }
@@ -986,15 +1007,15 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
   const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
-  const ItemRec first = a.items[4 * blk];
+  const ItemRec first = load_item(a.items + (4 * blk));
   if constexpr (DT != 2) {
     if (item_kind(first) == 1) {  // at most kMfmaTokCols tokens: larger items go to k_expand_panel
       expand_mfma_cols_item<DT>(a, first, sl, v, y, lds_pg, chunk);
       return;
     }
   }
-  const int wave = threadIdx.x >> 6;
-  const ItemRec it = a.items[4 * blk + wave];
+  const int wave = wave_id();
+  const ItemRec it = load_item(a.items + (4 * blk + wave));
   if (it.kind < 0) return;  // this path has no workgroup barrier: a wavefront may leave alone
   expand_valu_item<DT>(a, it, sl, v, y, my_pg + wave * kMaxRank, chunk);
 }
@@ -1007,7 +1028,7 @@ __global__ __launch_bounds__(256, PLORA_PANEL_WG_PER_CU) void k_expand_panel(con
   __shared__ int2 lds_pg[kMaxRank];
   int blk, chunk, q;
   expand_coords(a, blk, chunk, q);
-  const ItemRec it = a.items[4 * blk];
+  const ItemRec it = load_item(a.items + (4 * blk));
   if (item_kind(it) != 1) return;  // uniform
   const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];
@@ -1024,7 +1045,7 @@ __global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, cons
   __shared__ int2 lds_pg[kMaxRank];
   int pos, chunk, q;
   expand_coords(a, pos, chunk, q);
-  const ItemRec it = a.items[pos];
+  const ItemRec it = load_item(a.items + (pos));
   if (item_kind(it) != 0) return;
   const SlotRec sl = a.slots[p.slot[q]];
   expand_valu_item<DT>(a, it, sl, (const float*)p.a[q], (uint8_t*)p.b[q], lds_pg, chunk);
@@ -1033,7 +1054,7 @@ __global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, cons
 template <int DT>
 __global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int32_t lds_pt[kPtWindow / 4];
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
+  const ItemRec it = load_item(a.items + (a.slot_fastest ? blockIdx.z : blockIdx.x));
   if (item_kind(it) != 0) return;
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
@@ -1053,7 +1074,7 @@ __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const Item
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt, float (*red)[kShrinkRows * kValuTok]) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
-  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int wave = wave_id(), lane = lane_id();
   const int r = it.rank;
   const int d_in = sl.d_in;
   const int vs = a.v_stride;
@@ -1109,7 +1130,7 @@ template <int DT>
 __global__ __launch_bounds__(256) void k_shrink_coop(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int32_t lds_pt[kPtWindow / 4];
   __shared__ float red[4][kShrinkRows * kValuTok];
-  const ItemRec it = a.items[a.slot_fastest ? blockIdx.z : blockIdx.x];
+  const ItemRec it = load_item(a.items + (a.slot_fastest ? blockIdx.z : blockIdx.x));
   if (item_kind(it) != 0) return;  // uniform over the workgroup
   const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
   const SlotRec sl = a.slots[p.slot[q]];
@@ -1131,7 +1152,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg,
                                                  float* red, int chunk) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
-  const int wave = threadIdx.x >> 6, lane = lane_id();
+  const int wave = wave_id(), lane = lane_id();
   const int r = it.rank;
   const int d_out = sl.d_out;
   const int n0w = chunk * (kWave * VEC);
@@ -1237,7 +1258,7 @@ __global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const S
   __shared__ float red[4 * kValuTok * 8 * kWave];  // 32 KiB
   int pos, chunk, q;
   expand_coords(a, pos, chunk, q);
-  const ItemRec it = a.items[pos];
+  const ItemRec it = load_item(a.items + (pos));
   if (item_kind(it) != 0) return;  // uniform over the workgroup
   const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];

@@ -938,7 +938,7 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
       const int qi = order[q0 + q].second;
       ptrs.a[q] = in[qi];
       ptrs.b[q] = outp[qi];
-      ptrs.slot[q] = (int16_t)(slot0 + qi);
+      ptrs.slot[q] = slot0 + qi;
     }
     const int chunks = order[q0].first;
     q0 += nq;
