@@ -33,9 +33,13 @@ METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token de
 KCLASS = ["shrink", "expand"]
 
 
+SEED_OFFSET = 0  # --seed-offset: another draw of ranks, weights, activations and batches
+
+
 def workload_params(name):
     """Ranks, scales and pool size of a named workload (all drawn from its seed)."""
-    cfg = CONFIGS[name]
+    cfg = dict(CONFIGS[name])
+    cfg["seed"] += SEED_OFFSET
     lay = config_layout(cfg)
     rng = np.random.default_rng(cfg["seed"])
     n_ad = cfg.get("n_adapters") or cfg["population"]
@@ -451,6 +455,7 @@ def main():
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--same-batch", action="store_true", help="reuse one token->adapter draw for every step")
     ap.add_argument("--scatter", action="store_true", help="evict and reload adapters so that their pages are scattered")
+    ap.add_argument("--seed-offset", type=int, default=0, help="added to the workload's seed: another draw of ranks, weights and batches")
     ap.add_argument("--verbose", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -461,6 +466,8 @@ def main():
         print("bench.py: needs a GPU", file=sys.stderr)
         sys.exit(2)
     torch.cuda.set_device(0)
+    global SEED_OFFSET
+    SEED_OFFSET = args.seed_offset
     if args.workload == "cfg3":
         run_churn(args)
         return
@@ -520,7 +527,7 @@ def main():
         avg_ms = kms[dom] / kn[dom]
         per_launch = kb / kn[dom]
         ach = per_launch / (avg_ms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC.get(args.workload) if spc == lay.n_slots else None
+        traffic = MEASURED_TRAFFIC.get(args.workload) if spc == lay.n_slots and SEED_OFFSET == 0 else None  # measured on the default draw
         roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(ach / HBM_PEAK_GBS, 4), traffic=int(traffic[dom]) if traffic else None, avg_launch_ms=round(avg_ms, 5),
                     launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
@@ -532,7 +539,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": {0: "f16", 1: "bf16", 2: "f32"}[lay.dtype],
         "data": "synthetic",
         "config": {"workload": args.workload, "slots": lay.n_slots, "tokens": int(T), "adapters": int(w.n_ad),
-                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc),
+                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc), "seed": int(cfg["seed"]),
                    "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1),
                    "mean_run_of_consecutive_pages": round(w.mean_run_pages, 1), "activation_sets": len(w.act_sets), "activation_bytes_per_set": int(w.act_bytes)},
         "tokens_per_s": round(tokens_total / elapsed, 1),

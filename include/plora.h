@@ -148,9 +148,12 @@ int plora_shrink(plora_pool* pool, const plora_batch* batch, int32_t slot0, int3
 int plora_expand(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const float* const* v,
                  void* const* y, plora_stream stream);
 
-/* Ends the batch: records its completion on its stream, unpins its adapters and recycles the batch
- * object.  Kernels already enqueued keep running; pages freed afterwards are not overwritten before
- * they finish. */
+/* Ends the batch: unpins its adapters, hands the batch object back for reuse and notes that its
+ * completion has to be recorded on its stream (the stream given to plora_batch_begin).  Kernels
+ * already enqueued keep running; pages freed afterwards are not overwritten before they finish.
+ * The record itself may be put on the stream later, by this or a later call into the library (see
+ * the option "batches_per_marker"): a stream that batches ran on must therefore stay valid until
+ * the pool is destroyed, or the option be set to 1, which records inside this call. */
 int plora_batch_end(plora_pool* pool, plora_batch* batch);
 
 /* Counters of the pool (Sec. V-A lists memory utilisation and fragmentation as metrics). */
