@@ -161,7 +161,7 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
 
 /* Tunables.  An adapter group of n tokens and rank r uses the matrix-core items when n >=
  * "mfma_min_tokens" / "mfma_min_tokens_expand" (shrink / expand; defaults 16 / 64; 0 = never, 1 =
- * always) or when its work reaches "mfma_min_work" / "mfma_min_work_expand" (defaults 64 / 384; 1 ..
+ * always) or when its work reaches "mfma_min_work" / "mfma_min_work_expand" (defaults 64 / 128; 1 ..
  * 2^30), where work = n * r for shrink and n * r * r / (r rounded up to a multiple of 32) for expand;
  * they take effect for batches begun afterwards.  "slot_major" (-1 =
  * slots are the fastest grid dimension when their count is a multiple of 8, 0 never, 1 always; for

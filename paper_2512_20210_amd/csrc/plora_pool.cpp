@@ -133,7 +133,7 @@ struct plora_pool {
   // reaches min_work (min_tokens 0 = never).  Shrink: work = n * r.  Expand: work = n * r * (r / r
   // rounded up to 32), the second factor being the used part of the 32-row contraction tile.
   int mfma_min_tokens = 16, mfma_min_tokens_expand = 64;
-  int64_t mfma_min_work = 64, mfma_min_work_expand = 384;
+  int64_t mfma_min_work = 64, mfma_min_work_expand = 128;
   // launch geometry, [shrink, expand]
   int xcd_remap[2] = {1, 0};  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
