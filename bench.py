@@ -28,7 +28,7 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # HBM bytes per launch of the (shrink, expand) kernels measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE (scaled by the factors found on a copy kernel of known size: 2.0 and 1.0); sources:
 # profiles/decode_7b_cfg1_*.md, profiles/decode_13b_layer_cfg4_*.md, profiles/prefill_cfg2_*.md
-MEASURED_TRAFFIC = {"cfg1": (1.813e9, 2.103e9), "cfg4": (2.318e9, 2.457e9), "cfg2": (0.274e9, 0.400e9)}
+MEASURED_TRAFFIC = {"cfg1": (1.813e9, 2.100e9), "cfg4": (2.318e9, 2.452e9), "cfg2": (0.274e9, 0.400e9)}
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
 KCLASS = ["shrink", "expand"]
 
