@@ -691,15 +691,17 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
     }
   }
   uint4 wr[8];
+  if (!TAIL || j8 < r) {  // lanes whose 8 rows all lie past the rank request nothing (r <= 24: whole lane groups)
 #pragma unroll
-  for (int jj = 0; jj < 8; ++jj) {
-    const int j = j8 + jj;
-    const int je = TAIL ? imin(j, r - 1) : j;
-    const uint64_t vo = base + (uint64_t)je * rowb;
-    const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
-    const int2 pp = lds_pg[je];
-    const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
-    wr[jj] = ldw16<NTW>(a.slab + (pg << lp) + (inpage & pmask));
+    for (int jj = 0; jj < 8; ++jj) {
+      const int j = j8 + jj;
+      const int je = TAIL ? imin(j, r - 1) : j;
+      const uint64_t vo = base + (uint64_t)je * rowb;
+      const uint32_t inpage = ((uint32_t)vo & pmask) + lane_b;
+      const int2 pp = lds_pg[je];
+      const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
+      wr[jj] = ldw16<NTW>(a.slab + (pg << lp) + (inpage & pmask));
+    }
   }
   if (TAIL) {
 #pragma unroll
