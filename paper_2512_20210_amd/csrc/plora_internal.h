@@ -22,14 +22,11 @@ constexpr int kExpandU = PLORA_EXPAND_U;        // rows of B in flight per vecto
 #ifndef PLORA_MFMA_TOK_S
 #define PLORA_MFMA_TOK_S 32
 #endif
-#ifndef PLORA_MFMA_TOK_E
-#define PLORA_MFMA_TOK_E 64  // 64: token-split panel form for large groups; 16 or 32: column-split form only
-#endif
 constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item
-constexpr int kMfmaTokE = PLORA_MFMA_TOK_E;     // tokens per matrix-core expand item
+constexpr int kMfmaTokE = 64;           // tokens per matrix-core expand item of the panel kernel
 constexpr int kMfmaTokCols = 16;        // items of at most this many tokens take the column-split form
-constexpr int kMfmaColsMaxGroup = 32;   // groups (or last blocks of groups) of at most this many tokens are cut
-                                        // into column-split items
+constexpr int kMfmaColsMaxGroup = 32;   // panel batches: groups (or last blocks of groups) of at most this many
+                                        // tokens are cut into column-split items (default of an option)
 #ifndef PLORA_MFMA_ROWS
 #define PLORA_MFMA_ROWS 32
 #endif

@@ -15,13 +15,19 @@
 //   expand, vector-ALU item : all rows of B x 64 lanes x 16 bytes of columns x up to 4 tokens;
 //                             no reduction, read-modify-write of y.
 //   expand, matrix-core item: all rows of B x 512 columns; up to 16 tokens: every wavefront its own
-//                             128 columns, B transposed in registers; 33 to 64 tokens: B stationary
+//                             128 columns, B transposed in registers; 17 to 64 tokens (only in
+//                             batches with many large groups, kernel k_expand_panel): B stationary
 //                             in LDS, one 16-token tile per wavefront.  v is split into a high and a
 //                             low half so that fp32 v loses nothing that matters.
 //
 // Two more launch forms use the vector-ALU records alone: one record per single-wavefront workgroup,
 // and the cooperative kernels for calls too small to fill the machine (one record per 256-thread
-// workgroup whose wavefronts split the record's chain of loads).
+// workgroup whose wavefronts split the record's chain of loads).  k_scatter_pages moves a blob that
+// arrived contiguous in a staging buffer into its pages (staged loads).
+//
+// Uniform values stay scalar: grid coordinates, slot record, work record (one 32-byte scalar load)
+// and wavefront index live in scalar registers, so everything derived from them costs no vector
+// registers and no vector memory round trips at the head of a workgroup.
 //
 // Cache policy: y (read once, written once) goes through streaming loads and stores, and so do the
 // weights of items whose rows no other item reads; x, v, page tables and weights that the token
