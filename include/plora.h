@@ -203,6 +203,69 @@ int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 int plora_profile(plora_pool* pool, int enable);
 int plora_profile_read(plora_pool* pool, double* ms, uint64_t* launches);
 
+/* ---------------------------------------------------------------------------------------------
+ * Traffic predictor (Sec. III-A), host only: every pointer below is a host pointer and no call
+ * touches the GPU.  A stack of `layers` LSTM layers of `hidden` units over a sliding window of
+ * `window` prediction intervals, followed by a fully connected layer that gives one access
+ * probability per adapter for the next interval (the paper: 2 layers, 64 units); trained with
+ * Adam on Eq. 2 (binary cross-entropy summed over the adapters, averaged over a minibatch) from a
+ * replay buffer of the most recent `replay` intervals (the paper: lr 1e-3, batch 64, 10,000
+ * observations, an update every 100 requests).  An interval's input is the vector of its
+ * normalised access counts c / (1 + c); the first layer's input weights are one row of 4 * hidden
+ * values per adapter (its learned embedding).
+ * Parameter vector, in this order: layer 0: E[n_adapters][4H], W_hh[4H][H], b[4H]; layers l > 0:
+ * W_ih[4H][H], W_hh[4H][H], b[4H]; output: W_fc[n_adapters][H], b_fc[n_adapters]; gate order in 4H:
+ * input, forget, cell candidate, output.  Arithmetic is fp32.  Not thread-safe. */
+typedef struct plora_predictor plora_predictor;
+typedef struct {
+  int32_t n_adapters; /* >= 1 */
+  int32_t window;     /* intervals the LSTM runs over, 1 .. 1024 */
+  int32_t hidden;     /* 1 .. 1024 */
+  int32_t layers;     /* 1 .. 8 */
+  int32_t replay;     /* intervals kept for training, >= 2 */
+  int32_t batch;      /* samples per Adam step of plora_predictor_train, >= 1 */
+  float lr, beta1, beta2, eps;
+  uint64_t seed;      /* parameter initialisation (uniform in +-1/sqrt(hidden), biases 0) and minibatch sampling */
+} plora_predictor_config;
+
+/* INVAL for a value out of range, NOMEM. */
+int plora_predictor_create(const plora_predictor_config* config, plora_predictor** out);
+int plora_predictor_destroy(plora_predictor* predictor);
+
+/* One finished interval: the adapter ids of its requests (n_ids entries, repeats count).  It becomes
+ * the newest entry of the history and of the replay buffer (the oldest leaves when `replay` is
+ * exceeded).  INVAL for an id outside [0, n_adapters). */
+int plora_predictor_observe(plora_predictor* predictor, const int32_t* ids, int32_t n_ids);
+
+/* Intervals currently in the replay buffer. */
+int64_t plora_predictor_observed(const plora_predictor* predictor);
+
+/* p_hat[n_adapters]: predicted probability that each adapter is requested in the interval that
+ * follows the newest observed one (intervals before the first observation count as empty). */
+int plora_predictor_predict(plora_predictor* predictor, float* p_hat);
+
+/* `steps` Adam updates, each on `batch` samples drawn (splitmix64 on seed and a running counter)
+ * uniformly from the replay buffer: a sample is an interval as the target and the `window`
+ * intervals before it as the input.  mean_loss_out (may be NULL): Eq. 2 averaged over the samples of
+ * all steps.  Does nothing while fewer than 2 intervals have been observed. */
+int plora_predictor_train(plora_predictor* predictor, int32_t steps, float* mean_loss_out);
+
+/* One Adam update on the given samples: target_pos[k] in [1, observed) is the replay position
+ * (0 = oldest) of sample k's target interval.  INVAL for a position out of range. */
+int plora_predictor_train_batch(plora_predictor* predictor, const int32_t* target_pos, int32_t n_samples,
+                                float* mean_loss_out);
+
+/* Inspection: number of parameters; copy them out / in (param_count floats). */
+int64_t plora_predictor_param_count(const plora_predictor* predictor);
+int plora_predictor_get_params(const plora_predictor* predictor, float* out);
+int plora_predictor_set_params(plora_predictor* predictor, const float* in);
+
+/* Loss (Eq. 2) and its gradient for one explicit sample: seq[window][n_adapters] feature vectors,
+ * oldest first; target[n_adapters] of 0 / 1.  loss_out / grad_out (param_count floats) may be NULL.
+ * Leaves parameters and Adam state alone. */
+int plora_predictor_loss_grad(plora_predictor* predictor, const float* seq, const float* target, float* loss_out,
+                              float* grad_out);
+
 /* The last hipError_t seen by a call that returned PLORA_ERR_HIP (0 if none). */
 int plora_last_hip(void);
 

@@ -15,7 +15,11 @@ __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS",
            "plora_pool_create", "plora_pool_destroy", "plora_adapter_bytes", "plora_load_adapter",
            "plora_adapter_ready", "plora_wait_adapter", "plora_evict", "plora_batch_begin", "plora_batch_info",
            "plora_shrink", "plora_expand", "plora_batch_end", "plora_pool_stats", "plora_pool_set_option",
-           "plora_profile", "plora_profile_read", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH"]
+           "plora_profile", "plora_profile_read", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH",
+           "plora_predictor_create", "plora_predictor_destroy", "plora_predictor_observe", "plora_predictor_observed",
+           "plora_predictor_predict", "plora_predictor_train", "plora_predictor_train_batch",
+           "plora_predictor_param_count", "plora_predictor_get_params", "plora_predictor_set_params",
+           "plora_predictor_loss_grad", "LstmPredictor"]
 
 PLORA_OK, PLORA_ERR_INVAL, PLORA_ERR_NOMEM, PLORA_ERR_EXISTS = 0, -1, -2, -3
 PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP = -4, -5, -6
@@ -62,6 +66,28 @@ lib.plora_profile.argtypes = [_vp, C.c_int]
 lib.plora_profile_read.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
 lib.plora_last_hip.argtypes = []
 lib.plora_version.argtypes = []
+
+
+class _PredictorConfig(C.Structure):
+    _fields_ = [("n_adapters", C.c_int32), ("window", C.c_int32), ("hidden", C.c_int32), ("layers", C.c_int32),
+                ("replay", C.c_int32), ("batch", C.c_int32), ("lr", C.c_float), ("beta1", C.c_float),
+                ("beta2", C.c_float), ("eps", C.c_float), ("seed", C.c_uint64)]
+
+
+_fp = C.POINTER(C.c_float)
+lib.plora_predictor_create.argtypes = [C.POINTER(_PredictorConfig), C.POINTER(_vp)]
+lib.plora_predictor_destroy.argtypes = [_vp]
+lib.plora_predictor_observe.argtypes = [_vp, _vp, _i32]
+lib.plora_predictor_observed.argtypes = [_vp]
+lib.plora_predictor_observed.restype = C.c_int64
+lib.plora_predictor_predict.argtypes = [_vp, _vp]
+lib.plora_predictor_train.argtypes = [_vp, _i32, _fp]
+lib.plora_predictor_train_batch.argtypes = [_vp, _vp, _i32, _fp]
+lib.plora_predictor_param_count.argtypes = [_vp]
+lib.plora_predictor_param_count.restype = C.c_int64
+lib.plora_predictor_get_params.argtypes = [_vp, _vp]
+lib.plora_predictor_set_params.argtypes = [_vp, _vp]
+lib.plora_predictor_loss_grad.argtypes = [_vp, _vp, _vp, _fp, _vp]
 
 
 def _ptr_array(ptrs):
@@ -263,3 +289,99 @@ class PagedLoraPool:
 
     def set_option(self, key, value):
         _check("plora_pool_set_option", plora_pool_set_option(self.h, key, value))
+
+
+# ---------------------------------------------------------------------------------------------
+# traffic predictor (host only)
+# ---------------------------------------------------------------------------------------------
+def plora_predictor_create(n_adapters, window=8, hidden=64, layers=2, replay=10000, batch=64, lr=1e-3, beta1=0.9,
+                           beta2=0.999, eps=1e-8, seed=0):
+    cfg = _PredictorConfig(n_adapters, window, hidden, layers, replay, batch, lr, beta1, beta2, eps, seed)
+    out = C.c_void_p()
+    rc = lib.plora_predictor_create(C.byref(cfg), C.byref(out))
+    return rc, out.value
+
+
+def plora_predictor_destroy(pred):
+    return lib.plora_predictor_destroy(pred)
+
+
+def plora_predictor_observe(pred, ids):
+    a = np.ascontiguousarray(ids, dtype=np.int32)
+    return lib.plora_predictor_observe(pred, a.ctypes.data, len(a))
+
+
+def plora_predictor_observed(pred):
+    return lib.plora_predictor_observed(pred)
+
+
+def plora_predictor_predict(pred, n_adapters):
+    out = np.empty(n_adapters, np.float32)
+    rc = lib.plora_predictor_predict(pred, out.ctypes.data)
+    return rc, out
+
+
+def plora_predictor_train(pred, steps):
+    loss = C.c_float()
+    rc = lib.plora_predictor_train(pred, steps, C.byref(loss))
+    return rc, loss.value
+
+
+def plora_predictor_train_batch(pred, target_pos):
+    a = np.ascontiguousarray(target_pos, dtype=np.int32)
+    loss = C.c_float()
+    rc = lib.plora_predictor_train_batch(pred, a.ctypes.data, len(a), C.byref(loss))
+    return rc, loss.value
+
+
+def plora_predictor_param_count(pred):
+    return lib.plora_predictor_param_count(pred)
+
+
+def plora_predictor_get_params(pred):
+    out = np.empty(lib.plora_predictor_param_count(pred), np.float32)
+    rc = lib.plora_predictor_get_params(pred, out.ctypes.data)
+    return rc, out
+
+
+def plora_predictor_set_params(pred, params):
+    a = np.ascontiguousarray(params, dtype=np.float32)
+    if a.size != lib.plora_predictor_param_count(pred):
+        return PLORA_ERR_INVAL
+    return lib.plora_predictor_set_params(pred, a.ctypes.data)
+
+
+def plora_predictor_loss_grad(pred, seq, target, want_grad=True):
+    s = np.ascontiguousarray(seq, dtype=np.float32)
+    t = np.ascontiguousarray(target, dtype=np.float32)
+    loss = C.c_float()
+    grad = np.empty(lib.plora_predictor_param_count(pred), np.float32) if want_grad else None
+    rc = lib.plora_predictor_loss_grad(pred, s.ctypes.data, t.ctypes.data, C.byref(loss), None if grad is None else grad.ctypes.data)
+    return rc, loss.value, grad
+
+
+class LstmPredictor:
+    """The library's predictor behind the interface the prefetch manager expects: predict(ids of the
+    coming interval) returns p_hat computed from the intervals seen so far, and only then records the
+    coming interval's requests (they become history once the interval is over) and trains."""
+
+    def __init__(self, n_adapters, window=8, hidden=64, layers=2, replay=10000, batch=64, lr=1e-3, seed=0,
+                 train_steps=1):
+        self.n, self.train_steps = int(n_adapters), int(train_steps)
+        rc, self.h = plora_predictor_create(n_adapters, window, hidden, layers, replay, batch, lr, seed=seed)
+        _check("plora_predictor_create", rc)
+        self.last_loss = None
+
+    def predict(self, next_interval_ids):
+        rc, p_hat = plora_predictor_predict(self.h, self.n)
+        _check("plora_predictor_predict", rc)
+        _check("plora_predictor_observe", plora_predictor_observe(self.h, next_interval_ids))
+        if self.train_steps:
+            rc, self.last_loss = plora_predictor_train(self.h, self.train_steps)
+            _check("plora_predictor_train", rc)
+        return p_hat
+
+    def close(self):
+        if self.h:
+            plora_predictor_destroy(self.h)
+            self.h = None

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libplora.so")
-SOURCES = ["plora_pool.cpp", "plora_kernels.hip"]
+SOURCES = ["plora_pool.cpp", "plora_predictor.cpp", "plora_kernels.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
