@@ -255,6 +255,11 @@ int plora_predictor_train(plora_predictor* predictor, int32_t steps, float* mean
 int plora_predictor_train_batch(plora_predictor* predictor, const int32_t* target_pos, int32_t n_samples,
                                 float* mean_loss_out);
 
+/* Worker threads of plora_predictor_train / _train_batch (1 .. 64, default 1): the samples of a
+ * minibatch are dealt to the workers in turn and their gradients added in worker order, so results are
+ * reproducible for a given thread count (and differ between counts only by fp32 summation order). */
+int plora_predictor_set_threads(plora_predictor* predictor, int32_t threads);
+
 /* Inspection: number of parameters; copy them out / in (param_count floats). */
 int64_t plora_predictor_param_count(const plora_predictor* predictor);
 int plora_predictor_get_params(const plora_predictor* predictor, float* out);

@@ -19,7 +19,7 @@ __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS",
            "plora_predictor_create", "plora_predictor_destroy", "plora_predictor_observe", "plora_predictor_observed",
            "plora_predictor_predict", "plora_predictor_train", "plora_predictor_train_batch",
            "plora_predictor_param_count", "plora_predictor_get_params", "plora_predictor_set_params",
-           "plora_predictor_loss_grad", "LstmPredictor"]
+           "plora_predictor_loss_grad", "plora_predictor_set_threads", "LstmPredictor"]
 
 PLORA_OK, PLORA_ERR_INVAL, PLORA_ERR_NOMEM, PLORA_ERR_EXISTS = 0, -1, -2, -3
 PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP = -4, -5, -6
@@ -88,6 +88,7 @@ lib.plora_predictor_param_count.restype = C.c_int64
 lib.plora_predictor_get_params.argtypes = [_vp, _vp]
 lib.plora_predictor_set_params.argtypes = [_vp, _vp]
 lib.plora_predictor_loss_grad.argtypes = [_vp, _vp, _vp, _fp, _vp]
+lib.plora_predictor_set_threads.argtypes = [_vp, _i32]
 
 
 def _ptr_array(ptrs):
@@ -334,6 +335,10 @@ def plora_predictor_train_batch(pred, target_pos):
     return rc, loss.value
 
 
+def plora_predictor_set_threads(pred, threads):
+    return lib.plora_predictor_set_threads(pred, threads)
+
+
 def plora_predictor_param_count(pred):
     return lib.plora_predictor_param_count(pred)
 
@@ -366,10 +371,11 @@ class LstmPredictor:
     coming interval's requests (they become history once the interval is over) and trains."""
 
     def __init__(self, n_adapters, window=8, hidden=64, layers=2, replay=10000, batch=64, lr=1e-3, seed=0,
-                 train_steps=1):
+                 train_steps=1, threads=1):
         self.n, self.train_steps = int(n_adapters), int(train_steps)
         rc, self.h = plora_predictor_create(n_adapters, window, hidden, layers, replay, batch, lr, seed=seed)
         _check("plora_predictor_create", rc)
+        _check("plora_predictor_set_threads", plora_predictor_set_threads(self.h, threads))
         self.last_loss = None
 
     def predict(self, next_interval_ids):

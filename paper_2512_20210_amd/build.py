@@ -16,6 +16,8 @@ def build(verbose=False):
     for src in SOURCES:
         obj = os.path.join(CSRC, os.path.splitext(src)[0] + ".o")
         cmd = [HIPCC, "--offload-arch=gfx950"] + common
+        if src.endswith(".cpp"):
+            cmd += ["-fopenmp-simd"]  # honours the simd pragmas of the host code; no OpenMP runtime involved
         if src.endswith(".hip"):
             # no packed-fp32 instructions from the auto-vectoriser (device pass only)
             cmd += ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

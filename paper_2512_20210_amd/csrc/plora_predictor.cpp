@@ -14,6 +14,7 @@
 #include <cstring>
 #include <deque>
 #include <new>
+#include <thread>
 #include <vector>
 
 namespace {
@@ -35,19 +36,27 @@ inline uint64_t mix64(uint64_t x) {
 
 }  // namespace
 
+// Working state of one sample (one per worker thread): per step and layer the gate activations, cell
+// and hidden states of the forward pass, the backward pass's carries, and a gradient accumulator.
+struct Scratch {
+  std::vector<float> gi, gf, gg, go, cs, hs, tc;  // [W][L][H] each
+  std::vector<float> logits, dz, da, dh, dc, dh_up;
+  std::vector<float> g;                           // gradient of this worker's samples
+  double loss = 0.0;
+};
+
 struct plora_predictor {
   plora_predictor_config cfg;
   int n = 0, H = 0, L = 0, W = 0;
-  std::vector<float> p, g, m, v;  // parameters, gradient, Adam moments
+  std::vector<float> p, m, v;  // parameters, Adam moments
   struct Off { size_t w_in, w_hh, b; };
   std::vector<Off> off;
   size_t w_fc = 0, b_fc = 0;
   int64_t adam_t = 0;
   uint64_t draws = 0;               // minibatch samples drawn so far (counter of the generator)
   std::deque<Sparse> replay;        // the most recent intervals, oldest first
-  // scratch of one sample: per step and layer the gate activations, cell and hidden states
-  std::vector<float> gi, gf, gg, go, cs, hs, tc;  // [W][L][H] each
-  std::vector<float> logits, dz, da, dh, dc, dh_up;
+  int threads = 1;
+  std::vector<Scratch> scr;         // scr[0] also holds the summed gradient
 };
 
 namespace {
@@ -55,7 +64,7 @@ namespace {
 size_t idx(const plora_predictor* q, int t, int l) { return ((size_t)t * q->L + l) * q->H; }
 
 // Forward pass over the window `seq` (W entries, oldest first; a null entry is an all-zero interval).
-void forward(plora_predictor* q, const Sparse* const* seq) {
+void forward(const plora_predictor* q, Scratch& z, const Sparse* const* seq) {
   const int H = q->H, L = q->L, W = q->W, n = q->n;
   const float* P = q->p.data();
   std::vector<float> a(4 * H);
@@ -71,19 +80,21 @@ void forward(plora_predictor* q, const Sparse* const* seq) {
             for (int k = 0; k < 4 * H; ++k) a[k] += f * row[k];
           }
       } else {
-        const float* x = q->hs.data() + idx(q, t, l - 1);
+        const float* x = z.hs.data() + idx(q, t, l - 1);
         const float* w = P + q->off[l].w_in;
         for (int k = 0; k < 4 * H; ++k) {
           float s = 0.f;
+#pragma omp simd reduction(+ : s)
           for (int j = 0; j < H; ++j) s += w[(size_t)k * H + j] * x[j];
           a[k] += s;
         }
       }
       if (t > 0) {
-        const float* hp = q->hs.data() + idx(q, t - 1, l);
+        const float* hp = z.hs.data() + idx(q, t - 1, l);
         const float* w = P + q->off[l].w_hh;
         for (int k = 0; k < 4 * H; ++k) {
           float s = 0.f;
+#pragma omp simd reduction(+ : s)
           for (int j = 0; j < H; ++j) s += w[(size_t)k * H + j] * hp[j];
           a[k] += s;
         }
@@ -91,55 +102,56 @@ void forward(plora_predictor* q, const Sparse* const* seq) {
       const size_t o = idx(q, t, l);
       for (int j = 0; j < H; ++j) {
         const float i_ = sigmoidf(a[j]), f_ = sigmoidf(a[H + j]), g_ = std::tanh(a[2 * H + j]), o_ = sigmoidf(a[3 * H + j]);
-        const float cp = t > 0 ? q->cs[idx(q, t - 1, l) + j] : 0.f;
+        const float cp = t > 0 ? z.cs[idx(q, t - 1, l) + j] : 0.f;
         const float c = f_ * cp + i_ * g_;
         const float tch = std::tanh(c);
-        q->gi[o + j] = i_; q->gf[o + j] = f_; q->gg[o + j] = g_; q->go[o + j] = o_;
-        q->cs[o + j] = c; q->tc[o + j] = tch; q->hs[o + j] = o_ * tch;
+        z.gi[o + j] = i_; z.gf[o + j] = f_; z.gg[o + j] = g_; z.go[o + j] = o_;
+        z.cs[o + j] = c; z.tc[o + j] = tch; z.hs[o + j] = o_ * tch;
       }
     }
   }
-  const float* h = q->hs.data() + idx(q, W - 1, L - 1);
+  const float* h = z.hs.data() + idx(q, W - 1, L - 1);
   const float* w = P + q->w_fc;
   const float* b = P + q->b_fc;
   for (int i = 0; i < n; ++i) {
-    float s = b[i];
+    float s = 0.f;
+#pragma omp simd reduction(+ : s)
     for (int j = 0; j < H; ++j) s += w[(size_t)i * H + j] * h[j];
-    q->logits[i] = s;
+    z.logits[i] = s + b[i];
   }
 }
 
 // Eq. 2 on the logits of the last forward pass; target: ascending ids of the adapters accessed.
-float loss_of(const plora_predictor* q, const Sparse* target) {
+float loss_of(const plora_predictor* q, const Scratch& z, const Sparse* target) {
   double s = 0.0;
   size_t e = 0;
   for (int i = 0; i < q->n; ++i) {
-    const float z = q->logits[i];
+    const float zi = z.logits[i];
     const bool y = target && e < target->id.size() && target->id[e] == i;
     if (y) ++e;
-    s += std::max(z, 0.f) + std::log1p(std::exp(-std::fabs(z))) - (y ? z : 0.f);
+    s += std::max(zi, 0.f) + std::log1p(std::exp(-std::fabs(zi))) - (y ? zi : 0.f);
   }
   return (float)s;
 }
 
-// Backward pass of the last forward pass: adds scale * dLoss/dparams to q->g.
-void backward(plora_predictor* q, const Sparse* const* seq, const Sparse* target, float scale) {
+// Backward pass of the last forward pass in z: adds scale * dLoss/dparams to z.g.
+void backward(const plora_predictor* q, Scratch& z, const Sparse* const* seq, const Sparse* target, float scale) {
   const int H = q->H, L = q->L, W = q->W, n = q->n;
   const float* P = q->p.data();
-  float* G = q->g.data();
+  float* G = z.g.data();
   size_t e = 0;
   for (int i = 0; i < n; ++i) {
     const bool y = target && e < target->id.size() && target->id[e] == i;
     if (y) ++e;
-    q->dz[i] = scale * (sigmoidf(q->logits[i]) - (y ? 1.f : 0.f));
+    z.dz[i] = scale * (sigmoidf(z.logits[i]) - (y ? 1.f : 0.f));
   }
-  std::fill(q->dh.begin(), q->dh.end(), 0.f);  // [L][H]: from step t + 1
-  std::fill(q->dc.begin(), q->dc.end(), 0.f);
+  std::fill(z.dh.begin(), z.dh.end(), 0.f);  // [L][H]: from step t + 1
+  std::fill(z.dc.begin(), z.dc.end(), 0.f);
   {  // output layer
-    const float* h = q->hs.data() + idx(q, W - 1, L - 1);
-    float* dht = q->dh.data() + (size_t)(L - 1) * H;
+    const float* h = z.hs.data() + idx(q, W - 1, L - 1);
+    float* dht = z.dh.data() + (size_t)(L - 1) * H;
     for (int i = 0; i < n; ++i) {
-      const float d = q->dz[i];
+      const float d = z.dz[i];
       G[q->b_fc + i] += d;
       float* gw = G + q->w_fc + (size_t)i * H;
       const float* w = P + q->w_fc + (size_t)i * H;
@@ -147,17 +159,17 @@ void backward(plora_predictor* q, const Sparse* const* seq, const Sparse* target
     }
   }
   for (int t = W - 1; t >= 0; --t) {
-    std::fill(q->dh_up.begin(), q->dh_up.end(), 0.f);  // [L][H]: from the layer above at this step
+    std::fill(z.dh_up.begin(), z.dh_up.end(), 0.f);  // [L][H]: from the layer above at this step
     for (int l = L - 1; l >= 0; --l) {
       const size_t o = idx(q, t, l);
-      float* dh = q->dh.data() + (size_t)l * H;
-      float* dc = q->dc.data() + (size_t)l * H;
-      const float* up = q->dh_up.data() + (size_t)l * H;
-      float* da = q->da.data();
+      float* dh = z.dh.data() + (size_t)l * H;
+      float* dc = z.dc.data() + (size_t)l * H;
+      const float* up = z.dh_up.data() + (size_t)l * H;
+      float* da = z.da.data();
       for (int j = 0; j < H; ++j) {
         const float dht = dh[j] + up[j];
-        const float i_ = q->gi[o + j], f_ = q->gf[o + j], g_ = q->gg[o + j], o_ = q->go[o + j], tch = q->tc[o + j];
-        const float cp = t > 0 ? q->cs[idx(q, t - 1, l) + j] : 0.f;
+        const float i_ = z.gi[o + j], f_ = z.gf[o + j], g_ = z.gg[o + j], o_ = z.go[o + j], tch = z.tc[o + j];
+        const float cp = t > 0 ? z.cs[idx(q, t - 1, l) + j] : 0.f;
         const float dct = dc[j] + dht * o_ * (1.f - tch * tch);
         da[j] = dct * g_ * i_ * (1.f - i_);
         da[H + j] = dct * cp * f_ * (1.f - f_);
@@ -170,7 +182,7 @@ void backward(plora_predictor* q, const Sparse* const* seq, const Sparse* target
       // recurrent weights and the gradient that flows to step t - 1
       std::fill(dh, dh + H, 0.f);
       if (t > 0) {
-        const float* hp = q->hs.data() + idx(q, t - 1, l);
+        const float* hp = z.hs.data() + idx(q, t - 1, l);
         const float* w = P + q->off[l].w_hh;
         float* gw = G + q->off[l].w_hh;
         for (int k = 0; k < 4 * H; ++k) {
@@ -187,10 +199,10 @@ void backward(plora_predictor* q, const Sparse* const* seq, const Sparse* target
             for (int k = 0; k < 4 * H; ++k) row[k] += f * da[k];
           }
       } else {
-        const float* x = q->hs.data() + idx(q, t, l - 1);
+        const float* x = z.hs.data() + idx(q, t, l - 1);
         const float* w = P + q->off[l].w_in;
         float* gw = G + q->off[l].w_in;
-        float* below = q->dh_up.data() + (size_t)(l - 1) * H;
+        float* below = z.dh_up.data() + (size_t)(l - 1) * H;
         for (int k = 0; k < 4 * H; ++k) {
           const float d = da[k];
           for (int j = 0; j < H; ++j) { gw[(size_t)k * H + j] += d * x[j]; below[j] += d * w[(size_t)k * H + j]; }
@@ -210,19 +222,50 @@ void window_before(const plora_predictor* q, size_t end, std::vector<const Spars
   }
 }
 
-void adam(plora_predictor* q) {
+// Runs fn(worker) on `workers` threads (the caller is worker 0) and waits for all of them.
+template <typename F>
+void run_workers(int workers, F fn) {
+  std::vector<std::thread> th;
+  for (int t = 1; t < workers; ++t) th.emplace_back(fn, t);
+  fn(0);
+  for (auto& x : th) x.join();
+}
+
+void alloc_scratch(const plora_predictor* q, Scratch& z) {
+  const size_t s = (size_t)q->W * q->L * q->H;
+  for (auto* vec : {&z.gi, &z.gf, &z.gg, &z.go, &z.cs, &z.hs, &z.tc}) vec->assign(s, 0.f);
+  z.logits.assign(q->n, 0.f); z.dz.assign(q->n, 0.f); z.da.assign(4 * (size_t)q->H, 0.f);
+  z.dh.assign((size_t)q->L * q->H, 0.f); z.dc.assign((size_t)q->L * q->H, 0.f); z.dh_up.assign((size_t)q->L * q->H, 0.f);
+  z.g.assign(q->p.size(), 0.f);
+}
+
+// Sums the workers' gradients (in worker order, so the result does not depend on timing), clears
+// them, and applies one Adam update; every thread takes one slice of the parameter vector.
+void reduce_and_adam(plora_predictor* q, int workers) {
   const float b1 = q->cfg.beta1, b2 = q->cfg.beta2, lr = q->cfg.lr, eps = q->cfg.eps;
   q->adam_t++;
   const double c1 = 1.0 - std::pow((double)b1, (double)q->adam_t), c2 = 1.0 - std::pow((double)b2, (double)q->adam_t);
   const float i1 = (float)(1.0 / c1), i2 = (float)(1.0 / c2);
   const size_t np = q->p.size();
-  for (size_t k = 0; k < np; ++k) {
-    const float gk = q->g[k];
-    const float mk = b1 * q->m[k] + (1.f - b1) * gk;
-    const float vk = b2 * q->v[k] + (1.f - b2) * gk * gk;
-    q->m[k] = mk; q->v[k] = vk;
-    q->p[k] -= lr * (mk * i1) / (std::sqrt(vk * i2) + eps);
-  }
+  run_workers(workers, [&](int t) {
+    const size_t lo = np * (size_t)t / workers, hi = np * (size_t)(t + 1) / workers;
+    float* g0 = q->scr[0].g.data();
+    for (int w = 1; w < workers; ++w) {
+      float* gw = q->scr[w].g.data();
+      for (size_t k = lo; k < hi; ++k) { g0[k] += gw[k]; gw[k] = 0.f; }
+    }
+    float* P = q->p.data();
+    float* M = q->m.data();
+    float* V = q->v.data();
+    for (size_t k = lo; k < hi; ++k) {
+      const float gk = g0[k];
+      const float mk = b1 * M[k] + (1.f - b1) * gk;
+      const float vk = b2 * V[k] + (1.f - b2) * gk * gk;
+      M[k] = mk; V[k] = vk;
+      P[k] -= lr * (mk * i1) / (std::sqrt(vk * i2) + eps);
+      g0[k] = 0.f;
+    }
+  });
 }
 
 }  // namespace
@@ -251,7 +294,7 @@ int plora_predictor_create(const plora_predictor_config* c, plora_predictor** ou
   }
   q->w_fc = o; o += n * H;
   q->b_fc = o; o += n;
-  q->p.assign(o, 0.f); q->g.assign(o, 0.f); q->m.assign(o, 0.f); q->v.assign(o, 0.f);
+  q->p.assign(o, 0.f); q->m.assign(o, 0.f); q->v.assign(o, 0.f);
   // uniform in (-1/sqrt(H), 1/sqrt(H)), the usual LSTM initialisation; biases start at 0
   const float a = 1.0f / std::sqrt((float)H);
   for (size_t k = 0; k < o; ++k) {
@@ -262,10 +305,8 @@ int plora_predictor_create(const plora_predictor_config* c, plora_predictor** ou
     const double u = (double)(mix64(c->seed ^ (0xA5A5ULL << 32) ^ k) >> 11) * (1.0 / 9007199254740992.0);
     q->p[k] = (float)((2.0 * u - 1.0) * a);
   }
-  const size_t s = (size_t)q->W * q->L * H;
-  for (auto* vec : {&q->gi, &q->gf, &q->gg, &q->go, &q->cs, &q->hs, &q->tc}) vec->assign(s, 0.f);
-  q->logits.assign(n, 0.f); q->dz.assign(n, 0.f); q->da.assign(4 * H, 0.f);
-  q->dh.assign((size_t)q->L * H, 0.f); q->dc.assign((size_t)q->L * H, 0.f); q->dh_up.assign((size_t)q->L * H, 0.f);
+  q->scr.resize(1);
+  alloc_scratch(q, q->scr[0]);
   *out = q;
   return PLORA_OK;
 }
@@ -302,8 +343,8 @@ int plora_predictor_predict(plora_predictor* q, float* p_hat) {
   if (!q || !p_hat) return PLORA_ERR_INVAL;
   std::vector<const Sparse*> seq;
   window_before(q, q->replay.size(), seq);
-  forward(q, seq.data());
-  for (int i = 0; i < q->n; ++i) p_hat[i] = sigmoidf(q->logits[i]);
+  forward(q, q->scr[0], seq.data());
+  for (int i = 0; i < q->n; ++i) p_hat[i] = sigmoidf(q->scr[0].logits[i]);
   return PLORA_OK;
 }
 
@@ -311,18 +352,24 @@ int plora_predictor_train_batch(plora_predictor* q, const int32_t* target_pos, i
   if (!q || !target_pos || n_samples < 1) return PLORA_ERR_INVAL;
   for (int32_t k = 0; k < n_samples; ++k)
     if (target_pos[k] < 1 || (size_t)target_pos[k] >= q->replay.size()) return PLORA_ERR_INVAL;
-  std::fill(q->g.begin(), q->g.end(), 0.f);
-  std::vector<const Sparse*> seq;
-  double total = 0.0;
+  // sample k goes to worker k % workers; every worker's gradient buffer is all zeros on entry
+  const int workers = std::max(1, std::min(q->threads, (int)n_samples));
   const float scale = 1.0f / (float)n_samples;
-  for (int32_t k = 0; k < n_samples; ++k) {
-    window_before(q, (size_t)target_pos[k], seq);
-    forward(q, seq.data());
-    const Sparse* y = &q->replay[(size_t)target_pos[k]];
-    total += loss_of(q, y);
-    backward(q, seq.data(), y, scale);
-  }
-  adam(q);
+  run_workers(workers, [&](int t) {
+    Scratch& z = q->scr[t];
+    z.loss = 0.0;
+    std::vector<const Sparse*> seq;
+    for (int32_t k = t; k < n_samples; k += workers) {
+      window_before(q, (size_t)target_pos[k], seq);
+      forward(q, z, seq.data());
+      const Sparse* y = &q->replay[(size_t)target_pos[k]];
+      z.loss += loss_of(q, z, y);
+      backward(q, z, seq.data(), y, scale);
+    }
+  });
+  double total = 0.0;
+  for (int t = 0; t < workers; ++t) total += q->scr[t].loss;
+  reduce_and_adam(q, workers);
   if (mean_loss) *mean_loss = (float)(total / n_samples);
   return PLORA_OK;
 }
@@ -341,6 +388,17 @@ int plora_predictor_train(plora_predictor* q, int32_t steps, float* mean_loss) {
     total += l;
   }
   if (mean_loss) *mean_loss = steps ? (float)(total / steps) : 0.f;
+  return PLORA_OK;
+}
+
+int plora_predictor_set_threads(plora_predictor* q, int32_t threads) {
+  if (!q || threads < 1 || threads > 64) return PLORA_ERR_INVAL;
+  const size_t old = q->scr.size();
+  if ((size_t)threads > old) {
+    q->scr.resize(threads);
+    for (size_t t = old; t < (size_t)threads; ++t) alloc_scratch(q, q->scr[t]);
+  }
+  q->threads = threads;
   return PLORA_OK;
 }
 
@@ -374,12 +432,13 @@ int plora_predictor_loss_grad(plora_predictor* q, const float* seq_dense, const 
     if (target[i] != 0.f && target[i] != 1.f) return PLORA_ERR_INVAL;
     if (target[i] == 1.f) y.id.push_back(i);
   }
-  forward(q, seq.data());
-  if (loss) *loss = loss_of(q, &y);
+  Scratch& z = q->scr[0];
+  forward(q, z, seq.data());
+  if (loss) *loss = loss_of(q, z, &y);
   if (grad) {
-    std::fill(q->g.begin(), q->g.end(), 0.f);
-    backward(q, seq.data(), &y, 1.0f);
-    std::memcpy(grad, q->g.data(), q->g.size() * sizeof(float));
+    backward(q, z, seq.data(), &y, 1.0f);  // the buffer is all zeros between calls
+    std::memcpy(grad, z.g.data(), z.g.size() * sizeof(float));
+    std::fill(z.g.begin(), z.g.end(), 0.f);
   }
   return PLORA_OK;
 }

@@ -17,6 +17,7 @@ int main() {
     plora_predictor_config c{s[0], s[1], s[2], s[3], 12, 5, 1e-3f, 0.9f, 0.999f, 1e-8f, 42};
     plora_predictor* q = nullptr;
     CHECK(plora_predictor_create(&c, &q) == PLORA_OK);
+    CHECK(plora_predictor_set_threads(q, 1 + s[0] % 4) == PLORA_OK);
     std::vector<float> p_hat(s[0]);
     for (int step = 0; step < 60; ++step) {
       std::vector<int32_t> ids(rng() % 9);

@@ -59,7 +59,7 @@ def test_predictor_under_asan_ubsan(tmp_path):
     cmd = ["g++", "-std=c++17", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
            "-fno-omit-frame-pointer", "-I" + os.path.join(ROOT, "include"),
            os.path.join(ROOT, "tests", "native", "predictor_sanitize.cpp"),
-           os.path.join(ROOT, "paper_2512_20210_amd", "csrc", "plora_predictor.cpp"), "-o", exe]
+           os.path.join(ROOT, "paper_2512_20210_amd", "csrc", "plora_predictor.cpp"), "-pthread", "-o", exe]
     r = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=300)
     assert r.returncode == 0, r.stdout[-3000:]
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=1:abort_on_error=0", UBSAN_OPTIONS="print_stacktrace=1")

@@ -104,6 +104,28 @@ def test_adam_updates_on_fixed_samples_follow_the_oracle():
         assert np.abs(got[big] - p[big]).max() <= 2e-4, (t, np.abs(got[big] - p[big]).max())
 
 
+def test_worker_threads_give_the_same_updates():
+    n = 30
+    rng = np.random.default_rng(4)
+    hist = [rng.integers(0, n, size=12).tolist() for _ in range(20)]
+    res = []
+    for threads in (1, 3, 8):
+        h = _make(n, 8, 2, 4, replay=50, batch=8, lr=1e-2)
+        assert P.plora_predictor_set_threads(h, threads) == P.PLORA_OK
+        for ids in hist:
+            P.plora_predictor_observe(h, ids)
+        rc, loss = P.plora_predictor_train(h, 6)
+        assert rc == P.PLORA_OK
+        res.append((loss, P.plora_predictor_get_params(h)[1]))
+        P.plora_predictor_destroy(h)
+    for loss, params in res[1:]:
+        assert abs(loss - res[0][0]) <= 1e-4 * res[0][0]
+        assert np.abs(params - res[0][1]).max() <= 5e-4      # same samples, another summation order
+    h = _make(n, 8, 2, 4)
+    assert P.plora_predictor_set_threads(h, 0) == P.PLORA_ERR_INVAL and P.plora_predictor_set_threads(h, 65) == P.PLORA_ERR_INVAL
+    P.plora_predictor_destroy(h)
+
+
 def test_replay_limit_sampler_and_errors():
     n = 5
     h = _make(n, 4, 1, 2, replay=4, batch=3)

@@ -10,7 +10,7 @@ RAW_DTYPE = {DT_F16: np.uint16, DT_BF16: np.uint16, DT_F32: np.float32}
 
 __all__ = ["DT_F16", "DT_BF16", "DT_F32", "ELT_BYTES", "RAW_DTYPE", "to_elt", "from_elt", "Layout",
            "make_adapter", "make_adapters", "slot_views", "zipf_probs", "draw_tok2adapter", "make_act",
-           "prefill_requests", "churn_trace", "draw_ranks"]
+           "prefill_requests", "churn_trace", "periodic_trace", "draw_ranks"]
 
 
 def to_elt(a, dtype):
@@ -150,4 +150,28 @@ def churn_trace(rng, n_events, population, s, window=100, burst_prob=0.1, burst_
         k = window * (burst_mult if rng.random() < burst_prob else 1)
         out.append(rng.choice(population, size=k, p=p).astype(np.int32))
         total += k
+    return out
+
+
+def periodic_trace(rng, n_windows, population, s, window=100, n_periodic=300, periods=(2, 3, 4, 6, 8, 12)):
+    """Adapter-request trace with a recurring part (the stand-in for the timer-driven functions of a
+    production serverless trace): n_periodic adapters (a seeded choice among all ids) each have a period
+    T (drawn from `periods`) and a phase and are requested once or twice in every window t with
+    (t + phase) % T == 0; the rest of each window of `window` requests is i.i.d. Zipf(s) background over
+    all adapters.  Returns a list of n_windows int32 arrays (requests of a window in random order)."""
+    ids = rng.permutation(population)[:n_periodic]
+    T = rng.choice(np.asarray(periods), size=n_periodic)
+    phase = rng.integers(0, 1 << 16, size=n_periodic) % T
+    twice = rng.random(n_periodic) < 0.25
+    p = zipf_probs(population, s)
+    out = []
+    for t in range(n_windows):
+        active = (t + phase) % T == 0
+        req = np.concatenate([ids[active], ids[active & twice]])
+        if len(req) > window:
+            req = req[:window]
+        back = rng.choice(population, size=window - len(req), p=p)
+        win = np.concatenate([req, back]).astype(np.int32)
+        rng.shuffle(win)
+        out.append(win)
     return out
