@@ -275,8 +275,9 @@ def churn_setup(name="cfg3", blobs_per_rank=8, pinned=None):
 
 
 def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
-    """One pass over the churn trace.  quality None: adapters are loaded on demand only; otherwise the
-    prefetch manager runs on a synthetic prediction of that quality before every window."""
+    """One pass over the churn trace.  quality None: adapters are loaded on demand only; a number: the
+    prefetch manager runs on a synthetic prediction of that quality before every window; "lstm": on the
+    library's predictor, which learns online from the windows it has seen."""
     import torch
     from paper_2512_20210_amd.prefetch import PrefetchManager, SyntheticPredictor
     from workload import zipf_probs
@@ -289,7 +290,15 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
     mgr = PrefetchManager(pm, ranks, scales, lambda i: pinned[(int(ranks[i]), i % k_blobs)],
                           p_hat=popularity / popularity.max(), copy_stream=copy_stream.cuda_stream,
                           prefetch_stream=prefetch_stream.cuda_stream)
-    pred = SyntheticPredictor(pop, popularity, quality, seed=cfg["seed"] + 11) if quality is not None else None
+    if quality == "lstm":
+        import paper_2512_20210_amd as P
+        pred = P.LstmPredictor(pop, window=cfg.get("lstm_window", 8), hidden=64, layers=2, replay=10000, batch=64,
+                               lr=cfg.get("lstm_lr", 1e-3), seed=cfg["seed"] + 13, train_steps=cfg.get("lstm_steps", 1),
+                               threads=min(16, os.cpu_count() or 1))
+    else:
+        pred = SyntheticPredictor(pop, popularity, quality, seed=cfg["seed"] + 11) if quality is not None else None
+    per_window = []       # (requests, cold starts, |predicted & requested|, |predicted|, |requested|) per window
+    pred_s = 0.0
     rng = np.random.default_rng(cfg["seed"] + 7)
     x = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_in]
     y = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_out]
@@ -311,8 +320,15 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for win in trace:
+        cold0, ev0 = mgr.cold_starts, events
+        hit_pred = n_pred = 0
         if pred is not None:  # between two decode batches: the copies run beside the next batch's kernels
-            mgr.begin_interval(pred.predict(win))
+            tp = time.perf_counter()
+            p_hat = pred.predict(win)
+            pred_s += time.perf_counter() - tp
+            flagged = set(np.nonzero(p_hat > mgr.theta)[0].tolist())
+            hit_pred, n_pred = len(flagged & set(int(a) for a in win)), len(flagged)
+            mgr.begin_interval(p_hat)
         for aid in win:
             aid = int(aid)
             if aid in mgr.prefetched:
@@ -335,6 +351,7 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
         pool.batch_end(b)
         kbytes += algorithmic_bytes(lay, ranks, t2a, slots)["total"]
         batches += 1
+        per_window.append((events - ev0, mgr.cold_starts - cold0, hit_pred, n_pred, len(set(int(a) for a in win))))
         if events >= cfg["n_events"]:
             break
     torch.cuda.synchronize()
@@ -362,6 +379,15 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
         "decode_kernel_ms_per_batch": round(sum(kms) / max(batches, 1), 4),
         "resident_adapters_end": st["resident_adapters"],
     }
+    # the last quarter of the windows on its own: an online predictor has had time to learn by then
+    tail = np.array(per_window[-max(1, len(per_window) // 4):], dtype=np.float64).sum(0)
+    out["last_quarter"] = {"cold_start_rate": round(tail[1] / max(tail[0], 1), 4),
+                           "prediction_recall": round(tail[2] / max(tail[4], 1), 4) if pred is not None else None,
+                           "prediction_precision": round(tail[2] / max(tail[3], 1), 4) if pred is not None else None}
+    if pred is not None:
+        out["predictor_ms_per_window"] = round(pred_s / max(len(per_window), 1) * 1e3, 3)
+    if quality == "lstm":
+        pred.close()
     return out
 
 
@@ -421,6 +447,23 @@ def run_load_study(args):
                       "adapter_bytes": lay.adapter_elems(big_rank) * 2, "adapters": n_big, "page_bytes": page_bytes, "rows": rows}))
 
 
+def run_churn_periodic(args):
+    """cfg3p: the churn workload with a recurring request pattern (timer-like adapters on top of a Zipf
+    background) and a pool that holds a third of the adapters in play: loads on demand, the library's
+    LSTM predictor learning online, and a synthetic prediction of quality 0.86 for comparison."""
+    from workload import periodic_trace
+    out = {"metric": "cold starts under a recurring request pattern: on demand vs LSTM-predicted prefetch",
+           "workload": "cfg3p", "passes": []}
+    pinned = None
+    for quality in (None, "lstm", 0.86):
+        cfg, lay, ranks, scales, pool, pinned, _ = churn_setup("cfg3p", pinned=pinned)
+        trace = periodic_trace(np.random.default_rng(cfg["seed"] + 1), cfg["n_events"] // cfg["window"], cfg["population"],
+                               cfg["zipf"], cfg["window"], cfg["n_periodic"], cfg["periods"])
+        out["passes"].append(_churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality))
+        pool.close()
+    print(json.dumps(out))
+
+
 def run_churn(args):
     """cfg3: load/evict churn interleaved with decode batches; utilisation, H2D and kernel rates, once
     with loads on demand only and once with threshold prefetching on a synthetic prediction."""
@@ -443,7 +486,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "load_study"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg3p", "cfg4", "cfg5", "load_study"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
     ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="plain token threshold of the matrix-core items in shrink (default: the library's work-based rule)")
     ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand")
@@ -470,6 +513,9 @@ def main():
     SEED_OFFSET = args.seed_offset
     if args.workload == "cfg3":
         run_churn(args)
+        return
+    if args.workload == "cfg3p":
+        run_churn_periodic(args)
         return
     if args.workload == "load_study":
         run_load_study(args)

@@ -7,8 +7,9 @@ kernels); room is made with the eviction score of Eq. 3, but never at the cost o
 is itself predicted (p_hat > theta).  p_hat also enters Eq. 3 for the on-demand evictions of the
 interval.
 
-The paper's predictor is an LSTM trained on a production trace; neither is available here, so
-`SyntheticPredictor` stands in for it: it looks at the true next interval and degrades that
+Two sources of p_hat: the library's LSTM predictor (`LstmPredictor` in the binding: Sec. III-A,
+learning online from the intervals it has seen), and `SyntheticPredictor`, which needs no learning
+and so serves traces without structure to learn: it looks at the true next interval and degrades that
 knowledge to a chosen quality q (the paper reports 86 % prediction accuracy; read here as q = 0.86):
 every adapter that will be requested is flagged with probability q, and for every one it misses a
 wrong adapter is flagged instead (drawn by popularity among those that will not be requested), so

@@ -32,6 +32,14 @@ CONFIGS = {
                  ranks=None, rank_choices=[4, 8, 16, 32, 64, 128], zipf=1.0, scale=None,
                  page_bytes=64 * KIB, n_pages=32768, max_rank=128, n_events=10000, window=100,
                  burst_prob=0.1, burst_mult=8),
+    # cfg3 with a recurring request pattern (300 timer-like adapters with periods of 2 .. 12 windows on a
+    # Zipf background) and a pool of a fifth of cfg3's size, so that long-period adapters are evicted
+    # between two of their windows; for the traffic predictor (Sec. III-A)
+    "cfg3p": dict(seed=BASE_SEED + 6, dtype=DT_BF16, slots=[(4096, 4096)] * 4, tokens=512, population=4096,
+                  ranks=None, rank_choices=[4, 8, 16, 32, 64, 128], zipf=1.0, scale=None,
+                  page_bytes=64 * KIB, n_pages=6400, max_rank=128, n_events=80000, window=100,
+                  burst_prob=0.0, burst_mult=1, n_periodic=300, periods=(2, 3, 4, 6, 8, 12),
+                  lstm_window=12, lstm_lr=3e-3, lstm_steps=4),
     # one Llama-13B-shaped layer: q,k,v,o 5120->5120, up 5120->13824, down 13824->5120, bf16,
     # 1024-token decode batch over 1000 resident adapters, ranks uniform in {16,...,128}, Zipf(0.8),
     # 128 KiB pages, pool sized to the whole adapter set
