@@ -10,8 +10,8 @@ and a request for a non-resident adapter starts a host->GPU copy on the copy str
 gives neither the weights nor the normalisation nor the direction; the reading used here: s_i is a
 retention value (the lowest score is evicted), LRU_i = 1 - (rank by last use) / (n - 1) with 1 for
 the most recently used, freq_i = hits in a sliding window of the last `window` requests divided by
-the largest such count among resident adapters, p_hat_i supplied by the caller (a synthetic
-predictor), alpha = 0.4, beta = 0.3, gamma = 0.3, ties go to the lowest id.  Adapters that cannot
+the largest such count among resident adapters, p_hat_i supplied by the caller (the LSTM predictor's
+forecast or a synthetic one), alpha = 0.4, beta = 0.3, gamma = 0.3, ties go to the lowest id.  Adapters that cannot
 be evicted right now (copy still in flight, or pinned by an open batch) are skipped.
 
 The manager is written against a minimal pool interface (load / evict / stats, raising an error
