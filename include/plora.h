@@ -174,7 +174,7 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * workgroup, instead of one mixed launch; defaults 0 / 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
  * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound
  * by its longest chain of dependent loads; it runs the cooperative kernels instead, in which the four
- * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 2500, 0 = never; take effect for
+ * wavefronts of a workgroup share one vector-ALU item; defaults 600 / 2500, 0 = never; take effect for
  * batches begun afterwards).  "batches_per_marker" (1..64, default 4: plora_batch_end puts one completion
  * event on the stream per this many batches instead of one per batch; the library records a pending
  * one itself whenever an eviction, a load or the reuse of a batch object has to order against it, so

@@ -210,11 +210,36 @@ __device__ __forceinline__ float dot2(uint32_t a, uint32_t b, float c) {
     return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, a), __builtin_bit_cast(f16x2_t, b), c, false);
 }
 
-__device__ __forceinline__ float wave_sum(float s) {
+// Sums each of a[0 .. N) over the 64 lanes of the wavefront and returns, in lane l, the total of
+// a[l >> (6 - log2 N)].  While more than one value is left, a lane keeps the half of them that its
+// lane bit M selects and hands the other half to its partner, so N values cost N - 1 + (6 - log2 N)
+// exchanges instead of 6 N, and the totals end up spread over the lanes (one store writes them all).
+// a[] is used as working space.
+template <int N, int M>
+__device__ __forceinline__ float wave_sums_step(float* a, int lane) {
+  if constexpr (N > 1) {
+    const bool up = (lane & M) != 0;
 #pragma unroll
-  for (int m = 32; m >= 1; m >>= 1) s += __shfl_xor(s, m, 64);
-  return s;
+    for (int j = 0; j < N / 2; ++j) {
+      const float keep = up ? a[j + N / 2] : a[j];
+      const float give = up ? a[j] : a[j + N / 2];
+      a[j] = keep + __shfl_xor(give, M, 64);
+    }
+    return wave_sums_step<N / 2, M / 2>(a, lane);
+  } else if constexpr (M >= 1) {
+    a[0] += __shfl_xor(a[0], M, 64);
+    return wave_sums_step<1, M / 2>(a, lane);
+  } else {
+    return a[0];
+  }
 }
+template <int N>
+__device__ __forceinline__ float wave_sums(float* a, int lane) {
+  static_assert(N == 4 || N == 8 || N == 16 || N == 32, "a power of two of values, at most one per two lanes");
+  return wave_sums_step<N, 32>(a, lane);
+}
+template <int N>
+constexpr int wave_sums_shift() { return N == 32 ? 1 : N == 16 ? 2 : N == 8 ? 3 : 4; }
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 
@@ -328,13 +353,12 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
     shrink_valu_chunk<DT, NT, ROWS, false, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
   if (full < d_in) shrink_valu_chunk<DT, NT, ROWS, true, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
 
-#pragma unroll
-  for (int jj = 0; jj < ROWS; ++jj)
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-      const float s = wave_sum(acc[jj][i]);
-      if (lane == 0 && jj < nrows && i < it.ntok) v[tok[i] * vs + it.j0 + jj] = s;
-    }
+  // lane 2^sh * (jj * NT + i) ends up with the total of acc[jj][i] and stores it
+  constexpr int sh = wave_sums_shift<ROWS * NT>();
+  const float total = wave_sums<ROWS * NT>(&acc[0][0], lane);
+  const int idx = lane >> sh, jj = idx / NT, i = idx % NT;
+  const int ti = i == 1 ? it.tok[1] : i == 2 ? it.tok[2] : i == 3 ? it.tok[3] : it.tok[0];
+  if ((lane & ((1 << sh) - 1)) == 0 && jj < nrows && i < it.ntok) v[(int64_t)ti * vs + it.j0 + jj] = total;
 }
 
 template <int DT>
@@ -1118,13 +1142,11 @@ __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const Item
     shrink_valu_chunk<DT, NT, kShrinkRows, false, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, k0, acc);
   if (full < d_in && ((full / CH) & 3) == wave)
     shrink_valu_chunk<DT, NT, kShrinkRows, true, NTW>(a, x, tok, lds_pt, win0, base, rowb, nrows, d_in, full, acc);
-#pragma unroll
-  for (int jj = 0; jj < kShrinkRows; ++jj)
-#pragma unroll
-    for (int i = 0; i < NT; ++i) {
-      const float sum = wave_sum(acc[jj][i]);
-      if (lane == 0) red[wave][jj * NT + i] = sum;
-    }
+  {
+    constexpr int sh = wave_sums_shift<kShrinkRows * NT>();
+    const float total = wave_sums<kShrinkRows * NT>(&acc[0][0], lane);
+    if ((lane & ((1 << sh) - 1)) == 0) red[wave][lane >> sh] = total;
+  }
   __syncthreads();
   if (wave == 0 && lane < kShrinkRows * NT) {
     const int jj = lane / NT, i = lane % NT;

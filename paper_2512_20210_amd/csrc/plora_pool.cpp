@@ -139,7 +139,7 @@ struct plora_pool {
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
                          // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
-  int64_t coop_max_workgroups[2] = {192, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
+  int64_t coop_max_workgroups[2] = {600, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
                                                  // most this many workgroups use the cooperative kernels (0 = never)
   int slot_major[2] = {-1, 2}; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always;
                                // 2 (expand): the 512-column chunks are the fastest dimension
