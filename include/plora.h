@@ -184,6 +184,10 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * many such blocks (prefill); other batches (decode: a hot adapter or two) cut them into items of 16
  * tokens for the ordinary kernel instead (0 = always).  "mfma_cols_max_group" (default 32): in a
  * batch of the first kind, a group's last <= this many tokens still go as 16-token items.
+ * "mfma_shrink_depth" (0, 1 or 2; default 0): runs of 64 values of the contraction that a matrix-core
+ * shrink item keeps in flight per wavefront; 0 lets the library choose per launch (2 when the batch's
+ * matrix-core token tiles are at least half full on average, as in prefill, or a slot of the launch has
+ * d_in > 4096; else 1).  Results do not depend on it.
  * "staging_bytes" (0 .. 2^36, default 0 = off) and "staging_min_runs" (>= 1, default 3: with two runs the direct copies are as fast): staged loads
  * (Sec. III-B: loaded adapters arrive in a staging area before they are moved into place).  With
  * staging on, plora_load_adapter sends a blob of at most staging_bytes whose pages form at least

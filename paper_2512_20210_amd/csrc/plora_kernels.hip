@@ -9,9 +9,11 @@
 //
 //   shrink, vector-ALU item : up to 8 rows of A x up to 4 tokens.  Lanes stride along d_in with
 //                             16-byte loads, accumulate in fp32 (packed dot products for 16-bit
-//                             elements) and finish with a wavefront reduction.
+//                             elements) and finish with one transposing wavefront reduction
+//                             of all their sums.
 //   shrink, matrix-core item: 32 rows of A x up to 32 tokens, v_mfma_f32_16x16x32 (bf16 / f16), by
-//                             4 wavefronts that split d_in; operands staged in LDS.
+//                             4 wavefronts that split d_in; operands staged in LDS, one or two
+//                             runs of 64 k-values in flight per wavefront (two kernels).
 //   expand, vector-ALU item : all rows of B x 64 lanes x 16 bytes of columns x up to 4 tokens;
 //                             no reduction, read-modify-write of y.
 //   expand, matrix-core item: all rows of B x 512 columns; up to 16 tokens: every wavefront its own
@@ -536,7 +538,7 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
 constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16 pad per LDS row
 static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
-template <int DT, bool NTW>
+template <int DT, bool NTW, int DEPTH>
 __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                   const uint8_t* __restrict__ x, float* __restrict__ v,
                                                   uint8_t (*tile)[2][kSmRows * kSmPitch], int32_t* lds_pt) {
@@ -592,10 +594,11 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
 
   uint8_t* tw = tile[wave][0];
   uint8_t* tx = tile[wave][1];
-  uint4 wq[4], xq[4];
-  auto fetch = [&](int run) {
+  // Loads of a run of 64 k-values into registers (always issued: callers clamp the run, so that the
+  // compiler can count the loads in flight), their way into LDS, and the products from there.
+  auto fetch = [&](int run, uint4 (&wq)[4], uint4 (&xq)[4]) -> bool {
     const int k = run * 64 + lp8 * 8;
-    const bool ok = k < d_in;
+    const bool ok = k < d_in;  // past a ragged end the lane reads k = 0 and stages zeros
     const uint64_t kb = (uint64_t)(ok ? k : 0) * EB;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -604,20 +607,19 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
       wq[i] = ldw16<NTW>(a.slab + (pg << lp) + (vo & pmask));
       xq[i] = ld16(xrow[i] + kb);
     }
-    if (!ok) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) { wq[i] = make_uint4(0, 0, 0, 0); xq[i] = make_uint4(0, 0, 0, 0); }
-    }
+    return ok;
   };
-  if (mine > 0) fetch(SM_RUN(0));
-  for (int i = 0; i < mine; ++i) {
+  // (selects, not a branch around stores of zeros: a branch that touches registers with loads in
+  // flight makes the compiler wait for every load there, also the other run's)
+  auto keep_if = [](const uint4 q, bool ok) { return make_uint4(ok ? q.x : 0u, ok ? q.y : 0u, ok ? q.z : 0u, ok ? q.w : 0u); };
+  auto stage = [&](const uint4 (&wq)[4], const uint4 (&xq)[4], bool ok) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      *reinterpret_cast<uint4*>(tw + (lr + 8 * i) * kSmPitch + lp8 * 16) = wq[i];
-      *reinterpret_cast<uint4*>(tx + (lr + 8 * i) * kSmPitch + lp8 * 16) = xq[i];
+      *reinterpret_cast<uint4*>(tw + (lr + 8 * i) * kSmPitch + lp8 * 16) = keep_if(wq[i], ok);
+      *reinterpret_cast<uint4*>(tx + (lr + 8 * i) * kSmPitch + lp8 * 16) = keep_if(xq[i], ok);
     }
-    SM_SYNC();
-    if (i + 1 < mine) fetch(SM_RUN(i + 1));  // in flight while this run is multiplied
+  };
+  auto multiply = [&]() {
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
       uint4 wo[2], xo[2];
@@ -631,7 +633,63 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
 #pragma unroll
         for (int nt = 0; nt < 2; ++nt) acc[mt][nt] = mfma16<DT>(xo[mt], wo[nt], acc[mt][nt]);
     }
-    SM_SYNC();
+  };
+  if constexpr (DEPTH == 2) {
+    // two runs in flight: while one is multiplied, the next two are on their way
+    uint4 wq0[4], xq0[4], wq1[4], xq1[4];
+    bool ok0 = false, ok1 = false;
+    if (mine > 0) {
+      ok0 = fetch(SM_RUN(0), wq0, xq0);
+      __builtin_amdgcn_sched_barrier(0);  // first run's loads first: its wait then leaves the second run's in flight
+      ok1 = fetch(SM_RUN(imin(1, mine - 1)), wq1, xq1);  // (unconditional, so that the loop sees one state of loads in flight)
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    int i = 0;
+    for (; i + 3 < mine; i += 2) {  // whole pairs with two more runs to request: every trip leaves the same loads in flight
+      stage(wq0, xq0, ok0);
+      SM_SYNC();
+      ok0 = fetch(SM_RUN(i + 2), wq0, xq0);
+      multiply();
+      SM_SYNC();
+      __builtin_amdgcn_sched_barrier(0);  // keeps the other pair's work (and with it its wait) below this point
+      stage(wq1, xq1, ok1);
+      SM_SYNC();
+      ok1 = fetch(SM_RUN(i + 3), wq1, xq1);
+      multiply();
+      SM_SYNC();
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const int rem = mine - i;  // 0 (no run at all) .. 3 left, the first two of them requested
+    if (rem >= 1) {
+      stage(wq0, xq0, ok0);
+      SM_SYNC();
+      if (rem == 3) ok0 = fetch(SM_RUN(i + 2), wq0, xq0);
+      multiply();
+      SM_SYNC();
+    }
+    if (rem >= 2) {
+      stage(wq1, xq1, ok1);
+      SM_SYNC();
+      multiply();
+      SM_SYNC();
+    }
+    if (rem == 3) {
+      stage(wq0, xq0, ok0);
+      SM_SYNC();
+      multiply();
+      SM_SYNC();
+    }
+  } else {
+    uint4 wq[4], xq[4];
+    bool ok = false;
+    if (mine > 0) ok = fetch(SM_RUN(0), wq, xq);
+    for (int i = 0; i < mine; ++i) {
+      stage(wq, xq, ok);
+      SM_SYNC();
+      if (i + 1 < mine) ok = fetch(SM_RUN(i + 1), wq, xq);  // in flight while this run is multiplied
+      multiply();
+      SM_SYNC();
+    }
   }
 #if PLORA_SM_BARRIER
   // every wavefront passes 2 * per barriers: those with fewer runs (or none) catch up here
@@ -994,7 +1052,8 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
 // or up to 4 independent vector-ALU items, one per wavefront.  The matrix-core blocks come first in
 // the list, so their long dependent chains start first and the short items fill the machine around
 // and after them in the same launch.
-template <int DT>
+// DEPTH: runs of 64 k-values that a matrix-core item keeps in flight (1 or 2).
+template <int DT, int DEPTH>
 __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
   __shared__ __align__(16) uint8_t tile[4][2][kSmRows * kSmPitch];  // [wavefront][A | x]
   __shared__ int32_t lds_pt[kPtWindow];
@@ -1006,8 +1065,8 @@ __global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const La
   const ItemRec first = load_item(a.items + (4 * blk));
   if constexpr (DT != 2) {
     if (item_kind(first) == 1) {
-      if (item_once(first)) shrink_mfma4_body<DT, true>(a, first, sl, x, v, tile, lds_pt);
-      else shrink_mfma4_body<DT, false>(a, first, sl, x, v, tile, lds_pt);
+      if (item_once(first)) shrink_mfma4_body<DT, true, DEPTH>(a, first, sl, x, v, tile, lds_pt);
+      else shrink_mfma4_body<DT, false, DEPTH>(a, first, sl, x, v, tile, lds_pt);
       return;
     }
   }
@@ -1343,13 +1402,15 @@ static void launch(KernelFn k, dim3 grid, dim3 block, hipStream_t st, hipEvent_t
 
 hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int mode, hipStream_t st,
                          hipEvent_t e0, hipEvent_t e1) {
-  const bool single = mode != 0;  // one record per workgroup
+  const bool single = mode == 1 || mode == 2;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
   if (!single && a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
-  static const KernelFn table[3][3] = {{k_shrink<0>, k_shrink<1>, k_shrink<2>},
+  // mode 3: as mode 0 with two runs in flight per matrix-core item (fp32 has no such items)
+  static const KernelFn table[4][3] = {{k_shrink<0, 1>, k_shrink<1, 1>, k_shrink<2, 1>},
                                        {k_shrink_valu1<0>, k_shrink_valu1<1>, k_shrink_valu1<2>},
-                                       {k_shrink_coop<0>, k_shrink_coop<1>, k_shrink_coop<2>}};
-  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
+                                       {k_shrink_coop<0>, k_shrink_coop<1>, k_shrink_coop<2>},
+                                       {k_shrink<0, 2>, k_shrink<1, 2>, k_shrink<2, 1>}};
+  if (mode < 0 || mode > 3 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;

@@ -72,6 +72,7 @@ struct plora_batch {
   plora_pool* pool = nullptr;
   bool open = false;
   bool panel = false;  // expand: the matrix-core blocks go to the panel kernel
+  bool full_shrink_tiles = false;  // shrink: the matrix-core items average at least half a token tile
   hipStream_t stream = nullptr;
   int32_t n_tokens = 0, n_seg = 0, n_perm = 0;
   // host copies for plora_batch_info
@@ -139,6 +140,7 @@ struct plora_pool {
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
                          // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
+  int mfma_shrink_depth = 0;  // runs in flight per matrix-core shrink item: 1, 2, or 0 = by batch and slot shape
   int64_t coop_max_workgroups[2] = {600, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
                                                  // most this many workgroups use the cooperative kernels (0 = never)
   int slot_major[2] = {-1, 2}; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always;
@@ -585,6 +587,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->cols_max_group = (int)value;
     return PLORA_OK;
   }
+  if (k == "mfma_shrink_depth") {
+    if (value < 0 || value > 2) return PLORA_ERR_INVAL;
+    p->mfma_shrink_depth = (int)value;
+    return PLORA_OK;
+  }
   if (k == "batches_per_marker") {
     if (value < 1 || value > 64) return PLORA_ERR_INVAL;
     p->batches_per_marker = (int)value;
@@ -712,6 +719,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
   b->panel = p->panel_min_blocks > 0 && panel_blocks >= p->panel_min_blocks;
   const int32_t cols_max_group = b->panel ? p->cols_max_group : kTokBlock;
   size_t n_pt_total = 0;
+  int64_t mfma_shrink_items = 0, mfma_shrink_tokens = 0;
   for (int32_t u = 0; u < n_seg; ++u) {
     const Adapter& a = p->ad[touched[u]];
     const int32_t n = p->count[touched[u]];
@@ -735,6 +743,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
         for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
           for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokS) {
             const int16_t nt = (int16_t)std::min(kMfmaTokS, b1 - t0);
+            ++mfma_shrink_items;
+            mfma_shrink_tokens += nt;
             wl[0][1].items.push_back(ItemRec{kind, nt, rank, (int16_t)j0, a.scale, pt_off, {start + t0, 0, 0, 0}});
             cost += std::min(kMfmaRows, a.rank - j0) + nt;
           }
@@ -776,6 +786,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       }
     }
   }
+  b->full_shrink_tiles = mfma_shrink_items > 0 && 2 * mfma_shrink_tokens >= (int64_t)kMfmaTokS * mfma_shrink_items;
   // tokens without adapter: one rank-0 group of shrink items
   auto none_groups = [&](std::vector<ItemRec>& dst) {
     for (int32_t t0 = 0; t0 < n_none; t0 += kValuTok) {
@@ -959,8 +970,16 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     // one launch over the whole block list, or (longest-first list only) the matrix-core blocks in the
     // 256-thread kernel followed by the vector-ALU records one per single-wavefront workgroup
     const bool split = layout == 0 && (panel || (p->split[op] && n_all > b->n_heavy[op]));
+    // matrix-core shrink items keep two runs of k-values in flight where that pays: token tiles that
+    // are mostly full (prefill), or a long contraction
+    bool deep = false;
+    if (is_shrink && !coop && p->dtype != PLORA_F32 && b->n_heavy[0] > 0) {
+      int32_t max_in = 0;
+      for (int q = 0; q < nq; ++q) max_in = std::max(max_in, p->slots[ptrs.slot[q]].d_in);
+      deep = p->mfma_shrink_depth == 2 || (p->mfma_shrink_depth == 0 && (b->full_shrink_tiles || max_in > 4096));
+    }
     struct Part { const ItemRec* items; int n; int mode; };
-    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, panel ? 3 : coop ? 2 : 0},
+    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, panel ? 3 : coop ? 2 : deep ? 3 : 0},
                            {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, (panel && !p->split[op]) ? 0 : 1}};
     plora_pool::ProfRec rec{op, nullptr, nullptr};
     if (p->profiling) {

@@ -88,12 +88,14 @@ class Case:
         xs = [make_act(rng, T, lay.d_in[s], lay.dtype, x_std) for s in slots]
         y0 = [np.zeros((T, lay.d_out[s]), RAW_DTYPE[lay.dtype]) if y0_zero else make_act(rng, T, lay.d_out[s], lay.dtype)
               for s in slots]
-        # GPU side: with the cooperative kernels of small calls, with the panel kernel for every large
-        # group (as in a prefill batch), and with the library's own choice last (its outputs are returned)
-        for coop, panel in getattr(self, "kernel_modes", ((1 << 30, 8), (0, 1), (0, 8))):
+        # GPU side: with the cooperative kernels of small calls; with the panel kernel for every large
+        # group (as in a prefill batch) and two runs in flight in every matrix-core shrink item; and
+        # with the library's own choices last (its outputs are returned).  Each entry: (cooperative limit, panel_min_blocks, mfma_shrink_depth).
+        for coop, panel, depth in getattr(self, "kernel_modes", ((1 << 30, 8, 1), (0, 1, 2), (0, 8, 0))):
             self.gpool.set_option("coop_max_workgroups_shrink", coop)
             self.gpool.set_option("coop_max_workgroups_expand", coop)
             self.gpool.set_option("panel_min_blocks", panel)
+            self.gpool.set_option("mfma_shrink_depth", depth)
             out = self._run_gpu(t2a, slots, xs, y0, check)
         return out
 

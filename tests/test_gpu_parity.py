@@ -173,6 +173,28 @@ def test_slots_of_two_widths_in_one_call(oracle_mod):
     case.close()
 
 
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F16])
+def test_matrix_core_shrink_with_one_and_two_runs_in_flight(oracle_mod, dtype):
+    """Contractions of 1 .. 67 runs of 64 values (so the four wavefronts of an item get 0, 1, 2, 3,
+    even and odd numbers of runs), ragged last runs, full and ragged token tiles: both depths against
+    the oracle, and against each other bit for bit (the order of the sums is the same)."""
+    d_ins = (64, 72, 128, 192, 200, 448, 456, 640, 1000, 4096, 4288)
+    lay = Layout(d_ins, (64,) * len(d_ins), dtype)
+    ranks = [8, 24, 32, 64, 40]
+    case = Case(oracle_mod, lay, ranks, [1.0] * len(ranks), 4096, 4096, seed=77)
+    case.set_mfma(1)
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in ((0, 1), (1, 32), (2, 33), (3, 70), (4, 5))])
+    np.random.default_rng(78).shuffle(t2a)
+    got = {}
+    for depth in (1, 2):
+        case.kernel_modes = ((0, 8, depth),)
+        out = case.run(t2a, seed=3)
+        got[depth] = [o["v_got"].copy() for o in out]
+    for a, b in zip(got[1], got[2]):
+        assert (a.view(np.uint32) == b.view(np.uint32)).all()
+    case.close()
+
+
 @pytest.mark.parametrize("dtype", [DT_BF16, DT_F32])
 def test_maximum_rank(oracle_mod, dtype):
     """Ranks up to the library's limit of 512 (the expand stages one page pair per row of B), with
