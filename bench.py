@@ -56,10 +56,16 @@ def draw_batch(cfg, rng, n_adapters):
     return draw_tok2adapter(rng, cfg["tokens"], np.arange(n_adapters), cfg["zipf"])
 
 
-def algorithmic_bytes(lay, ranks, t2a, slots):
+def shares_x_with_earlier_slot(lay, s):
+    """--share-qkv-x: slots come in groups of four (q, k, v, o of a layer); k and v read q's x."""
+    return s % 4 in (1, 2) and lay.d_in[s] == lay.d_in[s - s % 4]
+
+
+def algorithmic_bytes(lay, ranks, t2a, slots, share_qkv_x=False):
     """Bytes the method itself must move for one batch over `slots` (each needed weight byte once per
-    batch, x read once, y read + written once, v written + read once, page-table entries and the
-    token permutation once per slot).  Returns per-slot-summed dicts for shrink and expand."""
+    batch, x read once (once per q, k, v group with share_qkv_x), y read + written once, v written +
+    read once, page-table entries and the token permutation once per slot).  Returns per-slot-summed
+    dicts for shrink and expand."""
     elt = lay.elt
     has = t2a >= 0
     Tn = int(has.sum())
@@ -71,7 +77,8 @@ def algorithmic_bytes(lay, ranks, t2a, slots):
     for s in slots:
         di, do = lay.d_in[s], lay.d_out[s]
         meta = 4 * Tn
-        shrink += sum_r_u * di * elt + Tn * di * elt + sum_r_t * 4 + meta
+        x_bytes = 0 if share_qkv_x and shares_x_with_earlier_slot(lay, s) else Tn * di * elt
+        shrink += sum_r_u * di * elt + x_bytes + sum_r_t * 4 + meta
         expand += sum_r_u * do * elt + 2 * Tn * do * elt + sum_r_t * 4 + meta
         flops += 2 * sum_r_t * (di + do)
     return dict(shrink=shrink, expand=expand, total=shrink + expand, flops=flops, n_unique=len(uniq), tokens=Tn)
@@ -128,14 +135,16 @@ class GpuWorkload:
                       st["h2d_bytes"] / 1e9 / self.t_load, st["h2d_copies"],
                       st["h2d_bytes"] / 1e6 / max(st["h2d_ms"], 1e-9)), file=sys.stderr, flush=True)
 
-    def alloc_activations(self, T, seed, zero_y=False, min_bytes=0):
-        """x ~ N(0,1), y0 ~ N(0,1) per slot on the device (raw element tensors), v buffers.  With
+    def alloc_activations(self, T, seed, zero_y=False, min_bytes=0, share_qkv_x=False):
+        """x ~ N(0,1), y0 ~ N(0,1) per slot on the device (raw element tensors), v buffers; with
+        share_qkv_x the k and v slots of a layer use the q slot's x buffer.  With
         min_bytes > 0 the whole set is replicated until it exceeds that many bytes and step() rotates
         through the replicas, so that activations cannot stay in the 256 MB last-level cache from
         one step to the next."""
         torch, lay = self.torch, self.lay
         rng = np.random.default_rng(seed)
         self.T = T
+        self.share_qkv_x = share_qkv_x
         self.x, self.y, self.v = [], [], []
         # one draw per distinct width, re-used with a per-slot roll so that slots differ
         base = {}
@@ -147,20 +156,29 @@ class GpuWorkload:
         for s in range(lay.n_slots):
             xs = np.roll(base[lay.d_in[s]], s, axis=0)
             ys = np.roll(base[lay.d_out[s]], -s - 1, axis=0)
-            self.x.append(torch.from_numpy(np.ascontiguousarray(xs).view(np.int16) if lay.elt == 2 else xs).to("cuda"))
+            if share_qkv_x and shares_x_with_earlier_slot(lay, s):
+                self.x.append(self.x[s - s % 4])
+            else:
+                self.x.append(torch.from_numpy(np.ascontiguousarray(xs).view(np.int16) if lay.elt == 2 else xs).to("cuda"))
             y = torch.from_numpy(np.ascontiguousarray(ys).view(np.int16) if lay.elt == 2 else ys).to("cuda")
             if zero_y:
                 y.zero_()
             self.y.append(y)
             self.v.append(torch.empty((T, self.max_rank), dtype=torch.float32, device="cuda"))
-        one = sum(t.numel() * t.element_size() for t in self.x + self.y + self.v)
+        one = sum(t.numel() * t.element_size() for t in {id(t): t for t in self.x + self.y + self.v}.values())
         self.act_sets = [(self.x, self.y, self.v)]
         while one * len(self.act_sets) < min_bytes:
-            self.act_sets.append(([t.clone() for t in self.x], [t.clone() for t in self.y], [t.clone() for t in self.v]))
+            copies = {}
+            for t in self.x:  # a shared buffer stays shared in the replica
+                if id(t) not in copies:
+                    copies[id(t)] = t.clone()
+            self.act_sets.append(([copies[id(t)] for t in self.x], [t.clone() for t in self.y], [t.clone() for t in self.v]))
         self.act_bytes, self.step_no = one, 0
         torch.cuda.synchronize()
 
     def host_x(self, s):
+        if self.share_qkv_x and shares_x_with_earlier_slot(self.lay, s):
+            s -= s % 4
         return np.roll(self.x_host_base[self.lay.d_in[s]], s, axis=0)
 
     def host_y0(self, s):
@@ -202,7 +220,7 @@ def cpu_baseline(w, t2a, budget_s=15.0):
         v = op.shrink(s, x, t2a, threads=threads)
         op.expand(s, v, t2a, y, threads=threads)
         t_total += time.perf_counter() - t0
-        bytes_total += algorithmic_bytes(lay, w.ranks, t2a, [s])["total"]
+        bytes_total += algorithmic_bytes(lay, w.ranks, t2a, [s], w.share_qkv_x)["total"]
         done += 1
         if t_total > budget_s or (done >= 2 and t_total / done * (done + 1) > budget_s * 1.5):
             break
@@ -214,7 +232,7 @@ def cpu_baseline(w, t2a, budget_s=15.0):
         v = op.shrink(s, x, t2a, threads=1)
         op.expand(s, v, t2a, y, threads=1)
         t1 += time.perf_counter() - t0
-        b1 += algorithmic_bytes(lay, w.ranks, t2a, [s])["total"]
+        b1 += algorithmic_bytes(lay, w.ranks, t2a, [s], w.share_qkv_x)["total"]
         n1 += 1
     op.close()
     per_slot = t_total / done
@@ -496,6 +514,7 @@ def main():
                          "shrink, 400 for expand; 0 = never)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
+    ap.add_argument("--share-qkv-x", action="store_true", help="k and v slots of a layer read the q slot's x buffer (as in a transformer layer); x is then counted once per group")
     ap.add_argument("--same-batch", action="store_true", help="reuse one token->adapter draw for every step")
     ap.add_argument("--scatter", action="store_true", help="evict and reload adapters so that their pages are scattered")
     ap.add_argument("--seed-offset", type=int, default=0, help="added to the workload's seed: another draw of ranks, weights and batches")
@@ -538,7 +557,7 @@ def main():
     n_draws = 1 if args.same_batch else args.steps + args.warmup
     batches = [draw_batch(cfg, rng, w.n_ad) for _ in range(n_draws)]
     T = max(len(b) for b in batches)
-    w.alloc_activations(T, cfg["seed"] + 9, min_bytes=768 << 20)
+    w.alloc_activations(T, cfg["seed"] + 9, min_bytes=768 << 20, share_qkv_x=args.share_qkv_x)
     spc = args.slots_per_call or lay.n_slots
     all_slots = list(range(lay.n_slots))
 
@@ -559,7 +578,7 @@ def main():
         w.pool.profile(False)
         kms, kn = w.pool.profile_read()
 
-    ab = [algorithmic_bytes(lay, w.ranks, t2a, all_slots) for t2a in timed]
+    ab = [algorithmic_bytes(lay, w.ranks, t2a, all_slots, args.share_qkv_x) for t2a in timed]
     bytes_total = sum(a["total"] for a in ab)
     tokens_total = sum(len(t2a) for t2a in timed)
     gbs = bytes_total / elapsed / 1e9
@@ -573,7 +592,7 @@ def main():
         avg_ms = kms[dom] / kn[dom]
         per_launch = kb / kn[dom]
         ach = per_launch / (avg_ms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC.get(args.workload) if spc == lay.n_slots and SEED_OFFSET == 0 else None  # measured on the default draw
+        traffic = MEASURED_TRAFFIC.get(args.workload) if spc == lay.n_slots and SEED_OFFSET == 0 and not args.share_qkv_x else None  # measured on the default draw
         roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(ach / HBM_PEAK_GBS, 4), traffic=int(traffic[dom]) if traffic else None, avg_launch_ms=round(avg_ms, 5),
                     launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
@@ -585,7 +604,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": {0: "f16", 1: "bf16", 2: "f32"}[lay.dtype],
         "data": "synthetic",
         "config": {"workload": args.workload, "slots": lay.n_slots, "tokens": int(T), "adapters": int(w.n_ad),
-                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc), "seed": int(cfg["seed"]),
+                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc), "seed": int(cfg["seed"]), "share_qkv_x": bool(args.share_qkv_x),
                    "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1),
                    "mean_run_of_consecutive_pages": round(w.mean_run_pages, 1), "activation_sets": len(w.act_sets), "activation_bytes_per_set": int(w.act_bytes)},
         "tokens_per_s": round(tokens_total / elapsed, 1),

@@ -78,14 +78,19 @@ class Case:
         self.opool.evict(i)
         self.gpool.evict(i)
 
-    def run(self, t2a, slots=None, seed=0, y0_zero=False, check=True, x_std=1.0):
-        """One batch over `slots` on both sides; returns per-slot dicts with raw outputs."""
+    def run(self, t2a, slots=None, seed=0, y0_zero=False, check=True, x_std=1.0, share_x=()):
+        """One batch over `slots` on both sides; returns per-slot dicts with raw outputs.  share_x:
+        groups of positions in `slots` (same d_in) that read one x buffer, as q, k, v of a layer do."""
         torch, lay = self.torch, self.lay
         t2a = np.ascontiguousarray(t2a, dtype=np.int32)
         T = len(t2a)
         slots = list(range(lay.n_slots)) if slots is None else list(slots)
         rng = np.random.default_rng(seed)
         xs = [make_act(rng, T, lay.d_in[s], lay.dtype, x_std) for s in slots]
+        for group in share_x:
+            for j in group[1:]:
+                assert lay.d_in[slots[j]] == lay.d_in[slots[group[0]]]
+                xs[j] = xs[group[0]]
         y0 = [np.zeros((T, lay.d_out[s]), RAW_DTYPE[lay.dtype]) if y0_zero else make_act(rng, T, lay.d_out[s], lay.dtype)
               for s in slots]
         # GPU side: with the cooperative kernels of small calls; with the panel kernel for every large
@@ -106,7 +111,12 @@ class Case:
         perm, seg_adapter, seg_start = self.gpool.batch_info(batch)
         o_perm, o_sa, o_ss = self.opool.translate(t2a)
         assert perm.tolist() == o_perm.tolist() and seg_adapter.tolist() == o_sa.tolist() and seg_start.tolist() == o_ss.tolist()
-        xd = [raw_to_torch(x, "cuda") for x in xs]
+        on_device = {}
+        xd = []
+        for x in xs:  # one device buffer per distinct x
+            if id(x) not in on_device:
+                on_device[id(x)] = raw_to_torch(x, "cuda")
+            xd.append(on_device[id(x)])
         yd = [raw_to_torch(y, "cuda") for y in y0]
         vd = [torch.full((max(T, 1), self.max_rank), float("nan"), device="cuda", dtype=torch.float32) for _ in slots]
         # contiguous slot runs go through one call each

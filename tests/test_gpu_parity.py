@@ -195,6 +195,19 @@ def test_matrix_core_shrink_with_one_and_two_runs_in_flight(oracle_mod, dtype):
     case.close()
 
 
+def test_slots_that_share_one_x_buffer(oracle_mod):
+    """q, k and v of a layer read the same x: slots of a call may be given one buffer."""
+    lay = Layout((256, 256, 256, 256, 200, 200, 128), (64, 128, 64, 64, 64, 72, 64), DT_BF16)
+    ranks = [8, 24, 32, 64, 40]
+    case = Case(oracle_mod, lay, ranks, [1.0] * len(ranks), 4096, 2048, seed=81)
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in ((0, 1), (1, 32), (2, 33), (3, 70), (4, 5))] + [np.full(3, -1, np.int32)])
+    np.random.default_rng(82).shuffle(t2a)
+    for mfma in (1, 0):
+        case.set_mfma(mfma)
+        case.run(t2a, seed=4, share_x=((0, 1, 2, 3), (4, 5)))
+    case.close()
+
+
 @pytest.mark.parametrize("dtype", [DT_BF16, DT_F32])
 def test_maximum_rank(oracle_mod, dtype):
     """Ranks up to the library's limit of 512 (the expand stages one page pair per row of B), with
