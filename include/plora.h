@@ -174,7 +174,7 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * workgroup, instead of one mixed launch; defaults 0 / 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
  * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound
  * by its longest chain of dependent loads; it runs the cooperative kernels instead, in which the four
- * wavefronts of a workgroup share one vector-ALU item; defaults 600 / 2500, 0 = never; take effect for
+ * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 2500, 0 = never; take effect for
  * batches begun afterwards).  "batches_per_marker" (1..64, default 4: plora_batch_end puts one completion
  * event on the stream per this many batches instead of one per batch; the library records a pending
  * one itself whenever an eviction, a load or the reuse of a batch object has to order against it, so
@@ -186,8 +186,8 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * batch of the first kind, a group's last <= this many tokens still go as 16-token items.
  * "mfma_shrink_depth" (0, 1 or 2; default 0): runs of 64 values of the contraction that a matrix-core
  * shrink item keeps in flight per wavefront; 0 lets the library choose per launch (2 when the batch's
- * matrix-core token tiles are at least half full on average, as in prefill, or a slot of the launch has
- * d_in > 4096; else 1).  Results do not depend on it.
+ * matrix-core token tiles are at least half full on average, as in prefill, when a slot of the launch
+ * has d_in > 4096, or when the launch has at most 2500 workgroups; else 1).  Results do not depend on it.
  * "staging_bytes" (0 .. 2^36, default 0 = off) and "staging_min_runs" (>= 1, default 3: with two runs the direct copies are as fast): staged loads
  * (Sec. III-B: loaded adapters arrive in a staging area before they are moved into place).  With
  * staging on, plora_load_adapter sends a blob of at most staging_bytes whose pages form at least

@@ -141,7 +141,8 @@ struct plora_pool {
   int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
                          // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
   int mfma_shrink_depth = 0;  // runs in flight per matrix-core shrink item: 1, 2, or 0 = by batch and slot shape
-  int64_t coop_max_workgroups[2] = {600, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
+  int64_t deep_max_workgroups = 2500;  // shrink launches of at most this many workgroups take the two-runs-in-flight kernel
+  int64_t coop_max_workgroups[2] = {192, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
                                                  // most this many workgroups use the cooperative kernels (0 = never)
   int slot_major[2] = {-1, 2}; // -1: slots are the fastest grid dimension when their count is a multiple of 8; 0 never; 1 always;
                                // 2 (expand): the 512-column chunks are the fastest dimension
@@ -976,7 +977,9 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     if (is_shrink && !coop && p->dtype != PLORA_F32 && b->n_heavy[0] > 0) {
       int32_t max_in = 0;
       for (int q = 0; q < nq; ++q) max_in = std::max(max_in, p->slots[ptrs.slot[q]].d_in);
-      deep = p->mfma_shrink_depth == 2 || (p->mfma_shrink_depth == 0 && (b->full_shrink_tiles || max_in > 4096));
+      // ... or a launch too small to hide the chain of an item's runs behind other workgroups
+      const bool small_launch = (int64_t)nq * (n_all / 4) <= p->deep_max_workgroups;
+      deep = p->mfma_shrink_depth == 2 || (p->mfma_shrink_depth == 0 && (b->full_shrink_tiles || max_in > 4096 || small_launch));
     }
     struct Part { const ItemRec* items; int n; int mode; };
     const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, panel ? 3 : coop ? 2 : deep ? 3 : 0},
