@@ -1025,12 +1025,17 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
       __syncthreads();
     }
     if (has_tok) {
+      // both column tiles' rows of y are requested before the first is updated: one trip, not two
+#pragma unroll
+      for (int ct = 0; ct < 2; ++ct) {
+        const int n = imin(nh0 + ct * 128 + 8 * c, d_out - 8);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) yq[ct][i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
+      }
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct) {
         const int n = nh0 + ct * 128 + 8 * c;
         if (n < d_out) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) yq[ct][i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             if (wave * 16 + g * 4 + i < it.ntok) {
