@@ -104,6 +104,7 @@ struct plora_pool {
   std::vector<SlotRec> slots;
   int64_t C = 0;
   int max_d_out = 0;
+  int min_chunks = 1;  // 512-column chunks (64 lanes x 16 bytes) of the narrowest slot: the fewest workgroups per expand block
   uint8_t* slab = nullptr;
   bool own_slab = false;
   SlotRec* d_slots = nullptr;
@@ -307,7 +308,7 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
   if (slab_or_null && ((uintptr_t)slab_or_null & 255)) return PLORA_ERR_INVAL;
   const int elt = lay->dtype == PLORA_F32 ? 4 : 2;
   int64_t c = 0;
-  int max_in = 0, max_out = 0;
+  int max_in = 0, max_out = 0, min_out = 1 << 30;
   std::vector<SlotRec> slots;
   for (int s = 0; s < lay->n_slots; ++s) {
     const int32_t di = lay->d_in[s], dn = lay->d_out[s];
@@ -316,6 +317,7 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
     c += (int64_t)di + dn;
     max_in = std::max(max_in, di);
     max_out = std::max(max_out, dn);
+    min_out = std::min(min_out, dn);
   }
   // page-table windows staged in LDS: 32 rows per matrix-core item (kPtWindow entries), 8 rows per
   // vector-ALU item (a quarter of that)
@@ -330,6 +332,7 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
   p->placement_only = (flags & PLORA_POOL_PLACEMENT_ONLY) != 0;
   p->dtype = lay->dtype; p->elt = elt; p->max_adapters = lay->max_adapters; p->max_rank = lay->max_rank;
   p->n_slots = lay->n_slots; p->slots = slots; p->C = c; p->max_d_out = max_out;
+  p->min_chunks = (min_out + kWave * (16 / elt) - 1) / (kWave * (16 / elt));
   p->free_bits.assign(((size_t)n_pages + 63) / 64, ~(uint64_t)0);
   if (n_pages & 63) p->free_bits.back() = (((uint64_t)1 << (n_pages & 63)) - 1);
   p->n_free = n_pages;
@@ -810,7 +813,8 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     // Cooperative form (calls too small to fill the machine): every group as vector-ALU records, one per
     // workgroup, longest chains first.  Not needed when even one slot's ordinary launch is past its limit.
     lists[op][2].clear();
-    if (p->coop_max_workgroups[op] > 0 && (int64_t)(lists[op][0].size() / 4) <= p->coop_max_workgroups[op]) {
+    const int64_t min_grid = op == 1 ? p->min_chunks : 1;  // workgroups per block of the list in the smallest launch
+    if (p->coop_max_workgroups[op] > 0 && (int64_t)(lists[op][0].size() / 4) * min_grid <= p->coop_max_workgroups[op]) {
       std::vector<ItemRec>& all = wl[op][1].items;  // reused as scratch: the matrix-core records are arranged already
       all.clear();
       size_t pt_run = 0;
