@@ -43,7 +43,8 @@ typedef enum {
   PLORA_ERR_EXISTS = -3,   /* id already resident (or still loading) */
   PLORA_ERR_NOTFOUND = -4, /* id not resident */
   PLORA_ERR_BUSY = -5,     /* evict of an adapter whose load has not completed or that an open batch uses */
-  PLORA_ERR_HIP = -6       /* a HIP runtime call failed; see plora_last_hip */
+  PLORA_ERR_HIP = -6,      /* a HIP runtime call failed; see plora_last_hip */
+  PLORA_ERR_LIMIT = -7     /* the request is valid but larger than a fixed capacity of the entry point */
 } plora_status;
 
 typedef enum { PLORA_F16 = 0, PLORA_BF16 = 1, PLORA_F32 = 2 } plora_dtype;
@@ -134,10 +135,13 @@ int plora_batch_info(const plora_batch* batch, int32_t* n_seg, int32_t* n_perm, 
  *   v[s][t, j] = 0                            (r_i <= j < max_rank, or t has no adapter)
  * x: host array of n_slots device pointers, x[q] -> n_tokens x d_in[slot0+q] elements, row-major,
  * 16-byte aligned.  v: host array of n_slots device pointers, v[q] -> n_tokens x max_rank floats,
- * 16-byte aligned.  Runs on `stream` (normally the stream given to plora_batch_begin; another stream
- * must be ordered after it by the caller).  While plora_profile is off, plora_shrink and plora_expand
- * allocate nothing and enqueue kernels only, so they may be recorded into a HIP graph on a capturing
- * stream; the batch has to stay open, and x, v, y in place, for as long as the graph is replayed. */
+ * 16-byte aligned.  Runs on `stream`: normally the stream given to plora_batch_begin; another stream
+ * must be ordered after that one by the caller (the batch's tables arrive on it), and plora_batch_end
+ * then makes the batch's own stream wait for the other stream's kernels, so that later evictions and
+ * loads are ordered after every kernel of the batch.  While plora_profile is off, plora_shrink and
+ * plora_expand call no device allocator and enqueue kernels only, so they may be recorded into a HIP
+ * graph on a capturing stream; the batch has to stay open, and x, v, y in place, for as long as the
+ * graph is replayed, and plora_batch_end must not be called while such a stream is still capturing. */
 int plora_shrink(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const void* const* x,
                  float* const* v, plora_stream stream);
 
@@ -147,6 +151,23 @@ int plora_shrink(plora_pool* pool, const plora_batch* batch, int32_t slot0, int3
  * d_out[slot0+q] elements, row-major, 16-byte aligned, updated in place. */
 int plora_expand(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const float* const* v,
                  void* const* y, plora_stream stream);
+
+/* Eq. 1's delta in one call: shrink, then expand, over the same slot range, as plora_shrink followed by
+ * plora_expand with the same arguments would do (v is the workspace in between; its contents afterwards
+ * are those plora_shrink leaves).  Nothing is queued if an argument is invalid. */
+int plora_delta(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const void* const* x,
+                float* const* v, void* const* y, plora_stream stream);
+
+/* plora_delta for callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid it): the workspace v lives in a static device array of the
+ * library, 16 MiB per GPU, held from the library's first use on that GPU until the process ends.
+ * Calls no allocator of the HIP runtime (nor any host allocator).  LIMIT if
+ * n_slots * round_up(n_tokens * max_rank * 4, 256) exceeds 16 MiB; INVAL while plora_profile is on.
+ * Every call on a GPU uses the same array from its start: two calls whose kernels may overlap on
+ * one GPU (different streams, or two pools) race; calls on one stream are ordered and safe.  x and y
+ * as in plora_shrink / plora_expand. */
+int plora_delta_static(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots,
+                       const void* const* x, void* const* y, plora_stream stream);
 
 /* Ends the batch: unpins its adapters, hands the batch object back for reuse and notes that its
  * completion has to be recorded on its stream (the stream given to plora_batch_begin).  Kernels
@@ -169,9 +190,7 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * neighbouring workgroups read neighbouring pieces of the same rows of B) and "xcd_remap" (1 = for
  * launches whose fastest dimension is not the slot, neighbouring work items share an XCD) set the
  * launch geometry of both operations; with the suffix "_shrink" / "_expand" of one (defaults: shrink
- * -1 and 1, expand 2 and 0).  "split_shrink" / "split_expand" (1 = when slots are the fastest dimension, launch the
- * matrix-core blocks in the 256-thread kernel and then the vector-ALU items one per single-wavefront
- * workgroup, instead of one mixed launch; defaults 0 / 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
+ * -1 and 1, expand 2 and 0).  "coop_max_workgroups_shrink" / "coop_max_workgroups_expand" (a call
  * whose ordinary launch would have at most this many workgroups is too small to fill the GPU and bound
  * by its longest chain of dependent loads; it runs the cooperative kernels instead, in which the four
  * wavefronts of a workgroup share one vector-ALU item; defaults 192 / 2500, 0 = never; take effect for

@@ -337,7 +337,7 @@ int oracle_shrink(void* h, int32_t s, const void* x, const int32_t* tok2adapter,
   int32_t n = tok_sel ? n_sel : T;
   int bad = 0;
   (void)threads;
-#pragma omp parallel for schedule(dynamic, 1) num_threads(threads) if (threads > 1)
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads) if (threads > 1) reduction(| : bad)
   for (int32_t q = 0; q < n; ++q) {
     int32_t t = tok_sel ? tok_sel[q] : q;
     int32_t i = tok2adapter[t];
@@ -366,7 +366,7 @@ int oracle_expand(void* h, int32_t s, const void* v, const int32_t* tok2adapter,
   int32_t n = tok_sel ? n_sel : T;
   int bad = 0;
   (void)threads;
-#pragma omp parallel for schedule(dynamic, 1) num_threads(threads) if (threads > 1)
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads) if (threads > 1) reduction(| : bad)
   for (int32_t q = 0; q < n; ++q) {
     int32_t t = tok_sel ? tok_sel[q] : q;
     int32_t i = tok2adapter[t];

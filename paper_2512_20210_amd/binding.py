@@ -11,10 +11,10 @@ import os
 import numpy as np
 
 __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS", "PLORA_ERR_NOTFOUND",
-           "PLORA_ERR_BUSY", "PLORA_ERR_HIP", "PLORA_F16", "PLORA_BF16", "PLORA_F32", "PLORA_POOL_PLACEMENT_ONLY",
+           "PLORA_ERR_BUSY", "PLORA_ERR_HIP", "PLORA_ERR_LIMIT", "PLORA_F16", "PLORA_BF16", "PLORA_F32", "PLORA_POOL_PLACEMENT_ONLY",
            "plora_pool_create", "plora_pool_destroy", "plora_adapter_bytes", "plora_load_adapter",
            "plora_adapter_ready", "plora_wait_adapter", "plora_evict", "plora_batch_begin", "plora_batch_info",
-           "plora_shrink", "plora_expand", "plora_batch_end", "plora_pool_stats", "plora_pool_set_option",
+           "plora_shrink", "plora_expand", "plora_delta", "plora_delta_static", "plora_batch_end", "plora_pool_stats", "plora_pool_set_option",
            "plora_profile", "plora_profile_read", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH",
            "plora_predictor_create", "plora_predictor_destroy", "plora_predictor_observe", "plora_predictor_observed",
            "plora_predictor_predict", "plora_predictor_train", "plora_predictor_train_batch",
@@ -22,10 +22,10 @@ __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS",
            "plora_predictor_loss_grad", "plora_predictor_set_threads", "LstmPredictor"]
 
 PLORA_OK, PLORA_ERR_INVAL, PLORA_ERR_NOMEM, PLORA_ERR_EXISTS = 0, -1, -2, -3
-PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP = -4, -5, -6
+PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP, PLORA_ERR_LIMIT = -4, -5, -6, -7
 PLORA_F16, PLORA_BF16, PLORA_F32 = 0, 1, 2
 PLORA_POOL_PLACEMENT_ONLY = 1
-_STATUS = {0: "OK", -1: "INVAL", -2: "NOMEM", -3: "EXISTS", -4: "NOTFOUND", -5: "BUSY", -6: "HIP"}
+_STATUS = {0: "OK", -1: "INVAL", -2: "NOMEM", -3: "EXISTS", -4: "NOTFOUND", -5: "BUSY", -6: "HIP", -7: "LIMIT"}
 
 LIB_PATH = os.environ.get("PLORA_LIB") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libplora.so")
 if not os.path.exists(LIB_PATH):
@@ -59,6 +59,8 @@ lib.plora_batch_info.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTE
                                  C.POINTER(C.POINTER(_i32)), C.POINTER(C.POINTER(_i32))]
 lib.plora_shrink.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp]
 lib.plora_expand.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp]
+lib.plora_delta.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp, _vp]
+lib.plora_delta_static.argtypes = [_vp, _vp, _i32, _i32, _vp, _vp, _vp]
 lib.plora_batch_end.argtypes = [_vp, _vp]
 lib.plora_pool_stats.argtypes = [_vp, C.POINTER(_Stats)]
 lib.plora_pool_set_option.argtypes = [_vp, C.c_char_p, C.c_int64]
@@ -163,6 +165,14 @@ def plora_shrink(pool, batch, slot0, n_slots, x_ptrs, v_ptrs, stream=None):
 
 def plora_expand(pool, batch, slot0, n_slots, v_ptrs, y_ptrs, stream=None):
     return lib.plora_expand(pool, batch, slot0, n_slots, _ptr_array(v_ptrs), _ptr_array(y_ptrs), stream)
+
+
+def plora_delta(pool, batch, slot0, n_slots, x_ptrs, v_ptrs, y_ptrs, stream=None):
+    return lib.plora_delta(pool, batch, slot0, n_slots, _ptr_array(x_ptrs), _ptr_array(v_ptrs), _ptr_array(y_ptrs), stream)
+
+
+def plora_delta_static(pool, batch, slot0, n_slots, x_ptrs, y_ptrs, stream=None):
+    return lib.plora_delta_static(pool, batch, slot0, n_slots, _ptr_array(x_ptrs), _ptr_array(y_ptrs), stream)
 
 
 def plora_batch_end(pool, batch):
@@ -271,6 +281,14 @@ class PagedLoraPool:
     def expand(self, batch, slot0, v_tensors, y_tensors, stream=None):
         _check("plora_expand", plora_expand(self.h, batch, slot0, len(y_tensors), [t.data_ptr() for t in v_tensors],
                                             [t.data_ptr() for t in y_tensors], stream))
+
+    def delta(self, batch, slot0, x_tensors, v_tensors, y_tensors, stream=None):
+        _check("plora_delta", plora_delta(self.h, batch, slot0, len(x_tensors), [t.data_ptr() for t in x_tensors],
+                                          [t.data_ptr() for t in v_tensors], [t.data_ptr() for t in y_tensors], stream))
+
+    def delta_static(self, batch, slot0, x_tensors, y_tensors, stream=None):
+        _check("plora_delta_static", plora_delta_static(self.h, batch, slot0, len(x_tensors), [t.data_ptr() for t in x_tensors],
+                                                        [t.data_ptr() for t in y_tensors], stream))
 
     def batch_end(self, batch):
         _check("plora_batch_end", plora_batch_end(self.h, batch))

@@ -7,30 +7,15 @@ namespace plora {
 
 constexpr int kWave = 64;               // one work item = one wavefront = one workgroup
 constexpr int kMaxSlotsPerLaunch = 128; // pointer pairs carried in the kernel arguments
-#ifndef PLORA_SHRINK_ROWS
-#define PLORA_SHRINK_ROWS 8
-#endif
-#ifndef PLORA_VALU_TOK
-#define PLORA_VALU_TOK 4
-#endif
-#ifndef PLORA_EXPAND_U
-#define PLORA_EXPAND_U 8
-#endif
-constexpr int kShrinkRows = PLORA_SHRINK_ROWS;  // rows of A per vector-ALU shrink item
-constexpr int kValuTok = PLORA_VALU_TOK;        // tokens per vector-ALU item (1, 2 or 4)
-constexpr int kExpandU = PLORA_EXPAND_U;        // rows of B in flight per vector-ALU expand iteration
-#ifndef PLORA_MFMA_TOK_S
-#define PLORA_MFMA_TOK_S 32
-#endif
-constexpr int kMfmaTokS = PLORA_MFMA_TOK_S;     // tokens per matrix-core shrink item
+constexpr int kShrinkRows = 8;          // rows of A per vector-ALU shrink item
+constexpr int kValuTok = 4;             // tokens per vector-ALU item (1, 2 or 4)
+constexpr int kExpandU = 8;             // rows of B in flight per vector-ALU expand iteration
+constexpr int kMfmaTokS = 32;           // tokens per matrix-core shrink item
 constexpr int kMfmaTokE = 64;           // tokens per matrix-core expand item of the panel kernel
 constexpr int kMfmaTokCols = 16;        // items of at most this many tokens take the column-split form
 constexpr int kMfmaColsMaxGroup = 32;   // panel batches: groups (or last blocks of groups) of at most this many
                                         // tokens are cut into column-split items (default of an option)
-#ifndef PLORA_MFMA_ROWS
-#define PLORA_MFMA_ROWS 32
-#endif
-constexpr int kMfmaRows = PLORA_MFMA_ROWS;      // rows of A per matrix-core shrink item
+constexpr int kMfmaRows = 32;           // rows of A per matrix-core shrink item
 constexpr int kMfmaCols = 128;          // columns of B per matrix-core expand pass
 constexpr int kPtWindow = 1024;         // page-table entries a shrink item may stage in LDS
 constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for (4 KiB of LDS)
@@ -89,11 +74,14 @@ struct ScatterRuns {
   int32_t phys_page[kScatterRuns];
 };
 
+enum LaunchMode { kModeBlocks = 0, kModeCoop = 1, kModeDeep = 2, kModePanel = 2 };
+
 // Launchers (plora_kernels.hip).  Both take a list of blocks of 4 records (one matrix-core item +
 // 3 padding records, or up to 4 vector-ALU items) and run one 256-thread workgroup per block, slot
-// and (expand) 512-column chunk.  mode 1: the list holds vector-ALU records only
-// and every record gets a single-wavefront workgroup of its own; mode 2: likewise, but a 256-thread
-// workgroup whose four wavefronts share the record's work (for calls too small to fill the machine).  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
+// and (expand) 512-column chunk.  kModeCoop: the list holds vector-ALU records only and every record
+// gets a 256-thread workgroup whose four wavefronts share the record's work (for calls too small to
+// fill the machine); kModeDeep (shrink): blocks, two runs in flight per matrix-core item; kModePanel
+// (expand): matrix-core blocks only, B stationary in LDS.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
 // a.slot_fastest is set: consecutive workgroups go to consecutive XCDs, so with a slot count that
 // is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
 // slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row
@@ -104,6 +92,11 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int 
                          hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+
+// The library's static device array (plora_delta_static keeps v there): its size, and its address on
+// the current device (looked up once per device).
+uint64_t static_scratch_bytes();
+hipError_t static_scratch(void** out);
 
 // Copies `bytes` bytes that lie contiguous at `staging` (device) into the pages pt[0 .. n_pages) (host
 // array, ascending) of the slab, in virtual order; (n_pages - 1) pages < bytes <= n_pages pages,

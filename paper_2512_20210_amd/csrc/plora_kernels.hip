@@ -22,9 +22,9 @@
 //                             in LDS, one 16-token tile per wavefront.  v is split into a high and a
 //                             low half so that fp32 v loses nothing that matters.
 //
-// Two more launch forms use the vector-ALU records alone: one record per single-wavefront workgroup,
-// and the cooperative kernels for calls too small to fill the machine (one record per 256-thread
-// workgroup whose wavefronts split the record's chain of loads).  k_scatter_pages moves a blob that
+// One more launch form uses the vector-ALU records alone: the cooperative kernels for calls too small
+// to fill the machine (one record per 256-thread workgroup whose wavefronts split the record's chain
+// of loads).  k_scatter_pages moves a blob that
 // arrived contiguous in a staging buffer into its pages (staged loads).
 //
 // Uniform values stay scalar: grid coordinates, slot record, work record (one 32-byte scalar load)
@@ -48,6 +48,8 @@
 #include "plora_internal.h"
 #include <hip/hip_ext.h>
 
+#include <mutex>
+
 namespace plora {
 namespace {
 
@@ -60,20 +62,7 @@ template <> struct Elt<2> { static constexpr int B = 4, VEC = 4; };
 
 __device__ __forceinline__ uint4 ld16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
 // Minimum workgroups per CU the compiler must leave room for (bounds the VGPR budget).
-#ifndef PLORA_SHRINK_WG_PER_CU
-#define PLORA_SHRINK_WG_PER_CU 3
-#endif
-#ifndef PLORA_PANEL_WG_PER_CU
-#define PLORA_PANEL_WG_PER_CU 3
-#endif
-#ifndef PLORA_EXPAND_WG_PER_CU
-#define PLORA_EXPAND_WG_PER_CU 3
-#endif
-// PLORA_NT_WEIGHTS: 0 = weight loads always cached, 1 = streaming (non-temporal) loads for items
-// whose weights no other item reads (record flag), 2 = streaming loads for every item.
-#ifndef PLORA_NT_WEIGHTS
-#define PLORA_NT_WEIGHTS 1
-#endif
+constexpr int kWgPerCu = 3;
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 // Weights that are read once per batch by this item alone are fetched with streaming loads: they
 // then do not push the re-used x / v rows, page-table entries and other items' shared weight rows out
@@ -111,29 +100,17 @@ __device__ __forceinline__ int wave_id() { return __builtin_amdgcn_readfirstlane
 // Record flag (bit 8 of a non-negative kind): no other item of the batch reads this item's weights.
 __device__ __forceinline__ int item_kind(const ItemRec& it) { return it.kind < 0 ? -1 : (it.kind & 0xff); }
 __device__ __forceinline__ bool item_once(const ItemRec& it) {
-  return PLORA_NT_WEIGHTS == 2 || (PLORA_NT_WEIGHTS == 1 && it.kind >= 0 && (it.kind & kItemOnce) != 0);
+  return it.kind >= 0 && (it.kind & kItemOnce) != 0;
 }
-// y is read once and written once per step: streaming (non-temporal) accesses (bit 0: loads, bit 1:
-// stores), so that its lines neither stay in the caches nor wait there to be written back during
-// the next kernel.
-#ifndef PLORA_NT_Y
-#define PLORA_NT_Y 3
-#endif
+// y is read once and written once per step: streaming (non-temporal) loads and stores, so that its
+// lines neither stay in the caches nor wait there to be written back during the next kernel.
 __device__ __forceinline__ uint4 ldy16(const void* p) {
-#if PLORA_NT_Y & 1
   const u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
   return make_uint4(q.x, q.y, q.z, q.w);
-#else
-  return *reinterpret_cast<const uint4*>(p);
-#endif
 }
 __device__ __forceinline__ void sty16(void* p, uint4 q) {
-#if PLORA_NT_Y & 2
   u32x4_t t; t.x = q.x; t.y = q.y; t.z = q.z; t.w = q.w;
   __builtin_nontemporal_store(t, reinterpret_cast<u32x4_t*>(p));
-#else
-  *reinterpret_cast<uint4*>(p) = q;
-#endif
 }
 
 __device__ __forceinline__ float half_bits_to_float(uint32_t h) {
@@ -158,15 +135,7 @@ __device__ __forceinline__ void unpack(const uint4 q, float* f) {
 }
 
 // fp32 -> element, round to nearest even.
-__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-  return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
 // Two fp32 -> one register of two bf16, round to nearest even, in one instruction (v_cvt_pk_bf16_f32).
-#ifndef PLORA_HW_BF16_CVT
-#define PLORA_HW_BF16_CVT 1
-#endif
 typedef __bf16 bf16x2_cvt_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_cvt_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
@@ -183,15 +152,8 @@ __device__ __forceinline__ uint4 pack(const float* f) {
   if constexpr (DT == 2) {
     q.x = __float_as_uint(f[0]); q.y = __float_as_uint(f[1]); q.z = __float_as_uint(f[2]); q.w = __float_as_uint(f[3]);
   } else if constexpr (DT == 1) {
-#if PLORA_HW_BF16_CVT
     q.x = f32x2_to_bf16x2(f[0], f[1]); q.y = f32x2_to_bf16x2(f[2], f[3]);
     q.z = f32x2_to_bf16x2(f[4], f[5]); q.w = f32x2_to_bf16x2(f[6], f[7]);
-#else
-    q.x = f32_to_bf16_bits(f[0]) | (f32_to_bf16_bits(f[1]) << 16);
-    q.y = f32_to_bf16_bits(f[2]) | (f32_to_bf16_bits(f[3]) << 16);
-    q.z = f32_to_bf16_bits(f[4]) | (f32_to_bf16_bits(f[5]) << 16);
-    q.w = f32_to_bf16_bits(f[6]) | (f32_to_bf16_bits(f[7]) << 16);
-#endif
   } else {
     q.x = f32_to_f16_bits(f[0]) | (f32_to_f16_bits(f[1]) << 16);
     q.y = f32_to_f16_bits(f[2]) | (f32_to_f16_bits(f[3]) << 16);
@@ -524,17 +486,7 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
 // row-contiguous 16-byte loads (8 lanes per row), parks them in its own LDS region and reads the
 // operands back in MFMA layout.  The next tiles are requested before the current ones are
 // multiplied.
-#ifndef PLORA_SM_INTERLEAVE
-#define PLORA_SM_INTERLEAVE 1
-#endif
-#ifndef PLORA_SM_BARRIER
-#define PLORA_SM_BARRIER 1
-#endif
-#if PLORA_SM_BARRIER
 #define SM_SYNC() __syncthreads()
-#else
-#define SM_SYNC() wave_sync()
-#endif
 constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16 pad per LDS row
 static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
@@ -577,14 +529,8 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
   // this wavefront's quarter of the contraction, in runs of 64 k-values
   const int nrun = (d_in + 63) >> 6;
   const int per = (nrun + 3) >> 2;
-#if PLORA_SM_INTERLEAVE
   const int mine = (nrun - wave + 3) >> 2;  // runs wave, wave + 4, ...
 #define SM_RUN(i) ((i) * 4 + wave)
-#else
-  const int c0 = imin(nrun, wave * per), c1 = imin(nrun, c0 + per);
-  const int mine = c1 - c0;
-#define SM_RUN(i) (c0 + (i))
-#endif
 
   f32x4 acc[2][2];
 #pragma unroll
@@ -691,13 +637,10 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
       SM_SYNC();
     }
   }
-#if PLORA_SM_BARRIER
   // every wavefront passes 2 * per barriers: those with fewer runs (or none) catch up here
   for (int run = mine; run < per; ++run) { __syncthreads(); __syncthreads(); }
-#else
-  __syncthreads();  // the reduction below reuses every wavefront's tiles
-#endif
 #undef SM_RUN
+#undef SM_SYNC
 
   // add the 4 partial sums in wavefront order: thread (w, lane) finishes tile (mt, nt) = (w >> 1, w & 1)
   float* red = reinterpret_cast<float*>(&tile[0][0][0]);  // 4 x 64 x 16 floats = 16 KiB, tiles are free now
@@ -727,39 +670,49 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
 // Splits 8 fp32 values into a high and a low 16-bit part: hi = round(v), lo = round(v - hi).
 template <int DT>
 __device__ __forceinline__ void split_hi_lo(const float* f, uint4& hi, uint4& lo) {
-#if PLORA_HW_BF16_CVT
-  if constexpr (DT == 1) {
-    uint32_t hp[4], lp[4];
+  uint32_t hp[4], lp[4];
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
+  for (int e = 0; e < 4; ++e) {
+    if constexpr (DT == 1) {
       hp[e] = f32x2_to_bf16x2(f[2 * e], f[2 * e + 1]);
       lp[e] = f32x2_to_bf16x2(f[2 * e] - __uint_as_float(hp[e] << 16), f[2 * e + 1] - __uint_as_float(hp[e] & 0xffff0000u));
-    }
-    hi = make_uint4(hp[0], hp[1], hp[2], hp[3]);
-    lo = make_uint4(lp[0], lp[1], lp[2], lp[3]);
-    return;
-  }
-#endif
-  uint32_t h[8], l[8];
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    if constexpr (DT == 1) {
-      h[e] = f32_to_bf16_bits(f[e]);
-      l[e] = f32_to_bf16_bits(f[e] - __uint_as_float(h[e] << 16));
     } else {
-      h[e] = f32_to_f16_bits(f[e]);
-      l[e] = f32_to_f16_bits(f[e] - half_bits_to_float(h[e]));
+      const uint32_t h0 = f32_to_f16_bits(f[2 * e]), h1 = f32_to_f16_bits(f[2 * e + 1]);
+      hp[e] = h0 | (h1 << 16);
+      lp[e] = f32_to_f16_bits(f[2 * e] - half_bits_to_float(h0)) | (f32_to_f16_bits(f[2 * e + 1] - half_bits_to_float(h1)) << 16);
     }
   }
-  hi = make_uint4(h[0] | (h[1] << 16), h[2] | (h[3] << 16), h[4] | (h[5] << 16), h[6] | (h[7] << 16));
-  lo = make_uint4(l[0] | (l[1] << 16), l[2] | (l[3] << 16), l[4] | (l[5] << 16), l[6] | (l[7] << 16));
+  hi = make_uint4(hp[0], hp[1], hp[2], hp[3]);
+  lo = make_uint4(lp[0], lp[1], lp[2], lp[3]);
 }
+
+// fp16 only: fp32 v does not fit fp16's exponent range in general (|v| > 65504 would become inf, tiny
+// rows would land among the subnormals), so every token's row of v goes into the matrix cores
+// multiplied by a power of two that brings its largest magnitude into [1, 2), and the row's sums are
+// multiplied back in fp32 afterwards; both multiplications are exact.  Lane (g, c) looks at the
+// values of operand row c it will load later (8 of every 32, from 8 g) and the four lane groups
+// combine.  Returns the biased exponent e of the row's largest magnitude, clamped to [1, 253]:
+// scale = 2^(127 - e), inverse = 2^(e - 127).  bf16 shares fp32's exponent range and needs none of this.
+__device__ __forceinline__ uint32_t row_exponent(const float* vrow, int r, int g) {
+  float m = 0.f;
+  for (int j = 8 * g; j < r; j += 32)
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (j + e < r) m = fmaxf(m, fabsf(vrow[j + e]));
+  m = fmaxf(m, __shfl_xor(m, 16, 64));
+  m = fmaxf(m, __shfl_xor(m, 32, 64));
+  uint32_t ex = (__float_as_uint(m) >> 23) & 0xffu;
+  if (ex == 0 || ex == 255) ex = 127;  // zero / subnormal rows, and rows with inf or NaN: unscaled
+  return ex > 253u ? 253u : ex;
+}
+__device__ __forceinline__ float exp_scale(uint32_t ex) { return __uint_as_float((254u - ex) << 23); }
+__device__ __forceinline__ float exp_inverse(uint32_t ex) { return __uint_as_float(ex << 23); }
 
 // One K-step (32 rows of B) of the matrix-core expand for one 128-column pass.
 template <int DT, int MT, bool TAIL, bool NTW>
 __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int2* lds_pg, const float* const* vrow,
                                                   uint64_t base, uint64_t rowb, uint32_t lane_b, int r, int jb,
-                                                  f32x4 (*acc)[8]) {
+                                                  const float* rs, f32x4 (*acc)[8]) {
   const int g = lane_id() >> 4;
   const int lp = a.log2_page;
   const uint32_t pmask = (1u << lp) - 1;
@@ -798,7 +751,13 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
   }
   uint4 vhi[MT], vlo[MT];
 #pragma unroll
-  for (int mt = 0; mt < MT; ++mt) split_hi_lo<DT>(vf[mt], vhi[mt], vlo[mt]);
+  for (int mt = 0; mt < MT; ++mt) {
+    if constexpr (DT == 0) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vf[mt][e] *= rs[mt];
+    }
+    split_hi_lo<DT>(vf[mt], vhi[mt], vlo[mt]);
+  }
   // in-register transpose, two column offsets at a time: the 8 rows' values of one column
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
@@ -838,12 +797,22 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
   const int32_t* perm = a.perm + it.tok[0];
   const float* vrow[MT];
   int64_t trow[MT][4];
+  float rs[MT], inv[MT][4];  // fp16: power-of-two scale of operand row c, inverse for this lane's result rows
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
     const int tc = perm[imin(mt * 16 + c, it.ntok - 1)];
     vrow[mt] = v + (int64_t)tc * vs;
 #pragma unroll
     for (int i = 0; i < 4; ++i) trow[mt][i] = __shfl(tc, g * 4 + i, 64);
+    rs[mt] = 1.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) inv[mt][i] = 1.f;
+    if constexpr (DT == 0) {
+      const uint32_t ex = row_exponent(vrow[mt], r, g);
+      rs[mt] = exp_scale(ex);
+#pragma unroll
+      for (int i = 0; i < 4; ++i) inv[mt][i] = exp_inverse((uint32_t)__shfl((int)ex, g * 4 + i, 64));
+    }
   }
   f32x4 acc[MT][8];
 #pragma unroll
@@ -857,8 +826,8 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
 #pragma unroll
     for (int i = 0; i < 4; ++i) yq[mt][i] = ldy16(y + ((uint64_t)trow[mt][i] * d_out + nn) * EB);
   int jb = 0;
-  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
-  if (jb < r) expand_mfma_kstep<DT, MT, true, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, acc);
+  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, rs, acc);
+  if (jb < r) expand_mfma_kstep<DT, MT, true, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, rs, acc);
   if (!ok) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -868,7 +837,10 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
         float yf[8];
         unpack<DT>(yq[mt][i], yf);
 #pragma unroll
-        for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
+        for (int cc = 0; cc < 8; ++cc) {
+          if constexpr (DT == 0) yf[cc] = yf[cc] + it.scale * (inv[mt][i] * acc[mt][cc][i]);
+          else yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
+        }
         sty16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
       }
     }
@@ -944,6 +916,13 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
   int64_t trow[4];                                       // tokens of the result rows this lane holds
 #pragma unroll
   for (int i = 0; i < 4; ++i) trow[i] = __shfl(tc, g * 4 + i, 64);
+  float rs = 1.f, inv[4] = {1.f, 1.f, 1.f, 1.f};         // fp16: scale of operand row c, inverses of the result rows
+  if constexpr (DT == 0) {
+    const uint32_t ex = row_exponent(vrow, r, g);
+    rs = exp_scale(ex);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) inv[i] = exp_inverse((uint32_t)__shfl((int)ex, g * 4 + i, 64));
+  }
   __syncthreads();
 
   const int ks_w = wave >> 1, ct_w = wave & 1;  // the tile this wavefront stages: K-step in panel, column tile
@@ -1010,6 +989,10 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
         for (int ks = 0; ks < 2; ++ks) {
           if (j0 + ks * 32 < r) {  // uniform
             uint4 vhi, vlo;
+            if constexpr (DT == 0) {
+#pragma unroll
+              for (int e = 0; e < 8; ++e) vf[ks][e] *= rs;
+            }
             split_hi_lo<DT>(vf[ks], vhi, vlo);
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct)
@@ -1042,7 +1025,10 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
               float yf[8];
               unpack<DT>(yq[ct][i], yf);
 #pragma unroll
-              for (int cc = 0; cc < 8; ++cc) yf[cc] = yf[cc] + it.scale * acc[ct][cc][i];
+              for (int cc = 0; cc < 8; ++cc) {
+                if constexpr (DT == 0) yf[cc] = yf[cc] + it.scale * (inv[i] * acc[ct][cc][i]);
+                else yf[cc] = yf[cc] + it.scale * acc[ct][cc][i];
+              }
               sty16(y + ((uint64_t)trow[i] * d_out + n) * EB, pack<DT>(yf));
             }
           }
@@ -1059,7 +1045,7 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
 // and after them in the same launch.
 // DEPTH: runs of 64 k-values that a matrix-core item keeps in flight (1 or 2).
 template <int DT, int DEPTH>
-__global__ __launch_bounds__(256, PLORA_SHRINK_WG_PER_CU) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
+__global__ __launch_bounds__(256, kWgPerCu) void k_shrink(const LaunchArgs a, const SlotPtrs p) {
   __shared__ __align__(16) uint8_t tile[4][2][kSmRows * kSmPitch];  // [wavefront][A | x]
   __shared__ int32_t lds_pt[kPtWindow];
   const int blk = a.slot_fastest ? blockIdx.z : blockIdx.x;
@@ -1095,7 +1081,7 @@ __device__ __forceinline__ void expand_coords(const LaunchArgs& a, int& pos, int
 }
 
 template <int DT>
-__global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const LaunchArgs a, const SlotPtrs p) {
+__global__ __launch_bounds__(256, kWgPerCu) void k_expand(const LaunchArgs a, const SlotPtrs p) {
   __shared__ int2 my_pg[4 * kMaxRank];  // page pairs: one part per wavefront (vector-ALU items) ...
   int2* lds_pg = my_pg;                 // ... or the first part for the workgroup's matrix-core item
   int blk, chunk, q;
@@ -1119,7 +1105,7 @@ __global__ __launch_bounds__(256, PLORA_EXPAND_WG_PER_CU) void k_expand(const La
 // The matrix-core blocks of a batch with many large adapter groups (prefill): one item of up to 64
 // tokens per workgroup; the list holds matrix-core blocks only (first record of each block of 4).
 template <int DT>
-__global__ __launch_bounds__(256, PLORA_PANEL_WG_PER_CU) void k_expand_panel(const LaunchArgs a, const SlotPtrs p) {
+__global__ __launch_bounds__(256, kWgPerCu) void k_expand_panel(const LaunchArgs a, const SlotPtrs p) {
   __shared__ __align__(16) uint4 op[4][8][kWave];  // 4 staged tiles of B in MFMA operand order (32 KiB)
   __shared__ int2 lds_pg[kMaxRank];
   int blk, chunk, q;
@@ -1131,30 +1117,6 @@ __global__ __launch_bounds__(256, PLORA_PANEL_WG_PER_CU) void k_expand_panel(con
   uint8_t* y = (uint8_t*)p.b[q];
   if (it.ntok <= kMfmaTokCols) expand_mfma_cols_item<DT>(a, it, sl, v, y, lds_pg, chunk);
   else expand_panel_item<DT>(a, it, sl, v, y, op, lds_pg, chunk);
-}
-
-// One vector-ALU item per single-wavefront workgroup: record i of the list is item i (padding
-// records do nothing).  Fewer registers and no LDS tiles, so more items are resident per CU than in
-// the 256-thread kernels; used for the vector-ALU part of a list when it is launched on its own.
-template <int DT>
-__global__ __launch_bounds__(kWave) void k_expand_valu1(const LaunchArgs a, const SlotPtrs p) {
-  __shared__ int2 lds_pg[kMaxRank];
-  int pos, chunk, q;
-  expand_coords(a, pos, chunk, q);
-  const ItemRec it = load_item(a.items + (pos));
-  if (item_kind(it) != 0) return;
-  const SlotRec sl = a.slots[p.slot[q]];
-  expand_valu_item<DT>(a, it, sl, (const float*)p.a[q], (uint8_t*)p.b[q], lds_pg, chunk);
-}
-
-template <int DT>
-__global__ __launch_bounds__(kWave) void k_shrink_valu1(const LaunchArgs a, const SlotPtrs p) {
-  __shared__ int32_t lds_pt[kPtWindow / 4];
-  const ItemRec it = load_item(a.items + (a.slot_fastest ? blockIdx.z : blockIdx.x));
-  if (item_kind(it) != 0) return;
-  const int q = a.slot_fastest ? blockIdx.x : blockIdx.z;
-  const SlotRec sl = a.slots[p.slot[q]];
-  shrink_valu_item<DT>(a, it, sl, (const uint8_t*)p.a[q], (float*)p.b[q], lds_pt);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1396,6 +1358,36 @@ __global__ __launch_bounds__(256) void k_scatter_pages(const uint8_t* __restrict
 
 }  // namespace
 
+// ------------------------------------------------------------------------------------------
+// Static device array for callers that cannot allocate (plora_delta_static): 16 MiB per GPU the
+// library runs on, held until the process ends.  On the host the array's name only stands for the
+// symbol; its device address is looked up once per device and every use goes through that pointer.
+// ------------------------------------------------------------------------------------------
+constexpr uint64_t kStaticScratchBytes = 16ull << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+uint64_t static_scratch_bytes() { return kStaticScratchBytes; }
+
+hipError_t static_scratch(void** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static void* ptr[kMaxDevices] = {};
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* q = nullptr;
+    e = hipGetSymbolAddress(&q, HIP_SYMBOL(scratch));  // with device `dev` current: each GPU has its own copy
+    if (e != hipSuccess) return e;
+    if (!q) return hipErrorInvalidSymbol;
+    ptr[dev] = q;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
+}
+
 // Launch with optional timing events attached to the dispatch itself (start / stop timestamps of
 // this kernel; no extra packets in the queue).
 typedef void (*KernelFn)(const LaunchArgs, const SlotPtrs);
@@ -1407,15 +1399,14 @@ static void launch(KernelFn k, dim3 grid, dim3 block, hipStream_t st, hipEvent_t
 
 hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int mode, hipStream_t st,
                          hipEvent_t e0, hipEvent_t e1) {
-  const bool single = mode == 1 || mode == 2;  // one record per workgroup
+  const bool single = mode == kModeCoop;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0) return hipSuccess;
   if (!single && a0.n_items % 4) return hipErrorInvalidValue;  // blocks of 4 records
-  // mode 3: as mode 0 with two runs in flight per matrix-core item (fp32 has no such items)
-  static const KernelFn table[4][3] = {{k_shrink<0, 1>, k_shrink<1, 1>, k_shrink<2, 1>},
-                                       {k_shrink_valu1<0>, k_shrink_valu1<1>, k_shrink_valu1<2>},
+  // kModeDeep: as kModeBlocks with two runs in flight per matrix-core item (fp32 has no such items)
+  static const KernelFn table[3][3] = {{k_shrink<0, 1>, k_shrink<1, 1>, k_shrink<2, 1>},
                                        {k_shrink_coop<0>, k_shrink_coop<1>, k_shrink_coop<2>},
                                        {k_shrink<0, 2>, k_shrink<1, 2>, k_shrink<2, 1>}};
-  if (mode < 0 || mode > 3 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
+  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;
@@ -1425,22 +1416,20 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     a.items = a0.items + per * first;
     a.n_items = per * nb;
     const dim3 grid = a.slot_fastest ? dim3(n_slots, 1, nb) : dim3(nb, 1, n_slots);
-    launch(table[mode][dtype], grid, dim3(mode == 1 ? kWave : 256), st, first == 0 ? e0 : nullptr,
-           first + step >= n_blocks ? e1 : nullptr, a, p);
+    launch(table[mode][dtype], grid, dim3(256), st, first == 0 ? e0 : nullptr, first + step >= n_blocks ? e1 : nullptr, a, p);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
-  const bool single = mode == 1 || mode == 2;  // one record per workgroup
+  const bool single = mode == kModeCoop;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
   if ((!single && a0.n_items % 4) || max_chunks > 65535) return hipErrorInvalidValue;
-  static const KernelFn table[4][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
-                                       {k_expand_valu1<0>, k_expand_valu1<1>, k_expand_valu1<2>},
+  static const KernelFn table[3][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
                                        {k_expand_coop<0>, k_expand_coop<1>, k_expand_coop<2>},
                                        {k_expand_panel<0>, k_expand_panel<1>, nullptr}};
-  if (mode < 0 || mode > 3 || dtype < 0 || dtype > 2 || !table[mode][dtype]) return hipErrorInvalidValue;
+  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2 || !table[mode][dtype]) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;
@@ -1451,8 +1440,7 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     a.n_items = per * nb;
     const dim3 grid = a.slot_fastest == 1 ? dim3(n_slots, nb, max_chunks)
                     : a.slot_fastest == 2 ? dim3(max_chunks, nb, n_slots) : dim3(nb, max_chunks, n_slots);
-    launch(table[mode][dtype], grid, dim3(mode == 1 ? kWave : 256), st, first == 0 ? e0 : nullptr,
-           first + step >= n_blocks ? e1 : nullptr, a, p);
+    launch(table[mode][dtype], grid, dim3(256), st, first == 0 ? e0 : nullptr, first + step >= n_blocks ? e1 : nullptr, a, p);
   }
   return hipGetLastError();
 }

@@ -93,6 +93,11 @@ struct plora_batch {
   std::vector<int32_t> adapters;      // pinned adapters
   std::shared_ptr<Event> done;        // recorded by plora_batch_end; the images are reusable once it has passed
   hipEvent_t ev_img = nullptr;        // the image has arrived on the device (recorded on the pool's aux stream)
+  // Streams other than `stream` that kernels of this batch were launched on (the caller orders them after
+  // `stream`); plora_batch_end makes `stream` wait for each of them, so that the batch's completion marker on
+  // `stream` covers their kernels too.  ev_other: one event per entry, kept for reuse.
+  mutable std::vector<hipStream_t> other_streams;
+  std::vector<hipEvent_t> ev_other;
 };
 
 struct plora_pool {
@@ -139,8 +144,8 @@ struct plora_pool {
   // launch geometry, [shrink, expand]
   int xcd_remap[2] = {1, 0};  // item-fastest launches take the lists dealt into XCD queues
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
-  int split[2] = {0, 0}; // [shrink, expand]: 1 = with the longest-first list, launch the matrix-core blocks
-                         // in the 256-thread kernel and the vector-ALU items one per single-wavefront workgroup
+  std::vector<std::pair<int, int>> run_order;  // scratch of a shrink / expand call, n_slots entries (never grows)
+  std::vector<float*> static_v;                // scratch of plora_delta_static, n_slots entries (never grows)
   int mfma_shrink_depth = 0;  // runs in flight per matrix-core shrink item: 1, 2, or 0 = by batch and slot shape
   int64_t deep_max_workgroups = 2500;  // shrink launches of at most this many workgroups take the two-runs-in-flight kernel
   int64_t coop_max_workgroups[2] = {192, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
@@ -337,6 +342,8 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
   if (n_pages & 63) p->free_bits.back() = (((uint64_t)1 << (n_pages & 63)) - 1);
   p->n_free = n_pages;
   p->ad.resize(lay->max_adapters);
+  p->run_order.resize(lay->n_slots);
+  p->static_v.resize(lay->n_slots);
   p->count.assign(lay->max_adapters, 0);
   p->cursor.assign(lay->max_adapters, 0);
   if (!p->placement_only) {
@@ -382,6 +389,7 @@ int plora_pool_destroy(plora_pool* p) {
     if (b->h_img) { if (p->placement_only) ::operator delete(b->h_img); else (void)hipHostFree(b->h_img); }
     if (b->d_img) (void)hipFree(b->d_img);
     if (b->ev_img) (void)hipEventDestroy(b->ev_img);
+    for (hipEvent_t e : b->ev_other) (void)hipEventDestroy(e);
     delete b;
   }
   delete p;
@@ -467,6 +475,12 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
     if (e == hipSuccess && rc == PLORA_OK) e = hipEventRecord(a.ev_ready, st);
     if (e != hipSuccess || rc != PLORA_OK) {  // undo the placement
       if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); rc = PLORA_ERR_HIP; }
+      // Copies (or the scatter kernel) already queued on the stream still write into these pages or read
+      // the staging buffer: let them finish before the pages are handed out again.  A rare path, so the
+      // host simply waits.
+      (void)hipStreamSynchronize(st);
+      (void)hipGetLastError();
+      if (staged) p->stage_next ^= 1;  // the buffer was not used after all (and is idle now)
       for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
       p->n_free += (uint32_t)m;
       p->hint_word = std::min<uint32_t>(p->hint_word, a.pt.empty() ? p->hint_word : (uint32_t)a.pt[0] >> 6);
@@ -612,11 +626,6 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     if (k != "xcd_remap_shrink") p->xcd_remap[1] = (int)value;
     return PLORA_OK;
   }
-  if (k == "split_shrink" || k == "split_expand") {
-    if (value != 0 && value != 1) return PLORA_ERR_INVAL;
-    p->split[k == "split_expand"] = (int)value;
-    return PLORA_OK;
-  }
   if (k == "slot_major" || k == "slot_major_shrink" || k == "slot_major_expand") {
     if (value < -1 || value > (k == "slot_major_expand" ? 2 : 1)) return PLORA_ERR_INVAL;  // 2: chunks fastest
     if (k != "slot_major_expand") p->slot_major[0] = (int)value;
@@ -668,6 +677,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     b = new (std::nothrow) plora_batch;
     if (!b) { for (int32_t i : touched) p->count[i] = 0; return PLORA_ERR_NOMEM; }
     b->pool = p;
+    b->other_streams.reserve(8);
     p->batches.push_back(b);
   }
   b->stream = (hipStream_t)s;
@@ -912,6 +922,10 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
   if (!in || !outp) return PLORA_ERR_INVAL;
   for (int q = 0; q < n_slots; ++q)
     if (!in[q] || !outp[q] || ((uintptr_t)in[q] & 15) || ((uintptr_t)outp[q] & 15)) return PLORA_ERR_INVAL;
+  // kernels on a stream other than the batch's own: plora_batch_end has to cover that stream too
+  if ((hipStream_t)s != b->stream &&
+      std::find(b->other_streams.begin(), b->other_streams.end(), (hipStream_t)s) == b->other_streams.end())
+    b->other_streams.push_back((hipStream_t)s);
   LaunchArgs a;
   a.slab = p->slab;
   a.perm = (const int32_t*)(b->d_img + b->off_perm);
@@ -926,13 +940,20 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
   a.pad = 0;
   // Launch classes: an expand launch has one grid dimension for the 512-column chunks, so slots with
   // different chunk counts go in launches of their own (no empty workgroups) ...; shrink has one class.
-  std::vector<std::pair<int, int>> order;  // (chunks, index within the call), stable by chunks
-  order.reserve(n_slots);
+  std::pair<int, int>* order = p->run_order.data();  // (chunks, index within the call), stable by chunks
   for (int q = 0; q < n_slots; ++q) {
     const int d_out = (int)p->slots[slot0 + q].d_out;
-    order.emplace_back(is_shrink ? 1 : (d_out + kWave * vec - 1) / (kWave * vec), q);
+    order[q] = {is_shrink ? 1 : (d_out + kWave * vec - 1) / (kWave * vec), q};
   }
-  std::stable_sort(order.begin(), order.end(), [](const auto& l, const auto& r) { return l.first < r.first; });
+  bool sorted = true;
+  for (int q = 1; q < n_slots; ++q) sorted = sorted && order[q - 1].first <= order[q].first;
+  if (!sorted)  // (std::stable_sort may allocate; an insertion sort of a few width classes does not)
+    for (int q = 1; q < n_slots; ++q) {
+      const std::pair<int, int> cur = order[q];
+      int k = q;
+      while (k > 0 && order[k - 1].first > cur.first) { order[k] = order[k - 1]; --k; }
+      order[k] = cur;
+    }
   // ... but only when every class keeps a multiple of 8 slots (one slot per XCD, all XCDs alike):
   // a short odd-sized launch costs more in ramp and tail than the empty workgroups it saves.
   bool classes = true;
@@ -943,7 +964,7 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     q0 += nq;
   }
   if (!classes) {  // one class in call order, with the largest chunk count
-    const int max_chunks = order.back().first;
+    const int max_chunks = order[n_slots - 1].first;
     for (int q = 0; q < n_slots; ++q) order[q] = {max_chunks, q};
   }
   for (int q0 = 0; q0 < n_slots;) {
@@ -972,9 +993,6 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     const ItemRec* list = (const ItemRec*)(b->d_img + b->off_items[op][layout]);
     const int n_all = b->n_items[op][layout];
     if (n_all == 0) continue;
-    // one launch over the whole block list, or (longest-first list only) the matrix-core blocks in the
-    // 256-thread kernel followed by the vector-ALU records one per single-wavefront workgroup
-    const bool split = layout == 0 && (panel || (p->split[op] && n_all > b->n_heavy[op]));
     // matrix-core shrink items keep two runs of k-values in flight where that pays: token tiles that
     // are mostly full (prefill), or a long contraction
     bool deep = false;
@@ -985,9 +1003,11 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
       const bool small_launch = (int64_t)nq * (n_all / 4) <= p->deep_max_workgroups;
       deep = p->mfma_shrink_depth == 2 || (p->mfma_shrink_depth == 0 && (b->full_shrink_tiles || max_in > 4096 || small_launch));
     }
+    // one launch over the whole block list, or (panel batches) the matrix-core blocks in the panel kernel
+    // followed by the vector-ALU quads in the ordinary one
     struct Part { const ItemRec* items; int n; int mode; };
-    const Part parts[2] = {{list, split ? b->n_heavy[op] : n_all, panel ? 3 : coop ? 2 : deep ? 3 : 0},
-                           {list + b->n_heavy[op], split ? n_all - b->n_heavy[op] : 0, (panel && !p->split[op]) ? 0 : 1}};
+    const Part parts[2] = {{list, panel ? b->n_heavy[op] : n_all, panel ? kModePanel : coop ? kModeCoop : deep ? kModeDeep : kModeBlocks},
+                           {list + b->n_heavy[op], panel ? n_all - b->n_heavy[op] : 0, kModeBlocks}};
     plora_pool::ProfRec rec{op, nullptr, nullptr};
     if (p->profiling) {
       for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
@@ -1024,6 +1044,32 @@ int plora_expand(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_s
   return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);
 }
 
+int plora_delta(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* x, float* const* v,
+                void* const* y, plora_stream s) {
+  if (!x || !v || !y) return (n_slots == 0 && p && b && b->open && b->pool == p && !p->placement_only) ? PLORA_OK : PLORA_ERR_INVAL;
+  // validate the second half's arguments before anything is queued
+  if (p && n_slots > 0 && slot0 >= 0 && slot0 + n_slots <= p->n_slots)
+    for (int q = 0; q < n_slots; ++q)
+      if (!y[q] || ((uintptr_t)y[q] & 15)) return PLORA_ERR_INVAL;
+  const int rc = run_slots(p, b, slot0, n_slots, x, (void* const*)v, s, true);
+  if (rc != PLORA_OK) return rc;
+  return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);
+}
+
+int plora_delta_static(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* x,
+                       void* const* y, plora_stream s) {
+  if (!p || !b || !b->open || b->pool != p || p->placement_only || p->profiling) return PLORA_ERR_INVAL;
+  if (slot0 < 0 || n_slots < 0 || slot0 + n_slots > p->n_slots) return PLORA_ERR_INVAL;
+  if (n_slots == 0 || b->n_tokens == 0) return PLORA_OK;
+  // one v region per slot of the call, each rounded up to 256 bytes, in the library's static device array
+  const uint64_t per_slot = align_up((uint64_t)b->n_tokens * (uint64_t)p->max_rank * sizeof(float), 256);
+  if (per_slot * (uint64_t)n_slots > static_scratch_bytes()) return PLORA_ERR_LIMIT;
+  void* base = nullptr;
+  HIP_TRY(static_scratch(&base));
+  for (int q = 0; q < n_slots; ++q) p->static_v[q] = (float*)((uint8_t*)base + (uint64_t)q * per_slot);
+  return plora_delta(p, b, slot0, n_slots, x, p->static_v.data(), y, s);
+}
+
 int plora_profile(plora_pool* p, int enable) {
   if (!p || p->placement_only) return PLORA_ERR_INVAL;
   p->profiling = enable != 0;
@@ -1050,6 +1096,18 @@ int plora_batch_end(plora_pool* p, plora_batch* b) {
   if (!p || !b || !b->open || b->pool != p) return PLORA_ERR_INVAL;
   std::shared_ptr<Event> done;
   if (!p->placement_only) {
+    // kernels that ran on other streams: the batch's own stream waits for them, so that its marker
+    // (recorded below or later, but after these waits) stands for all of the batch's kernels
+    for (size_t k = 0; k < b->other_streams.size(); ++k) {
+      if (b->ev_other.size() <= k) {
+        hipEvent_t ev = nullptr;
+        HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        b->ev_other.push_back(ev);
+      }
+      HIP_TRY(hipEventRecord(b->ev_other[k], b->other_streams[k]));
+      HIP_TRY(hipStreamWaitEvent(b->stream, b->ev_other[k], 0));
+    }
+    b->other_streams.clear();
     if (!p->cur_done || p->cur_done->recorded || p->cur_done->stream != b->stream) {
       if (p->cur_done && !p->cur_done->recorded) {  // another stream takes over: close the old marker
         const int rc = record_now(*p->cur_done);

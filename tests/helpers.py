@@ -78,9 +78,10 @@ class Case:
         self.opool.evict(i)
         self.gpool.evict(i)
 
-    def run(self, t2a, slots=None, seed=0, y0_zero=False, check=True, x_std=1.0, share_x=()):
+    def run(self, t2a, slots=None, seed=0, y0_zero=False, check=True, x_std=1.0, share_x=(), y0_fill=None):
         """One batch over `slots` on both sides; returns per-slot dicts with raw outputs.  share_x:
-        groups of positions in `slots` (same d_in) that read one x buffer, as q, k, v of a layer do."""
+        groups of positions in `slots` (same d_in) that read one x buffer, as q, k, v of a layer do.
+        y0_fill: a raw element value that every entry of y0 takes (e.g. the bit pattern of -0)."""
         torch, lay = self.torch, self.lay
         t2a = np.ascontiguousarray(t2a, dtype=np.int32)
         T = len(t2a)
@@ -93,18 +94,21 @@ class Case:
                 xs[j] = xs[group[0]]
         y0 = [np.zeros((T, lay.d_out[s]), RAW_DTYPE[lay.dtype]) if y0_zero else make_act(rng, T, lay.d_out[s], lay.dtype)
               for s in slots]
+        if y0_fill is not None:
+            y0 = [np.full_like(y, y0_fill) for y in y0]
         # GPU side: with the cooperative kernels of small calls; with the panel kernel for every large
-        # group (as in a prefill batch) and two runs in flight in every matrix-core shrink item; and
-        # with the library's own choices last (its outputs are returned).  Each entry: (cooperative limit, panel_min_blocks, mfma_shrink_depth).
-        for coop, panel, depth in getattr(self, "kernel_modes", ((1 << 30, 8, 1), (0, 1, 2), (0, 8, 0))):
+        # group (as in a prefill batch) and two runs in flight in every matrix-core shrink item, through
+        # the one-call form plora_delta; and with the library's own choices last (its outputs are
+        # returned).  Each entry: (cooperative limit, panel_min_blocks, mfma_shrink_depth, entry points).
+        for coop, panel, depth, api in getattr(self, "kernel_modes", ((1 << 30, 8, 1, "pair"), (0, 1, 2, "delta"), (0, 8, 0, "pair"))):
             self.gpool.set_option("coop_max_workgroups_shrink", coop)
             self.gpool.set_option("coop_max_workgroups_expand", coop)
             self.gpool.set_option("panel_min_blocks", panel)
             self.gpool.set_option("mfma_shrink_depth", depth)
-            out = self._run_gpu(t2a, slots, xs, y0, check)
+            out = self._run_gpu(t2a, slots, xs, y0, check, api)
         return out
 
-    def _run_gpu(self, t2a, slots, xs, y0, check):
+    def _run_gpu(self, t2a, slots, xs, y0, check, api="pair"):
         torch, lay = self.torch, self.lay
         T = len(t2a)
         batch = self.gpool.batch_begin(t2a, self.stream)
@@ -125,8 +129,11 @@ class Case:
             j = i
             while j + 1 < len(slots) and slots[j + 1] == slots[j] + 1:
                 j += 1
-            self.gpool.shrink(batch, slots[i], xd[i:j + 1], vd[i:j + 1], self.stream)
-            self.gpool.expand(batch, slots[i], vd[i:j + 1], yd[i:j + 1], self.stream)
+            if api == "delta":
+                self.gpool.delta(batch, slots[i], xd[i:j + 1], vd[i:j + 1], yd[i:j + 1], self.stream)
+            else:
+                self.gpool.shrink(batch, slots[i], xd[i:j + 1], vd[i:j + 1], self.stream)
+                self.gpool.expand(batch, slots[i], vd[i:j + 1], yd[i:j + 1], self.stream)
             i = j + 1
         self.gpool.batch_end(batch)
         torch.cuda.synchronize()

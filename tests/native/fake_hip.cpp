@@ -35,6 +35,7 @@ std::vector<ihipStream_t*> g_streams{&g_null_stream};
 std::vector<ihipEvent_t*> g_dead_events;  // kept: queued operations may still name them
 std::map<void*, size_t> g_host, g_dev;
 bool g_ignore_waits = false;
+int g_copy_fault_in = 0;  // > 0: that many hipMemcpyAsync calls from now, one fails
 
 ihipStream_t* S(hipStream_t st) { return st ? st : &g_null_stream; }
 
@@ -111,6 +112,7 @@ void drain() {
 }
 
 void set_ignore_waits(bool on) { g_ignore_waits = on; }
+void fail_copy_in(int calls) { g_copy_fault_in = calls; }
 
 size_t pending_ops() {
   size_t n = 0;
@@ -127,6 +129,23 @@ hipError_t hipGetLastError(void) { return hipSuccess; }
 hipError_t hipStreamCreateWithFlags(hipStream_t* stream, unsigned int) {
   *stream = new ihipStream_t;
   g_streams.push_back(*stream);
+  return hipSuccess;
+}
+
+// Everything queued on the stream so far has run when this returns (other streams advance as far as
+// that needs).
+hipError_t hipStreamSynchronize(hipStream_t stream) {
+  ihipStream_t* s = S(stream);
+  while (!s->q.empty()) {
+    if (fakehip::step(s)) continue;
+    bool progress = false;  // blocked on a wait: let another stream advance by one operation
+    for (ihipStream_t* o : g_streams)
+      if (o != s && fakehip::step(o)) { progress = true; break; }
+    if (!progress) {
+      std::printf("fake HIP: hipStreamSynchronize on a stream that can never drain\n");
+      std::abort();
+    }
+  }
   return hipSuccess;
 }
 
@@ -239,6 +258,7 @@ hipError_t hipMemcpy(void* dst, const void* src, size_t n, hipMemcpyKind) {
 }
 
 hipError_t hipMemcpyAsync(void* dst, const void* src, size_t n, hipMemcpyKind, hipStream_t stream) {
+  if (g_copy_fault_in > 0 && --g_copy_fault_in == 0) return hipErrorUnknown;  // injected fault: nothing is queued
   Op op;
   op.kind = Op::COPY;
   op.dst = dst;

@@ -24,5 +24,7 @@ int pump_random(uint64_t& rng_state, int max_ops, const std::vector<hipStream_t>
 void drain();
 // All waits become no-ops (to show that a check notices missing ordering).
 void set_ignore_waits(bool on);
+// The `calls`-th hipMemcpyAsync from now fails (hipErrorUnknown) without queueing anything; 0 = none.
+void fail_copy_in(int calls);
 size_t pending_ops();
 }  // namespace fakehip

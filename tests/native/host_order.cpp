@@ -1,6 +1,7 @@
 // Ordering of the library's copies and kernels, checked on the CPU against a stand-in HIP runtime
 // (fake_hip.*) whose streams run only when pumped, in random orders that stream and event semantics
-// allow.  Random histories of loads, evictions and batches on two compute and two copy streams; the
+// allow.  Random histories of loads, evictions and batches on two compute and two copy streams (a
+// batch's kernels sometimes on the compute stream it was not begun on); the
 // stubbed kernels, when they finally run, look at what they would read:
 //   * the batch image must have landed (sane work records),
 //   * every page that a record's page table names must hold the blob of an adapter (and of the very
@@ -21,7 +22,7 @@
 #include "plora_internal.h"
 
 namespace {
-long g_violations = 0, g_kernels_run = 0, g_pages_checked = 0, g_staged_loads = 0;
+long g_violations = 0, g_kernels_run = 0, g_pages_checked = 0, g_staged_loads = 0, g_failed_loads = 0;
 bool g_verbose = true;
 std::shared_ptr<std::set<uint64_t>> g_expect;  // (adapter + 1) << 24 | load generation, of the batch being queued
 int g_elt = 2;
@@ -93,6 +94,10 @@ hipError_t launch_scatter(const uint8_t* staging, uint8_t* slab, int log2_page, 
   });
   return hipSuccess;
 }
+// the static device array of plora_delta_static: plain host memory here
+static unsigned char g_static_scratch[1 << 20];
+uint64_t static_scratch_bytes() { return sizeof(g_static_scratch); }
+hipError_t static_scratch(void** out) { *out = g_static_scratch; return hipSuccess; }
 }  // namespace plora
 
 #define CHECK(c) do { if (!(c)) { std::printf("CHECK failed at line %d: %s\n", __LINE__, #c); std::exit(1); } } while (0)
@@ -126,7 +131,10 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits, int stagin
   float* vs[2] = {(float*)v, (float*)v};
   const float* vsc[2] = {(float*)v, (float*)v};
   void* ys[2] = {y, y};
-  int batches = 0, evictions = 0, busy = 0;
+  int batches = 0, evictions = 0, busy = 0, cross_stream_batches = 0;
+  long failed_loads = 0;
+  hipEvent_t cross = nullptr;
+  CHECK(hipEventCreateWithFlags(&cross, hipEventDisableTiming) == hipSuccess);
   for (int step = 0; step < 600; ++step) {
     const int what = rnd(rng) % 20;
     const int id = rnd(rng) % max_ad;
@@ -139,8 +147,14 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits, int stagin
         blobs.push_back(blob);
         ++gen[id];
         for (uint64_t o = 0; o < S; o += 8) { const uint64_t w = word_of(id, gen[id], o / P); std::memcpy((char*)blob + o, &w, 8); }
+        // now and then one of the load's copies fails after others were queued: the load must be undone
+        // without leaving those copies in flight over pages that the next load may be given
+        const bool fault = rnd(rng) % 8 == 0;
+        if (fault) fakehip::fail_copy_in(1 + (int)(rnd(rng) % 3));
         const int rc = plora_load_adapter(p, id, r, 1.0f, blob, copy[rnd(rng) % 2], nullptr, nullptr);
-        CHECK(rc == PLORA_OK || rc == PLORA_ERR_NOMEM);
+        fakehip::fail_copy_in(0);
+        CHECK(rc == PLORA_OK || rc == PLORA_ERR_NOMEM || (fault && rc == PLORA_ERR_HIP));
+        if (rc == PLORA_ERR_HIP) { ++failed_loads; CHECK(plora_adapter_ready(p, id) == PLORA_ERR_NOTFOUND); }
         if (rc == PLORA_OK) rank_of[id] = r;
       }
     } else if (what < 10) {
@@ -161,13 +175,30 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits, int stagin
         t2a[t] = rnd(rng) % 9 == 0 ? -1 : res[(first + rnd(rng) % n_used) % res.size()];
         if (t2a[t] >= 0) expect->insert(((uint64_t)(t2a[t] + 1) << 24) | (uint64_t)gen[t2a[t]]);
       }
-      hipStream_t st = compute[rnd(rng) % 2];
+      const int which = (int)(rnd(rng) % 2);
+      hipStream_t st = compute[which];
       plora_batch* b = nullptr;
       CHECK(plora_batch_begin(p, t2a.data(), T, st, &b) == PLORA_OK);
       g_expect = expect;
-      CHECK(plora_shrink(p, b, 0, 2, xs, vs, st) == PLORA_OK);
-      if (rnd(rng) % 4 == 0) fakehip::pump_random(rng, 2, prefer);
-      CHECK(plora_expand(p, b, 0, 2, vsc, ys, st) == PLORA_OK);
+      // now and then the kernels run on the other compute stream, ordered after the batch's own by an
+      // event as the contract asks of the caller: plora_batch_end has to cover that stream as well
+      hipStream_t run_on = st;
+      if (rnd(rng) % 3 == 0) {
+        run_on = compute[1 - which];
+        CHECK(hipEventRecord(cross, st) == hipSuccess);
+        CHECK(hipStreamWaitEvent(run_on, cross, 0) == hipSuccess);
+        ++cross_stream_batches;
+      }
+      const int form = (int)(rnd(rng) % 3);
+      if (form == 0) {
+        CHECK(plora_shrink(p, b, 0, 2, xs, vs, run_on) == PLORA_OK);
+        if (rnd(rng) % 4 == 0) fakehip::pump_random(rng, 2, prefer);
+        CHECK(plora_expand(p, b, 0, 2, vsc, ys, st) == PLORA_OK);  // (the expand on the batch's own stream)
+      } else if (form == 1) {
+        CHECK(plora_delta(p, b, 0, 2, xs, vs, ys, run_on) == PLORA_OK);
+      } else {
+        CHECK(plora_delta_static(p, b, 0, 2, xs, ys, run_on) == PLORA_OK);
+      }
       CHECK(plora_batch_end(p, b) == PLORA_OK);
       ++batches;
     } else if (rnd(rng) % 4 == 0) {
@@ -180,11 +211,13 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits, int stagin
   CHECK(plora_pool_stats(p, &stats) == PLORA_OK);
   CHECK(staging == 0 ? stats.staged_loads == 0 : staging == 1 ? stats.staged_loads > 10 : true);
   g_staged_loads += (long)stats.staged_loads;
+  g_failed_loads += failed_loads;
+  CHECK(hipEventDestroy(cross) == hipSuccess);
   CHECK(plora_pool_destroy(p) == PLORA_OK);
   for (void* bl : blobs) CHECK(hipHostFree(bl) == hipSuccess);
   CHECK(hipFree(x) == hipSuccess && hipFree(v) == hipSuccess && hipFree(y) == hipSuccess);
   for (hipStream_t s : {compute[0], compute[1], copy[0], copy[1]}) CHECK(hipStreamDestroy(s) == hipSuccess);
-  CHECK(batches > 100 && evictions > 20);
+  CHECK(batches > 100 && evictions > 20 && cross_stream_batches > 20);
   return g_violations;
 }
 
@@ -202,7 +235,7 @@ int main() {
       }
     }
   total_kernels = g_kernels_run;
-  CHECK(total_kernels > 10000 && g_pages_checked > 10000 && g_staged_loads > 1000);
+  CHECK(total_kernels > 10000 && g_pages_checked > 10000 && g_staged_loads > 1000 && g_failed_loads > 100);
   // the same histories without the runtime honouring waits: the kernels must notice
   g_verbose = false;
   int caught = 0;

@@ -1,10 +1,9 @@
-"""Full-size workloads in the launch configuration bench.py times, checked on sampled outputs.
+"""Full-size workloads in the launch configuration bench.py times, checked element by element.
 
-The oracle cannot run a whole step at these sizes in seconds, so it recomputes sampled
-(slot, token) rows one by one (fp64 accumulation) through its own page pool holding the same
-adapters; page tables and the batch translation are compared in full, and the properties that hold
-at any size (v is zero beyond each token's rank, untouched rows stay untouched) are checked on
-every slot.
+The oracle runs the whole step on all host threads (fp64 accumulation, OpenMP over tokens) through
+its own page pool holding the same adapters: every element of v and of y of every slot is compared,
+page tables and the batch translation are compared in full, and v must be zero beyond each token's
+rank and y untouched for tokens without adapter.
 """
 import time
 
@@ -17,7 +16,7 @@ from helpers import TOL_V, TOL_Y, rel_err, torch_to_raw
 pytestmark = pytest.mark.gpu
 
 
-def _run(oracle_mod, name, n_slots_checked, n_tok_checked):
+def _run(oracle_mod, name, slots_per_call=0):
     import torch
     import bench
     t0 = time.time()
@@ -31,7 +30,7 @@ def _run(oracle_mod, name, n_slots_checked, n_tok_checked):
     # poison v so that unwritten entries show
     for v in w.v:
         v.fill_(float("nan"))
-    w.step(t2a, lay.n_slots)  # one call over all slots, as bench.py does by default
+    w.step(t2a, slots_per_call or lay.n_slots)  # one call over all slots, as bench.py does by default
     torch.cuda.synchronize()
     print("%s: step done" % name, flush=True)
 
@@ -47,52 +46,49 @@ def _run(oracle_mod, name, n_slots_checked, n_tok_checked):
     assert perm.tolist() == o_perm.tolist() and sa.tolist() == o_sa.tolist() and ss.tolist() == o_ss.tolist()
     print("%s: tables and translation match (%d groups)" % (name, len(sa)), flush=True)
 
-    # properties on every slot
+    from oracle.pool import max_threads
+    threads = max_threads()
     rank_of = np.asarray(w.ranks)[t2a]
     col = np.arange(w.max_rank)[None, :]
-    for s in range(lay.n_slots):
-        v = w.v[s].cpu().numpy()[:T]
-        assert not np.isnan(v).any(), "slot %d: v has unwritten entries" % s
-        assert (v[col >= rank_of[:, None]] == 0).all(), "slot %d: v not zero beyond the rank" % s
-
-    # sampled rows: hottest group, a mid group, singletons, first and last token
-    ids, counts = np.unique(t2a, return_counts=True)
-    order = np.argsort(-counts)
-    picks = [ids[order[0]], ids[order[len(order) // 2]], ids[order[-1]], ids[order[-2]]]
-    toks = sorted(set([0, T - 1] + [int(np.nonzero(t2a == a)[0][k]) for a in picks for k in (0, -1)]
-                      + rng.choice(T, size=n_tok_checked, replace=False).tolist()))
-    sel = np.asarray(toks, np.int32)
-    slots = sorted(set([0, lay.n_slots - 1] + rng.choice(lay.n_slots, size=min(n_slots_checked, lay.n_slots),
-                                                        replace=False).tolist()))
     worst_v = worst_y = 0.0
-    for s in slots:
-        x, y0 = w.host_x(s), np.ascontiguousarray(w.host_y0(s))
-        v_ref = op.shrink(s, x, t2a, acc64=True, tok_sel=sel)
-        y_ref = op.expand(s, v_ref, t2a, y0.copy(), acc64=True, tok_sel=sel)
+    t0 = time.time()
+    for s in range(lay.n_slots):
         v_got = w.v[s].cpu().numpy()[:T]
+        assert not np.isnan(v_got).any(), "slot %d: v has unwritten entries" % s
+        assert (v_got[col >= rank_of[:, None]] == 0).all(), "slot %d: v not zero beyond the rank" % s
+        x, y0 = w.host_x(s), np.ascontiguousarray(w.host_y0(s))
+        v_ref = op.shrink(s, x, t2a, acc64=True, threads=threads)
+        y_ref = op.expand(s, v_ref, t2a, y0.copy(), acc64=True, threads=threads)
         y_got = torch_to_raw(w.y[s], lay.dtype)[:T]
-        ev = rel_err(v_got[sel], v_ref[sel])
-        ey = rel_err(from_elt(y_got[sel], lay.dtype), from_elt(y_ref[sel], lay.dtype))
+        ev = rel_err(v_got, v_ref)
+        ey = rel_err(from_elt(y_got, lay.dtype), from_elt(y_ref, lay.dtype))
         worst_v, worst_y = max(worst_v, ev), max(worst_y, ey)
         assert ev <= TOL_V, "slot %d: v error %.3g" % (s, ev)
         assert ey <= TOL_Y[lay.dtype], "slot %d: y error %.3g" % (s, ey)
-    print("%s: %d slots x %d tokens sampled, worst err_v %.3g err_y %.3g" % (name, len(slots), len(sel), worst_v, worst_y),
-          flush=True)
+        if s % 16 == 15:
+            print("%s: slots 0..%d checked (%.1fs)" % (name, s, time.time() - t0), flush=True)
+    print("%s: every element of %d slots x %d tokens checked in %.1fs on %d threads, worst err_v %.3g err_y %.3g" % (
+        name, lay.n_slots, T, time.time() - t0, threads, worst_v, worst_y), flush=True)
     op.close()
     w.close()
 
 
 def test_cfg1_decode_7b_full_size(oracle_mod):
-    _run(oracle_mod, "cfg1", 6, 10)
+    _run(oracle_mod, "cfg1")
+
+
+def test_cfg1_decode_7b_one_layer_per_call(oracle_mod):
+    """The same step as a decoder would issue it: one call per layer (q, k, v, o = 4 slots)."""
+    _run(oracle_mod, "cfg1", slots_per_call=4)
 
 
 def test_cfg2_prefill_full_size(oracle_mod):
-    _run(oracle_mod, "cfg2", 4, 24)
+    _run(oracle_mod, "cfg2")
 
 
 def test_cfg4_decode_13b_layer_full_size(oracle_mod):
-    _run(oracle_mod, "cfg4", 6, 10)
+    _run(oracle_mod, "cfg4")
 
 
 def test_cfg5_decode_gqa_projections_full_size(oracle_mod):
-    _run(oracle_mod, "cfg5", 6, 10)
+    _run(oracle_mod, "cfg5")

@@ -2,7 +2,7 @@
 import numpy as np
 import pytest
 
-from workload import (CONFIGS, DT_BF16, DT_F16, DT_F32, Layout, config_layout, draw_tok2adapter)
+from workload import (CONFIGS, DT_BF16, DT_F16, DT_F32, Layout, config_layout, draw_tok2adapter, from_elt)
 from helpers import Case
 
 pytestmark = pytest.mark.gpu
@@ -16,13 +16,11 @@ def test_cfg0_small_workload(oracle_mod):
     rng = np.random.default_rng(cfg["seed"])
     t2a = draw_tok2adapter(rng, cfg["tokens"], np.arange(4), s=None)
     print("cfg0 t2a", t2a.tolist(), flush=True)
-    for mfma, major, remap, split in ((0, -1, 1, 0), (1, 0, 1, 1), (4, 1, 1, 1), (2, 0, 0, 0), (1, 1, 0, 0)):
+    for mfma, major, remap in ((0, -1, 1), (1, 0, 1), (4, 1, 1), (2, 0, 0), (1, 1, 0)):
         case.set_mfma(mfma, 0 if mfma == 4 else mfma)
         if major >= 0:  # -1: the library's own geometry (shrink: slots fastest if a multiple of 8, expand: chunks fastest)
             case.gpool.set_option("slot_major", major)
         case.gpool.set_option("xcd_remap", remap)
-        case.gpool.set_option("split_shrink", split)
-        case.gpool.set_option("split_expand", 1 - split if major == 1 else split)
         out = case.run(t2a, seed=1)
         print("mfma_min", mfma, "err_v %.3g err_y %.3g" % (out[0]["err_v"], out[0]["err_y"]), flush=True)
         out = case.run(t2a, seed=2, y0_zero=True)
@@ -43,7 +41,6 @@ def test_ragged_multi_slot(oracle_mod, dtype, mfma, major):
                 mfma_min_tokens=mfma)
     if major >= 0:
         case.gpool.set_option("slot_major", major)
-    case.gpool.set_option("split_shrink", 1 if mfma == 3 else 0)
     # scatter: evict two adapters and reload them so that their pages interleave
     case.evict(0)
     case.evict(6)
@@ -187,7 +184,7 @@ def test_matrix_core_shrink_with_one_and_two_runs_in_flight(oracle_mod, dtype):
     np.random.default_rng(78).shuffle(t2a)
     got = {}
     for depth in (1, 2):
-        case.kernel_modes = ((0, 8, depth),)
+        case.kernel_modes = ((0, 8, depth, "pair"),)
         out = case.run(t2a, seed=3)
         got[depth] = [o["v_got"].copy() for o in out]
     for a, b in zip(got[1], got[2]):
@@ -333,4 +330,102 @@ def test_staged_loads_put_the_same_bytes_in_the_same_pages(oracle_mod, page_byte
     ids = np.array([n_fill + k for k in range(len(big_ranks))] + [1, 3], dtype=np.int32)
     t2a = ids[rng.integers(0, len(ids), size=24)].astype(np.int32)
     case.run(t2a, seed=9)
+    case.close()
+
+
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F16, DT_F32])
+def test_zero_and_negative_scale_and_signed_zero_y(oracle_mod, dtype):
+    """Scale 0 (the delta vanishes: y keeps its value, and only the sign of a zero may change), scale
+    < 0, y0 = +0 and y0 = -0 everywhere; vector-ALU and matrix-core items (Eq. 1 with the per-adapter
+    scale applied once in fp32)."""
+    lay = Layout((520, 256), (264, 1024), dtype)
+    ranks = [8, 16, 40, 64, 5]
+    scales = [0.0, -2.0, -0.125, 0.0, 1.5]
+    case = Case(oracle_mod, lay, ranks, scales, 8192, 256, seed=91)
+    rng = np.random.default_rng(92)
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in zip(range(5), (21, 40, 3, 1, 18))] + [np.full(2, -1, np.int32)])
+    rng.shuffle(t2a)
+    minus_zero = np.float32(-0.0) if dtype == DT_F32 else np.uint16(0x8000)
+    for mfma in (0, 2):
+        case.set_mfma(mfma)
+        for kw in (dict(), dict(y0_zero=True), dict(y0_fill=minus_zero)):
+            out = case.run(t2a, seed=5, **kw)
+            for o in out:
+                zero_scale = np.isin(t2a, [0, 3])
+                got, y0 = from_elt(o["y_got"], dtype), from_elt(o["y0"], dtype)
+                # zero scale: y keeps its value, bit for bit, except that a -0 may come back as +0
+                # (-0 + (+0) = +0; which zero the product 0 * acc is depends on the sign of acc)
+                assert (got[zero_scale] == y0[zero_scale]).all()
+                keeps_bits = (o["y_got"][zero_scale] == o["y0"][zero_scale]) | (y0[zero_scale] == 0)
+                assert keeps_bits.all()
+        print("scales dtype", dtype, "mfma", mfma, "ok", flush=True)
+    case.close()
+
+
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F16])
+@pytest.mark.parametrize("x_std", [1.0 / 64, 64.0, 1e-4, 3e3])
+def test_activations_far_from_unit_scale(oracle_mod, dtype, x_std):
+    """v = x A^T scales with x: rows of v of magnitude 1e-4 .. 3e3 through the vector-ALU items and
+    through the matrix-core expand, which feeds v to the matrix cores as 16-bit halves (fp16: after a
+    per-row power-of-two scaling)."""
+    lay = Layout((1024,), (520,), dtype)
+    ranks = [8, 32, 64, 24]
+    # a large scale on one adapter pushes |v| further out; y0 = 0 so that y itself stays finite in fp16
+    case = Case(oracle_mod, lay, ranks, [1.0, 0.25, 1.0 / 64, 2.0], 16384, 64, seed=95)
+    rng = np.random.default_rng(96)
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in zip(range(4), (17, 70, 5, 2))])
+    rng.shuffle(t2a)
+    if dtype == DT_F16 and x_std > 60:
+        x_std = min(x_std, 600.0)  # x itself must stay below 65504 after 4-sigma draws
+    for mfma in (0, 1):
+        case.set_mfma(mfma)
+        out = case.run(t2a, seed=6, x_std=x_std, y0_zero=True)
+        vmax = float(np.abs(out[0]["v_ref"]).max())
+        print("x_std %g dtype %d mfma %d: max|v| %.3g err_v %.2g err_y %.2g" % (x_std, dtype, mfma, vmax, out[0]["err_v"], out[0]["err_y"]), flush=True)
+        assert np.isfinite(from_elt(out[0]["y_got"], dtype)).all() == np.isfinite(from_elt(out[0]["y_ref"], dtype)).all()
+    case.close()
+
+
+def test_fp16_rows_of_v_beyond_fp16_range(oracle_mod):
+    """fp16 elements; rows of v from 2^-17 to 2^18 in one batch (fp16 itself holds 2^-14 .. 65504 with
+    full precision): adapter 0 has A sixteen times the usual size and tokens of magnitude 2^-8 .. 2^14,
+    adapter 1 has A a sixteenth of it and tokens of magnitude 2^-13 .. 2^-11; the adapters' scales
+    bring the deltas back into fp16's range.  The matrix-core expand must neither overflow the large
+    rows nor lose the small ones (each row has its own power-of-two scale), checked row by row."""
+    from workload import make_adapters, slot_views, to_elt
+    from helpers import rel_err
+    lay = Layout((4096,), (512,), DT_F16)
+    ranks = [32, 16]
+    blobs = make_adapters(97, lay, ranks)
+    for blob, r, f in zip(blobs, ranks, (16.0, 1.0 / 16)):
+        A, _ = slot_views(lay, r, blob)[0]
+        A[:] = to_elt(from_elt(A, DT_F16) * np.float32(f), DT_F16)
+    case = Case(oracle_mod, lay, ranks, [2.0 ** -8, 2.0 ** 12], 16384, 64, seed=97, blobs=blobs)
+    case.set_mfma(1)
+    T0, T1 = 40, 9
+    t2a = np.concatenate([np.zeros(T0, np.int32), np.ones(T1, np.int32)])
+    rng = np.random.default_rng(98)
+    mags = np.concatenate([np.float32(2.0) ** rng.integers(-8, 15, size=T0).astype(np.float32),
+                           np.float32(2.0) ** rng.integers(-13, -10, size=T1).astype(np.float32)])
+    mags[0], mags[1] = 2.0 ** 14, 2.0 ** -8
+    order = rng.permutation(T0 + T1)
+    t2a, mags = t2a[order], mags[order]
+    x = np.clip(rng.standard_normal((T0 + T1, 4096), dtype=np.float32), -3.5, 3.5) * mags[:, None]
+    xs = [to_elt(x, DT_F16)]
+    y0 = [np.zeros((T0 + T1, 512), np.uint16)]
+    for coop, panel, depth, api in ((0, 8, 0, "pair"), (0, 1, 2, "delta")):
+        case.gpool.set_option("coop_max_workgroups_shrink", coop)
+        case.gpool.set_option("coop_max_workgroups_expand", coop)
+        case.gpool.set_option("panel_min_blocks", panel)
+        case.gpool.set_option("mfma_shrink_depth", depth)
+        out = case._run_gpu(t2a, [0], xs, y0, False, api)[0]
+        vmax = np.abs(out["v_ref"]).max(axis=1)
+        print("fp16 wide rows (panel_min_blocks %d): max|v| per token from %.3g to %.3g" % (panel, vmax.min(), vmax.max()), flush=True)
+        assert vmax.max() > 4 * 65504 and vmax.min() < 2.0 ** -14
+        got, ref = from_elt(out["y_got"], DT_F16), from_elt(out["y_ref"], DT_F16)
+        assert np.isfinite(ref).all() and np.isfinite(got).all()
+        worst = max(rel_err(got[t], ref[t]) for t in range(T0 + T1))
+        print("   worst row error %.3g" % worst, flush=True)
+        for t in range(T0 + T1):
+            assert rel_err(got[t], ref[t]) <= 1e-2, "token %d (max|v| %.3g): %.3g" % (t, vmax[t], rel_err(got[t], ref[t]))
     case.close()
