@@ -26,11 +26,57 @@ from workload import (CONFIGS, RAW_DTYPE, config_layout, draw_ranks, draw_tok2ad
 
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # HBM bytes per launch of the (shrink, expand) kernels measured with rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE (scaled by the factors found on a copy kernel of known size: 2.0 and 1.0); sources:
-# profiles/decode_7b_cfg1_*.md, profiles/decode_13b_layer_cfg4_*.md, profiles/prefill_cfg2_*.md
-MEASURED_TRAFFIC = {"cfg1": (1.813e9, 2.100e9), "cfg4": (2.318e9, 2.452e9), "cfg2": (0.274e9, 0.400e9)}
+# WRITE_SIZE on the default draw of each workload, all slots per call (the profile named holds the
+# commands and the scaling factors found on a copy kernel of known size).  Each entry carries the
+# digest of the kernel and host sources it was measured on (kernel_sources_digest below): the
+# figure is reported only while the sources are still those, and null as soon as they change.
+MEASURED_TRAFFIC = {
+    "cfg1": dict(shrink=1.813e9, expand=2.100e9, profile="profiles/decode_7b_cfg1_kernels_and_hbm_traffic.md", sources=None),
+    "cfg4": dict(shrink=2.318e9, expand=2.452e9, profile="profiles/decode_13b_layer_cfg4_kernels_and_hbm_traffic.md", sources=None),
+    "cfg2": dict(shrink=0.274e9, expand=0.400e9, profile="profiles/prefill_cfg2_kernels_traffic_and_mfma_activity.md", sources=None),
+}
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
 KCLASS = ["shrink", "expand"]
+
+
+def kernel_sources_digest():
+    """sha256 (first 16 hex digits) over the sources that decide what the kernels do and how they are launched."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in ("plora_kernels.hip", "plora_pool.cpp", "plora_internal.h"):
+        with open(os.path.join(ROOT, "paper_2512_20210_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def measured_traffic(workload, kclass, default_draw):
+    """(bytes per launch, profile) from MEASURED_TRAFFIC if it still describes the code that runs, else (None, None)."""
+    rec = MEASURED_TRAFFIC.get(workload)
+    if not rec or not default_draw or rec["sources"] != kernel_sources_digest():
+        return None, None
+    return int(rec[kclass]), rec["profile"]
+
+
+def streaming_probes(P, stream, lay, ab):
+    """What bare kernels reach on this GPU, for the roofline line: a plain streaming read, the same with
+    a read-modify-write stream mixed in at the ratio of this workload's expand (weight bytes : y bytes),
+    and one large pinned host -> device copy."""
+    out = {}
+    rc, ms = P.plora_probe_stream(2 << 30, 0, 64 << 10, 0, 20, stream)
+    if rc == 0:
+        out["read_gbs"] = round((2 << 30) / ms / 1e6, 1)
+    # weights : y read (= y written) of the expand, per 4 KiB of y
+    w_per_y = ab["expand_weights"] / max(ab["expand_y_read"], 1)
+    w_tile = max(1, int(round(w_per_y))) * 4096
+    n_tiles = max(1, (2 << 30) // (w_tile + 2 * 4096))
+    rc, ms = P.plora_probe_stream(n_tiles * w_tile, n_tiles * 4096, w_tile, 4096, 20, stream)
+    if rc == 0:
+        out["read_plus_rmw_gbs"] = round(n_tiles * (w_tile + 2 * 4096) / ms / 1e6, 1)
+        out["read_plus_rmw_mix"] = "%d KiB read : 4 KiB read-modify-write" % (w_tile // 1024)
+    rc, ms = P.plora_probe_h2d(1 << 30, 3, stream)
+    if rc == 0:
+        out["h2d_single_pinned_copy_gbs"] = round((1 << 30) / ms / 1e6, 2)
+    return out
 
 
 SEED_OFFSET = 0  # --seed-offset: another draw of ranks, weights, activations and batches
@@ -73,15 +119,18 @@ def algorithmic_bytes(lay, ranks, t2a, slots, share_qkv_x=False):
     sum_r_u = int(sum(int(ranks[u]) for u in uniq))
     sum_r_t = int(sum(int(ranks[i]) for i in t2a[has]))
     shrink = expand = 0
-    flops = 0
+    flops = ew = ey = 0
     for s in slots:
         di, do = lay.d_in[s], lay.d_out[s]
         meta = 4 * Tn
         x_bytes = 0 if share_qkv_x and shares_x_with_earlier_slot(lay, s) else Tn * di * elt
         shrink += sum_r_u * di * elt + x_bytes + sum_r_t * 4 + meta
         expand += sum_r_u * do * elt + 2 * Tn * do * elt + sum_r_t * 4 + meta
+        ew += sum_r_u * do * elt
+        ey += Tn * do * elt
         flops += 2 * sum_r_t * (di + do)
-    return dict(shrink=shrink, expand=expand, total=shrink + expand, flops=flops, n_unique=len(uniq), tokens=Tn)
+    return dict(shrink=shrink, expand=expand, total=shrink + expand, flops=flops, n_unique=len(uniq), tokens=Tn,
+                expand_weights=ew, expand_y_read=ey)
 
 
 class GpuWorkload:
@@ -245,34 +294,9 @@ def cpu_baseline(w, t2a, budget_s=15.0):
                 tokens_per_s=len(t2a) / (per_slot * lay.n_slots), seconds=t_total)
 
 
-class _PoolForManager:
-    """Adapts PagedLoraPool to the manager's load/evict interface and samples utilisation."""
-
-    def __init__(self, pool, lay):
-        self.pool, self.lay = pool, lay
-        self.filled = False
-        self.page_util, self.byte_util = [], []
-
-    def load(self, aid, rank, scale, blob, stream=None):
-        try:
-            pt = self.pool.load(aid, rank, scale, blob, stream)
-        except Exception as e:
-            if getattr(e, "code", None) == -2:
-                self.filled = True
-            raise
-        if self.filled:  # sampled after every load once the pool has first run out of pages
-            st = self.pool.stats()
-            self.page_util.append(st["used_pages"] / st["n_pages"])
-            self.byte_util.append(st["resident_bytes"] / (st["n_pages"] * st["page_bytes"]))
-        return pt
-
-    def evict(self, aid):
-        self.pool.evict(aid)
-
-
 def churn_setup(name="cfg3", blobs_per_rank=8, pinned=None):
     """Pool, shared pinned blobs (blobs_per_rank distinct weight sets per rank; made unless given) and
-    the request trace."""
+    the request trace (windows; long enough for the configured number of load / evict events)."""
     import torch
     import paper_2512_20210_amd as P
     from workload import churn_trace, make_adapter
@@ -287,29 +311,29 @@ def churn_setup(name="cfg3", blobs_per_rank=8, pinned=None):
             make_adapter(rng, lay, r, out=t.numpy().view(np.uint16))
             pinned[(r, k)] = t
     pool = P.PagedLoraPool(page_bytes, n_pages, lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
-    trace = churn_trace(np.random.default_rng(cfg["seed"] + 1), cfg["n_events"], pop, cfg["zipf"], cfg["window"],
-                        cfg["burst_prob"], cfg["burst_mult"])
+    trace = churn_trace(np.random.default_rng(cfg["seed"] + 1), cfg.get("max_requests", cfg["n_events"]), pop, cfg["zipf"],
+                        cfg["window"], cfg["burst_prob"], cfg["burst_mult"])
     return cfg, lay, ranks, scales, pool, pinned, trace
 
 
-def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
-    """One pass over the churn trace.  quality None: adapters are loaded on demand only; a number: the
-    prefetch manager runs on a synthetic prediction of that quality before every window; "lstm": on the
-    library's predictor, which learns online from the windows it has seen."""
+def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality, stop_on="events"):
+    """One pass over the churn trace, driven by the library's residency policy (plora_manager_*).  quality
+    None: adapters are loaded on demand only; a number: threshold prefetching on a synthetic prediction
+    of that quality before every window; "lstm": on the library's predictor, which learns online from
+    the windows it has seen.  stop_on "events": the pass ends with the window in which the number of
+    loads + evictions reaches cfg["n_events"]; "requests": after cfg["n_events"] requests."""
     import torch
-    from paper_2512_20210_amd.prefetch import PrefetchManager, SyntheticPredictor
-    from workload import zipf_probs
+    import paper_2512_20210_amd as P
+    from workload import SyntheticPredictor, zipf_probs
     pop, T = cfg["population"], cfg["tokens"]
     k_blobs = len(pinned) // len(set(int(x) for x in ranks))
     copy_stream, prefetch_stream = torch.cuda.Stream(), torch.cuda.Stream()
     stream = torch.cuda.current_stream().cuda_stream
-    pm = _PoolForManager(pool, lay)
     popularity = zipf_probs(pop, cfg["zipf"])
-    mgr = PrefetchManager(pm, ranks, scales, lambda i: pinned[(int(ranks[i]), i % k_blobs)],
-                          p_hat=popularity / popularity.max(), copy_stream=copy_stream.cuda_stream,
-                          prefetch_stream=prefetch_stream.cuda_stream)
+    mgr = P.ResidencyManager(pool, ranks, scales, lambda i: pinned[(int(ranks[i]), i % k_blobs)],
+                             copy_stream=copy_stream.cuda_stream, prefetch_stream=prefetch_stream.cuda_stream)
+    mgr.set_prediction(popularity / popularity.max())
     if quality == "lstm":
-        import paper_2512_20210_amd as P
         pred = P.LstmPredictor(pop, window=cfg.get("lstm_window", 8), hidden=64, layers=2, replay=10000, batch=64,
                                lr=cfg.get("lstm_lr", 1e-3), seed=cfg["seed"] + 13, train_steps=cfg.get("lstm_steps", 1),
                                threads=min(16, os.cpu_count() or 1))
@@ -318,8 +342,9 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
     per_window = []       # (requests, cold starts, |predicted & requested|, |predicted|, |requested|) per window
     pred_s = 0.0
     rng = np.random.default_rng(cfg["seed"] + 7)
-    x = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_in]
-    y = [torch.from_numpy(to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16)).cuda() for d in lay.d_out]
+    base = {d: to_elt(rng.standard_normal((T, d), dtype=np.float32), lay.dtype).view(np.int16) for d in set(lay.d_in) | set(lay.d_out)}
+    x = [torch.from_numpy(np.roll(base[d], s, axis=0)).cuda() for s, d in enumerate(lay.d_in)]
+    y = [torch.from_numpy(np.roll(base[d], -s - 1, axis=0)).cuda() for s, d in enumerate(lay.d_out)]
     v = [torch.empty((T, cfg["max_rank"]), dtype=torch.float32, device="cuda") for _ in lay.d_in]
     slots = list(range(lay.n_slots))
     pool.profile(True)
@@ -327,18 +352,25 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
     kbytes = 0
     pending, ttr_ms = {}, []   # cold misses whose copy is still running -> host time of the request
     prefetched_ready = prefetched_first_use = 0
+    cold = 0
 
     def poll():
         now = time.perf_counter()
         for a in list(pending):
-            if a not in mgr.last_use:   # became ready and was evicted again between two polls
+            if not mgr.state(a) & 1:    # became ready and was evicted again between two polls
                 del pending[a]
             elif pool.ready(a):
                 ttr_ms.append((now - pending.pop(a)) * 1e3)
+
+    def done():
+        if stop_on == "requests":
+            return events >= cfg["n_events"]
+        st = pool.stats()
+        return st["loads"] + st["evictions"] >= cfg["n_events"]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for win in trace:
-        cold0, ev0 = mgr.cold_starts, events
+        cold0, ev0 = cold, events
         hit_pred = n_pred = 0
         if pred is not None:  # between two decode batches: the copies run beside the next batch's kernels
             tp = time.perf_counter()
@@ -346,21 +378,22 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
             pred_s += time.perf_counter() - tp
             flagged = set(np.nonzero(p_hat > mgr.theta)[0].tolist())
             hit_pred, n_pred = len(flagged & set(int(a) for a in win)), len(flagged)
-            mgr.begin_interval(p_hat)
+            mgr.prefetch(p_hat)
         for aid in win:
             aid = int(aid)
-            if aid in mgr.prefetched:
+            if mgr.state(aid) & 2:
                 prefetched_first_use += 1
                 prefetched_ready += bool(pool.ready(aid))
-            if not mgr.request(aid) and aid in mgr.last_use:
-                pending[aid] = time.perf_counter()
+            if not mgr.request(aid):
+                cold += 1
+                if mgr.state(aid) & 1:
+                    pending[aid] = time.perf_counter()
             if pending:
                 poll()
             events += 1
-            if events >= cfg["n_events"]:
+            if stop_on == "requests" and events >= cfg["n_events"]:
                 break
-        res = np.fromiter(mgr.resident(), dtype=np.int32)
-        res.sort()
+        res = mgr.residents()
         p = popularity[res] / popularity[res].sum()
         t2a = res[rng.choice(len(res), size=T, p=p)].astype(np.int32)
         b = pool.batch_begin(t2a, stream)
@@ -369,27 +402,29 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
         pool.batch_end(b)
         kbytes += algorithmic_bytes(lay, ranks, t2a, slots)["total"]
         batches += 1
-        per_window.append((events - ev0, mgr.cold_starts - cold0, hit_pred, n_pred, len(set(int(a) for a in win))))
-        if events >= cfg["n_events"]:
+        per_window.append((events - ev0, cold - cold0, hit_pred, n_pred, len(set(int(a) for a in win))))
+        if done():
             break
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     poll()
     kms, kn = pool.profile_read()
-    st = pool.stats()
+    st, ms = pool.stats(), mgr.stats()
+    n_util = max(ms["util_samples"], 1)
     out = {
-        "prediction_quality": quality, "events": events, "decode_batches": batches, "wall_s": round(wall, 3),
-        "page_util_avg": round(float(np.mean(pm.page_util)), 4), "page_util_min": round(float(np.min(pm.page_util)), 4),
-        "byte_util_avg": round(float(np.mean(pm.byte_util)), 4), "byte_util_min": round(float(np.min(pm.byte_util)), 4),
-        "hit_rate": round(mgr.hits / max(1, mgr.hits + mgr.misses), 4),
-        "cold_start_rate": round(mgr.cold_starts / max(1, events), 4),
+        "prediction_quality": quality, "requests": events, "load_plus_evict_events": st["loads"] + st["evictions"],
+        "decode_batches": batches, "wall_s": round(wall, 3),
+        "page_util_avg": round(ms["page_util_sum"] / n_util, 4), "page_util_min": round(ms["page_util_min"], 4),
+        "byte_util_avg": round(ms["byte_util_sum"] / n_util, 4), "byte_util_min": round(ms["byte_util_min"], 4),
+        "hit_rate": round(ms["hits"] / max(1, ms["hits"] + ms["misses"]), 4),
+        "cold_start_rate": round(ms["misses"] / max(1, events), 4),
         "cold_time_to_ready_ms_mean": round(float(np.mean(ttr_ms)), 3) if ttr_ms else None,
         "cold_time_to_ready_ms_p95": round(float(np.percentile(ttr_ms, 95)), 3) if ttr_ms else None,
-        "prefetch_loads": mgr.prefetch_loads, "useful_prefetches": mgr.useful_prefetches,
-        "wasted_prefetches": mgr.wasted_prefetches,
+        "prefetch_loads": ms["prefetch_loads"], "useful_prefetches": ms["useful_prefetches"],
+        "wasted_prefetches": ms["wasted_prefetches"],
         "prefetched_ready_at_first_use": round(prefetched_ready / max(1, prefetched_first_use), 4) if pred is not None else None,
         "loads": st["loads"], "evictions": st["evictions"],
-        "skipped_busy_victims": mgr.skipped_busy, "failed_loads": mgr.failed,
+        "skipped_busy_victims": ms["skipped_busy"], "host_waits_for_a_busy_victim": ms["waited_for_busy"], "failed_loads": ms["failed_loads"],
         "h2d_gb": round(st["h2d_bytes"] / 1e9, 2), "h2d_copies": st["h2d_copies"],
         "h2d_gbs_copy_time": round(st["h2d_bytes"] / 1e6 / max(st["h2d_ms"], 1e-9), 2),
         "h2d_gbs_wall": round(st["h2d_bytes"] / 1e9 / wall, 2),
@@ -406,6 +441,7 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality):
         out["predictor_ms_per_window"] = round(pred_s / max(len(per_window), 1) * 1e3, 3)
     if quality == "lstm":
         pred.close()
+    mgr.close()
     return out
 
 
@@ -477,16 +513,22 @@ def run_churn_periodic(args):
         cfg, lay, ranks, scales, pool, pinned, _ = churn_setup("cfg3p", pinned=pinned)
         trace = periodic_trace(np.random.default_rng(cfg["seed"] + 1), cfg["n_events"] // cfg["window"], cfg["population"],
                                cfg["zipf"], cfg["window"], cfg["n_periodic"], cfg["periods"])
-        out["passes"].append(_churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality))
+        out["passes"].append(_churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality, stop_on="requests"))
         pool.close()
     print(json.dumps(out))
 
 
 def run_churn(args):
-    """cfg3: load/evict churn interleaved with decode batches; utilisation, H2D and kernel rates, once
-    with loads on demand only and once with threshold prefetching on a synthetic prediction."""
+    """cfg3: load/evict churn interleaved with decode batches until 10,000 loads + evictions have
+    happened; utilisation, H2D and kernel rates, with loads on demand only and with threshold
+    prefetching on a synthetic prediction (direct and staged copies); then the same for the reading in
+    which an adapter covers all 32 layers (cfg3L: 8 .. 256 MiB per adapter, about two dozen resident)."""
+    import paper_2512_20210_amd as P
     out = {"metric": "pool utilisation under churn + H2D prefetch GB/s + decode kernel GB/s + cold starts",
-           "workload": "cfg3", "passes": []}
+           "workload": "cfg3", "passes": [], "passes_32_layer_adapters": []}
+    rc, ms = P.plora_probe_h2d(1 << 30, 3, None)
+    if rc == 0:
+        out["h2d_single_pinned_copy_gbs"] = round((1 << 30) / ms / 1e6, 2)
     pinned = None
     for quality, staged in ((None, False), (0.86, False), (0.86, True)):
         cfg, lay, ranks, scales, pool, pinned, trace = churn_setup("cfg3", pinned=pinned)
@@ -495,6 +537,11 @@ def run_churn(args):
         res = _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality)
         res["staged_loads"] = pool.stats()["staged_loads"]
         out["passes"].append(res)
+        pool.close()
+    pinned = None
+    for quality in (None, 0.86):
+        cfg, lay, ranks, scales, pool, pinned, trace = churn_setup("cfg3L", blobs_per_rank=1, pinned=pinned)
+        out["passes_32_layer_adapters"].append(_churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality))
         pool.close()
     print(json.dumps(out))
 
@@ -511,7 +558,8 @@ def main():
     ap.add_argument("--xcd-remap", type=int, default=-1)
     ap.add_argument("--coop-max-workgroups", type=int, default=-1,
                     help="calls of at most this many workgroups use the cooperative kernels (library defaults 192 for "
-                         "shrink, 400 for expand; 0 = never)")
+                         "shrink, 2500 for expand; 0 = never)")
+    ap.add_argument("--no-probes", action="store_true", help="skip the streaming / copy probes and the per-layer-call leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--share-qkv-x", action="store_true", help="k and v slots of a layer read the q slot's x buffer (as in a transformer layer); x is then counted once per group")
@@ -592,9 +640,11 @@ def main():
         avg_ms = kms[dom] / kn[dom]
         per_launch = kb / kn[dom]
         ach = per_launch / (avg_ms * 1e-3) / 1e9
-        traffic = MEASURED_TRAFFIC.get(args.workload) if spc == lay.n_slots and SEED_OFFSET == 0 and not args.share_qkv_x else None  # measured on the default draw
+        default_draw = spc == lay.n_slots and SEED_OFFSET == 0 and not args.share_qkv_x
+        traffic, traffic_profile = measured_traffic(args.workload, KCLASS[dom], default_draw)
         roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=int(traffic[dom]) if traffic else None, avg_launch_ms=round(avg_ms, 5),
+                    frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic, traffic_profile=traffic_profile,
+                    kernel_sources=kernel_sources_digest(), avg_launch_ms=round(avg_ms, 5),
                     launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
                     all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(2) if kn[k]})
 
@@ -615,6 +665,31 @@ def main():
         "pool_page_util": round(w.stats_after_load["used_pages"] / w.stats_after_load["n_pages"], 4),
         "roofline": roof,
     }
+    if not args.no_probes:
+        # the same steps as a layer-by-layer decoder has to issue them: one call per layer (4 slots)
+        if lay.n_slots > 4 and lay.n_slots % 4 == 0 and spc == lay.n_slots:
+            n = min(args.steps, 200)
+            for i in range(10):
+                w.step(timed[i % len(timed)], 4)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for i in range(n):
+                w.step(timed[i % len(timed)], 4)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            b4 = sum(ab[i % len(timed)]["total"] for i in range(n))
+            out["per_layer_calls"] = {"slots_per_call": 4, "steps": n, "ms_per_step": round(dt / n * 1e3, 4),
+                                      "value": round(b4 / dt / 1e9, 1), "unit": "GB/s",
+                                      "pct_of_hbm_peak": round(100.0 * b4 / dt / 1e9 / HBM_PEAK_GBS, 2),
+                                      "tokens_per_s": round(sum(len(timed[i % len(timed)]) for i in range(n)) / dt, 1)}
+        probes = streaming_probes(w.P, w.stream, lay, ab[0])
+        out["streaming_roof"] = probes
+        if probes.get("read_gbs"):
+            out["pct_of_streaming_roof"] = round(100.0 * gbs / probes["read_gbs"], 2)
+        if roof is not None and probes.get("read_plus_rmw_gbs"):
+            roof["frac_of_probe"] = round(roof["achieved"] / (probes["read_plus_rmw_gbs"] if roof["kernel"] == "expand" else probes["read_gbs"]), 4)
+        if probes.get("h2d_single_pinned_copy_gbs"):
+            out["h2d_pct_of_single_pinned_copy"] = round(100.0 * out["h2d_prefetch_gbs"] / probes["h2d_single_pinned_copy_gbs"], 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, timed[0])
     w.close()

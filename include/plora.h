@@ -109,6 +109,9 @@ int plora_adapter_ready(plora_pool* pool, int32_t id);
 /* Makes `stream` wait (device side) until the adapter's copies have completed. */
 int plora_wait_adapter(plora_pool* pool, int32_t id, plora_stream stream);
 
+/* Blocks the calling host thread until the adapter's copies have completed. */
+int plora_sync_adapter(plora_pool* pool, int32_t id);
+
 /* Return the adapter's pages to the free set (Sec. III-B "Eviction Policy": the mechanism).  The
  * pages are allocatable at once.  NOTFOUND; BUSY if the load has not completed or an open batch
  * names the adapter. */
@@ -225,6 +228,89 @@ int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
  * ms and launches: host, 2 entries each. */
 int plora_profile(plora_pool* pool, int enable);
 int plora_profile_read(plora_pool* pool, double* ms, uint64_t* launches);
+
+/* ---------------------------------------------------------------------------------------------
+ * Residency policy (Sec. III-B), host code on top of a pool: load on demand, eviction by the score of
+ * Eq. 3, threshold prefetching ("Proactive Prefetching").  The paper gives neither weights nor
+ * normalisation nor direction of Eq. 3 and no value of theta; this library reads them as follows.
+ *   s_i = alpha * LRU_i + beta * freq_i + gamma * p_hat_i is a retention value: when the pool is out
+ *   of pages the resident adapter with the LOWEST score is evicted first, equal scores by lowest id.
+ *   LRU_i = k / (n - 1) where k is the adapter's position among the n residents ordered by the clock of
+ *   their last request, oldest first (equal clocks by id; n = 1: LRU = 1).  freq_i = requests for i
+ *   among the last `window` requests, divided by the largest such count among the residents (at
+ *   least 1).  p_hat_i = the latest prediction handed over (0 before the first).  The clock counts
+ *   requests.  The scores are evaluated in double precision, ((alpha*LRU) + (beta*freq)) + (gamma*p),
+ *   once per load that finds the pool full; victims are then taken in that order until the load fits.
+ *   Residents that plora_evict reports BUSY (their own copy is still running, or an open batch uses them)
+ *   are passed over; if a load on demand finds nothing else to evict, the host waits for the copy of the
+ *   lowest-scored such resident and evicts that one (the request could not be served before its own
+ *   load anyway); a prefetch never waits.
+ *   Prefetching: adapters with p_hat_i > theta that are not resident are loaded, most probable first
+ *   (equal probabilities by id); room is made with the same score but only among residents with
+ *   p_hat <= theta, and when none of those is left the remaining prefetches are dropped.
+ * Every pointer is a host pointer.  Not thread safe.  The pool must outlive the manager, and adapters
+ * the manager handles must not be loaded or evicted behind its back. */
+typedef struct plora_manager plora_manager;
+typedef struct {
+  double alpha, beta, gamma; /* weights of Eq. 3, each >= 0 */
+  double theta;              /* prefetch threshold on p_hat, 0 .. 1 */
+  int32_t window;            /* requests the frequency term looks back over, >= 1 */
+} plora_manager_config;
+typedef struct {
+  uint64_t hits, misses;       /* requests that found their adapter resident / not (cold starts) */
+  uint64_t loads, evictions;   /* done by the manager */
+  uint64_t failed_loads;       /* requests whose load found no room even after evictions */
+  uint64_t skipped_busy;       /* victims passed over because plora_evict said BUSY */
+  uint64_t waited_for_busy;    /* host waits for a busy victim's copy (loads on demand with nothing else to evict) */
+  uint64_t prefetch_loads, useful_prefetches, wasted_prefetches; /* prefetched; requested before eviction; evicted unrequested */
+  uint64_t prefetch_no_room;   /* prefetch rounds cut short for lack of unpredicted victims */
+  /* memory utilisation (Sec. V-A lists it as a metric), sampled after every successful load once the pool
+   * has first run out of pages: page_util = used pages / pages, byte_util = resident adapter bytes / pool bytes */
+  uint64_t util_samples;
+  double page_util_sum, page_util_min, byte_util_sum, byte_util_min;
+} plora_manager_stats;
+
+/* n_adapters: ids 0 .. n_adapters - 1 (at most the pool's max_adapters).  INVAL for values out of range. */
+int plora_manager_create(plora_pool* pool, int32_t n_adapters, const plora_manager_config* config, plora_manager** out);
+int plora_manager_destroy(plora_manager* manager);
+/* What a load of adapter `id` needs: its rank, scale and page-locked host blob (NULL for a placement-only
+ * pool), as plora_load_adapter takes them.  BUSY while the adapter is resident. */
+int plora_manager_set_adapter(plora_manager* manager, int32_t id, int32_t rank, float scale, const void* pinned_host_ptr);
+/* p_hat: n_adapters predicted access probabilities (copied), or NULL for "no prediction" (p_hat = 0). */
+int plora_manager_set_prediction(plora_manager* manager, const float* p_hat);
+/* One request for adapter `id`: advances the clock and the frequency window; a resident adapter is a hit
+ * (*hit_out = 1); otherwise (*hit_out = 0) its load is started on copy_stream, after evictions by score if
+ * the pool is full (failed_loads counts the case that no room could be made; the call still returns OK).
+ * INVAL for an id that was not registered; errors of the pool are passed on. */
+int plora_manager_request(plora_manager* manager, int32_t id, plora_stream copy_stream, int32_t* hit_out);
+/* Takes the prediction for the coming interval and starts the loads it asks for on prefetch_stream (give
+ * it a stream of its own, so that loads on demand do not queue behind them).  *n_started_out: loads started. */
+int plora_manager_prefetch(plora_manager* manager, const float* p_hat, plora_stream prefetch_stream, int32_t* n_started_out);
+/* Inspection.  Scores of the residents (ids ascending; at most cap entries written, *n_out = residents);
+ * the residents alone; bit 0 = resident, bit 1 = prefetched and not requested since; the counters; the
+ * decisions so far as (kind, id) pairs, kind 0 = load, 1 = evict (at most cap_pairs written, *n_pairs =
+ * pairs recorded; clear != 0 empties the record). */
+int plora_manager_scores(plora_manager* manager, int32_t* ids_out, double* scores_out, int32_t cap, int32_t* n_out);
+int plora_manager_residents(plora_manager* manager, int32_t* ids_out, int32_t cap, int32_t* n_out);
+int plora_manager_state(plora_manager* manager, int32_t id);
+int plora_manager_get_stats(plora_manager* manager, plora_manager_stats* out);
+int plora_manager_log(plora_manager* manager, int32_t* out, int64_t cap_pairs, int64_t* n_pairs, int32_t clear);
+
+/* Measurement aids for benchmarks; no part of the method (Sec. V-A asks for throughput and memory
+ * figures, which want a roof measured on the same GPU beside the published peaks).
+ * plora_probe_stream runs a bare kernel, 3 warm-up launches and then `iters` timed ones on `stream`,
+ * in which every workgroup walks over tiles in turn: w_tile bytes of a w_bytes buffer read with
+ * streaming 16-byte loads, then y_tile bytes of a y_bytes buffer read, changed and written back
+ * (y_bytes = y_tile = 0: the plain streaming read).  One launch reads w_bytes, and reads and writes
+ * (w_bytes / w_tile) * y_tile bytes of y (wrapping around y_bytes).  The buffers are allocated, filled
+ * and freed inside the call, which synchronises the stream.  ms_per_launch: host.  INVAL unless the
+ * tiles are multiples of 4096, w_tile >= 4096, and each buffer is a whole number of tiles of at most 2^36 bytes.
+ * plora_probe_h2d times `iters` copies of one page-locked host buffer of `bytes` bytes (allocated
+ * inside) to the device on `stream`, after one warm-up copy: the rate a single large pinned copy
+ * reaches, to hold the adapter loads against. */
+int plora_probe_stream(uint64_t w_bytes, uint64_t y_bytes, uint32_t w_tile, uint32_t y_tile, int32_t iters,
+                       plora_stream stream, double* ms_per_launch);
+int plora_probe_h2d(uint64_t bytes, int32_t iters, plora_stream stream, double* ms_per_copy);
 
 /* ---------------------------------------------------------------------------------------------
  * Traffic predictor (Sec. III-A), host only: every pointer below is a host pointer and no call

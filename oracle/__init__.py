@@ -5,3 +5,4 @@ package.  It loads oracle/liboracle.so (built from plora_oracle.cpp by build()) 
 ctypes and shares nothing with the HIP library.
 """
 from .pool import OraclePool, build, OracleError  # noqa: F401
+from .manager import OracleManager  # noqa: F401

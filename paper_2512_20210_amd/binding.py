@@ -13,13 +13,16 @@ import numpy as np
 __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS", "PLORA_ERR_NOTFOUND",
            "PLORA_ERR_BUSY", "PLORA_ERR_HIP", "PLORA_ERR_LIMIT", "PLORA_F16", "PLORA_BF16", "PLORA_F32", "PLORA_POOL_PLACEMENT_ONLY",
            "plora_pool_create", "plora_pool_destroy", "plora_adapter_bytes", "plora_load_adapter",
-           "plora_adapter_ready", "plora_wait_adapter", "plora_evict", "plora_batch_begin", "plora_batch_info",
+           "plora_adapter_ready", "plora_wait_adapter", "plora_sync_adapter", "plora_evict", "plora_batch_begin", "plora_batch_info",
            "plora_shrink", "plora_expand", "plora_delta", "plora_delta_static", "plora_batch_end", "plora_pool_stats", "plora_pool_set_option",
-           "plora_profile", "plora_profile_read", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH",
+           "plora_profile", "plora_profile_read", "plora_probe_stream", "plora_probe_h2d", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH",
            "plora_predictor_create", "plora_predictor_destroy", "plora_predictor_observe", "plora_predictor_observed",
            "plora_predictor_predict", "plora_predictor_train", "plora_predictor_train_batch",
            "plora_predictor_param_count", "plora_predictor_get_params", "plora_predictor_set_params",
-           "plora_predictor_loss_grad", "plora_predictor_set_threads", "LstmPredictor"]
+           "plora_predictor_loss_grad", "plora_predictor_set_threads", "LstmPredictor",
+           "plora_manager_create", "plora_manager_destroy", "plora_manager_set_adapter", "plora_manager_set_prediction",
+           "plora_manager_request", "plora_manager_prefetch", "plora_manager_scores", "plora_manager_residents",
+           "plora_manager_state", "plora_manager_get_stats", "plora_manager_log", "ResidencyManager"]
 
 PLORA_OK, PLORA_ERR_INVAL, PLORA_ERR_NOMEM, PLORA_ERR_EXISTS = 0, -1, -2, -3
 PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP, PLORA_ERR_LIMIT = -4, -5, -6, -7
@@ -54,6 +57,7 @@ lib.plora_load_adapter.argtypes = [_vp, _i32, _i32, _f32, _vp, _vp, C.POINTER(C.
 lib.plora_adapter_ready.argtypes = [_vp, _i32]
 lib.plora_wait_adapter.argtypes = [_vp, _i32, _vp]
 lib.plora_evict.argtypes = [_vp, _i32]
+lib.plora_sync_adapter.argtypes = [_vp, _i32]
 lib.plora_batch_begin.argtypes = [_vp, _vp, _i32, _vp, C.POINTER(_vp)]
 lib.plora_batch_info.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(C.POINTER(_i32)),
                                  C.POINTER(C.POINTER(_i32)), C.POINTER(C.POINTER(_i32))]
@@ -66,8 +70,34 @@ lib.plora_pool_stats.argtypes = [_vp, C.POINTER(_Stats)]
 lib.plora_pool_set_option.argtypes = [_vp, C.c_char_p, C.c_int64]
 lib.plora_profile.argtypes = [_vp, C.c_int]
 lib.plora_profile_read.argtypes = [_vp, C.POINTER(C.c_double), C.POINTER(C.c_uint64)]
+lib.plora_probe_stream.argtypes = [_u64, _u64, _u32, _u32, _i32, _vp, C.POINTER(C.c_double)]
+lib.plora_probe_h2d.argtypes = [_u64, _i32, _vp, C.POINTER(C.c_double)]
 lib.plora_last_hip.argtypes = []
 lib.plora_version.argtypes = []
+
+
+class _ManagerConfig(C.Structure):
+    _fields_ = [("alpha", C.c_double), ("beta", C.c_double), ("gamma", C.c_double), ("theta", C.c_double), ("window", C.c_int32)]
+
+
+class _ManagerStats(C.Structure):
+    _fields_ = [(k, C.c_uint64) for k in ("hits", "misses", "loads", "evictions", "failed_loads", "skipped_busy", "waited_for_busy",
+                                          "prefetch_loads", "useful_prefetches", "wasted_prefetches", "prefetch_no_room",
+                                          "util_samples")] + [(k, C.c_double) for k in ("page_util_sum", "page_util_min",
+                                                                                         "byte_util_sum", "byte_util_min")]
+
+
+lib.plora_manager_create.argtypes = [_vp, _i32, C.POINTER(_ManagerConfig), C.POINTER(_vp)]
+lib.plora_manager_destroy.argtypes = [_vp]
+lib.plora_manager_set_adapter.argtypes = [_vp, _i32, _i32, _f32, _vp]
+lib.plora_manager_set_prediction.argtypes = [_vp, _vp]
+lib.plora_manager_request.argtypes = [_vp, _i32, _vp, C.POINTER(_i32)]
+lib.plora_manager_prefetch.argtypes = [_vp, _vp, _vp, C.POINTER(_i32)]
+lib.plora_manager_scores.argtypes = [_vp, _vp, _vp, _i32, C.POINTER(_i32)]
+lib.plora_manager_residents.argtypes = [_vp, _vp, _i32, C.POINTER(_i32)]
+lib.plora_manager_state.argtypes = [_vp, _i32]
+lib.plora_manager_get_stats.argtypes = [_vp, C.POINTER(_ManagerStats)]
+lib.plora_manager_log.argtypes = [_vp, _vp, C.c_int64, C.POINTER(C.c_int64), _i32]
 
 
 class _PredictorConfig(C.Structure):
@@ -132,6 +162,10 @@ def plora_adapter_ready(pool, aid):
 
 def plora_wait_adapter(pool, aid, stream=None):
     return lib.plora_wait_adapter(pool, aid, stream)
+
+
+def plora_sync_adapter(pool, aid):
+    return lib.plora_sync_adapter(pool, aid)
 
 
 def plora_evict(pool, aid):
@@ -200,6 +234,20 @@ def plora_profile_read(pool):
     n = (C.c_uint64 * 2)()
     rc = lib.plora_profile_read(pool, ms, n)
     return rc, list(ms), list(n)
+
+
+def plora_probe_stream(w_bytes, y_bytes, w_tile, y_tile, iters, stream=None):
+    """-> (status, ms per launch)."""
+    ms = C.c_double(0.0)
+    rc = lib.plora_probe_stream(w_bytes, y_bytes, w_tile, y_tile, iters, stream, C.byref(ms))
+    return rc, ms.value
+
+
+def plora_probe_h2d(nbytes, iters, stream=None):
+    """-> (status, ms per copy)."""
+    ms = C.c_double(0.0)
+    rc = lib.plora_probe_h2d(nbytes, iters, stream, C.byref(ms))
+    return rc, ms.value
 
 
 def plora_last_hip():
@@ -409,3 +457,142 @@ class LstmPredictor:
         if self.h:
             plora_predictor_destroy(self.h)
             self.h = None
+
+
+# ---------------------------------------------------------------------------------------------
+# residency policy (host only)
+# ---------------------------------------------------------------------------------------------
+def plora_manager_create(pool, n_adapters, alpha=0.4, beta=0.3, gamma=0.3, theta=0.5, window=1000):
+    cfg = _ManagerConfig(alpha, beta, gamma, theta, window)
+    out = C.c_void_p()
+    rc = lib.plora_manager_create(pool, n_adapters, C.byref(cfg), C.byref(out))
+    return rc, out.value
+
+
+def plora_manager_destroy(mgr):
+    return lib.plora_manager_destroy(mgr)
+
+
+def plora_manager_set_adapter(mgr, aid, rank, scale, pinned_host_ptr=None):
+    return lib.plora_manager_set_adapter(mgr, aid, rank, scale, pinned_host_ptr)
+
+
+def plora_manager_set_prediction(mgr, p_hat):
+    if p_hat is None:
+        return lib.plora_manager_set_prediction(mgr, None)
+    a = np.ascontiguousarray(p_hat, dtype=np.float32)
+    return lib.plora_manager_set_prediction(mgr, a.ctypes.data)
+
+
+def plora_manager_request(mgr, aid, copy_stream=None):
+    """-> (status, hit)."""
+    hit = C.c_int32(0)
+    rc = lib.plora_manager_request(mgr, aid, copy_stream, C.byref(hit))
+    return rc, hit.value
+
+
+def plora_manager_prefetch(mgr, p_hat, prefetch_stream=None):
+    """-> (status, number of loads started)."""
+    a = np.ascontiguousarray(p_hat, dtype=np.float32)
+    n = C.c_int32(0)
+    rc = lib.plora_manager_prefetch(mgr, a.ctypes.data, prefetch_stream, C.byref(n))
+    return rc, n.value
+
+
+def plora_manager_residents(mgr):
+    n = C.c_int32(0)
+    rc = lib.plora_manager_residents(mgr, None, 0, C.byref(n))
+    ids = np.empty(n.value, np.int32)
+    if rc == 0 and n.value:
+        rc = lib.plora_manager_residents(mgr, ids.ctypes.data, n.value, C.byref(n))
+    return rc, ids
+
+
+def plora_manager_scores(mgr):
+    """-> (status, ids ascending, scores)."""
+    n = C.c_int32(0)
+    rc = lib.plora_manager_scores(mgr, None, None, 0, C.byref(n))
+    ids, sc = np.empty(n.value, np.int32), np.empty(n.value, np.float64)
+    if rc == 0 and n.value:
+        rc = lib.plora_manager_scores(mgr, ids.ctypes.data, sc.ctypes.data, n.value, C.byref(n))
+    return rc, ids, sc
+
+
+def plora_manager_state(mgr, aid):
+    return lib.plora_manager_state(mgr, aid)
+
+
+def plora_manager_get_stats(mgr):
+    st = _ManagerStats()
+    rc = lib.plora_manager_get_stats(mgr, C.byref(st))
+    return rc, {k: getattr(st, k) for k, _ in _ManagerStats._fields_}
+
+
+def plora_manager_log(mgr, clear=False):
+    """-> (status, int32 array of (kind, id) pairs; kind 0 = load, 1 = evict)."""
+    n = C.c_int64(0)
+    rc = lib.plora_manager_log(mgr, None, 0, C.byref(n), 0)
+    out = np.empty((n.value, 2), np.int32)
+    if rc == 0:
+        rc = lib.plora_manager_log(mgr, out.ctypes.data if n.value else None, n.value, C.byref(n), int(clear))
+    return rc, out
+
+
+class ResidencyManager:
+    """The library's residency policy (load on demand, eviction by score, threshold prefetching) with
+    errors raised; no arithmetic of its own."""
+
+    def __init__(self, pool, ranks, scales, blob_of=None, alpha=0.4, beta=0.3, gamma=0.3, theta=0.5, window=1000,
+                 copy_stream=None, prefetch_stream=None):
+        """pool: PagedLoraPool; ranks / scales: per adapter id; blob_of(id) -> page-locked torch tensor (None for
+        a placement-only pool)."""
+        self.pool, self.theta = pool, theta
+        self.copy_stream, self.prefetch_stream = copy_stream, prefetch_stream
+        rc, self.h = plora_manager_create(pool.h, len(ranks), alpha, beta, gamma, theta, window)
+        _check("plora_manager_create", rc)
+        self._blobs = []
+        for i, (r, sc) in enumerate(zip(ranks, scales)):
+            blob = blob_of(i) if blob_of is not None else None
+            self._blobs.append(blob)
+            _check("plora_manager_set_adapter", plora_manager_set_adapter(self.h, i, int(r), float(sc), None if blob is None else blob.data_ptr()))
+
+    def close(self):
+        if self.h:
+            plora_manager_destroy(self.h)
+            self.h = None
+
+    def request(self, aid):
+        rc, hit = plora_manager_request(self.h, int(aid), self.copy_stream)
+        _check("plora_manager_request", rc)
+        return bool(hit)
+
+    def prefetch(self, p_hat):
+        rc, n = plora_manager_prefetch(self.h, p_hat, self.prefetch_stream)
+        _check("plora_manager_prefetch", rc)
+        return n
+
+    def set_prediction(self, p_hat):
+        _check("plora_manager_set_prediction", plora_manager_set_prediction(self.h, p_hat))
+
+    def residents(self):
+        rc, ids = plora_manager_residents(self.h)
+        _check("plora_manager_residents", rc)
+        return ids
+
+    def scores(self):
+        rc, ids, sc = plora_manager_scores(self.h)
+        _check("plora_manager_scores", rc)
+        return dict(zip(ids.tolist(), sc.tolist()))
+
+    def state(self, aid):
+        return _check("plora_manager_state", plora_manager_state(self.h, int(aid)))
+
+    def stats(self):
+        rc, st = plora_manager_get_stats(self.h)
+        _check("plora_manager_get_stats", rc)
+        return st
+
+    def log(self, clear=False):
+        rc, a = plora_manager_log(self.h, clear)
+        _check("plora_manager_log", rc)
+        return [tuple(x) for x in a.tolist()]

@@ -5,7 +5,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libplora.so")
-SOURCES = ["plora_pool.cpp", "plora_predictor.cpp", "plora_kernels.hip"]
+SOURCES = ["plora_pool.cpp", "plora_manager.cpp", "plora_predictor.cpp", "plora_kernels.hip", "plora_probe.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
@@ -18,6 +18,8 @@ def build(verbose=False):
         cmd = [HIPCC, "--offload-arch=gfx950"] + common
         if src.endswith(".cpp"):
             cmd += ["-fopenmp-simd"]  # honours the simd pragmas of the host code; no OpenMP runtime involved
+        if src == "plora_manager.cpp":
+            cmd += ["-ffp-contract=off"]  # its scores decide an order: one rounding per operation
         if src.endswith(".hip"):
             # no packed-fp32 instructions from the auto-vectoriser (device pass only)
             cmd += ["-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

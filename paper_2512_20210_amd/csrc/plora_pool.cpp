@@ -515,6 +515,16 @@ int plora_wait_adapter(plora_pool* p, int32_t id, plora_stream s) {
   return PLORA_OK;
 }
 
+int plora_sync_adapter(plora_pool* p, int32_t id) {
+  if (!p || id < 0 || id >= p->max_adapters) return PLORA_ERR_INVAL;
+  Adapter& a = p->ad[id];
+  if (!a.present) return PLORA_ERR_NOTFOUND;
+  if (p->placement_only || !a.copy_pending) return PLORA_OK;
+  HIP_TRY(hipEventSynchronize(a.ev_ready));
+  const int rdy = poll_ready(p, a);
+  return rdy < 0 ? rdy : PLORA_OK;
+}
+
 int plora_evict(plora_pool* p, int32_t id) {
   if (!p || id < 0 || id >= p->max_adapters) return PLORA_ERR_INVAL;
   Adapter& a = p->ad[id];
@@ -1046,11 +1056,12 @@ int plora_expand(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_s
 
 int plora_delta(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* x, float* const* v,
                 void* const* y, plora_stream s) {
-  if (!x || !v || !y) return (n_slots == 0 && p && b && b->open && b->pool == p && !p->placement_only) ? PLORA_OK : PLORA_ERR_INVAL;
-  // validate the second half's arguments before anything is queued
-  if (p && n_slots > 0 && slot0 >= 0 && slot0 + n_slots <= p->n_slots)
-    for (int q = 0; q < n_slots; ++q)
-      if (!y[q] || ((uintptr_t)y[q] & 15)) return PLORA_ERR_INVAL;
+  if (!p || !b || !b->open || b->pool != p || p->placement_only) return PLORA_ERR_INVAL;
+  if (slot0 < 0 || n_slots < 0 || slot0 + n_slots > p->n_slots) return PLORA_ERR_INVAL;
+  if (n_slots == 0 || b->n_tokens == 0) return PLORA_OK;
+  if (!x || !v || !y) return PLORA_ERR_INVAL;
+  for (int q = 0; q < n_slots; ++q)  // the second half's arguments, before anything is queued
+    if (!y[q] || ((uintptr_t)y[q] & 15)) return PLORA_ERR_INVAL;
   const int rc = run_slots(p, b, slot0, n_slots, x, (void* const*)v, s, true);
   if (rc != PLORA_OK) return rc;
   return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);

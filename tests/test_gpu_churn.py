@@ -1,115 +1,196 @@
-"""Churn: load/evict decisions of the residency manager driven on the GPU pool, replayed on the oracle.
+"""Churn on the GPU pool, driven by the library's residency policy (plora_manager_*).
 
-The eviction policy is outside both implementations (parity unpinned: the paper fixes neither the
-weights nor the normalisation of its score), so the check is that the same sequence of loads and
-evictions yields bit-identical page tables and counters on both sides, >= 87 % pool utilisation
-once the pool has filled, and a decode batch over the survivors that matches the oracle.
+(a) With the copy streams drained before every request (so that no victim is ever busy), the library's
+    decisions on the GPU pool are compared one by one with the policy oracle's on the oracle's pool:
+    hits, loads and evictions in order, scores, counters; a 512-token decode batch in the middle of the
+    churn and one at the end are compared with the oracle element by element.
+(b) With copies in flight (threshold prefetching on a synthetic or on the LSTM's prediction, direct
+    and staged loads, a decode batch after every window) the library's own record of loads and
+    evictions is replayed on the oracle's pool: same counters, >= 87 % utilisation, decode parity.
+(c) The same for adapters that cover all 32 layers (8 .. 256 MiB each).
 """
 import numpy as np
 import pytest
 
-from workload import from_elt, make_act, zipf_probs
+from workload import SyntheticPredictor, from_elt, make_act, zipf_probs
 from helpers import TOL_V, TOL_Y, raw_to_torch, rel_err, torch_to_raw
 
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("quality,staged", [(None, False), (0.86, False), (0.86, True), ("lstm", False)])
-def test_churn_tables_utilisation_and_decode(oracle_mod, quality, staged):
-    """quality None: loads on demand only; 0.86: threshold prefetching on a synthetic prediction before
-    every window, with a decode batch after every window while copies may still be in flight; staged:
-    blobs whose pages are scattered go through a staging buffer and the scatter kernel; "lstm": the
-    prediction comes from the library's predictor instead."""
+def _decode_parity(pool, op, lay, cfg, t2a, stream, seed, slots=None, tok_sel=None, threads=1):
+    """One decode batch over `slots` on both pools; every element (or the tokens of tok_sel) compared."""
+    import torch
+    rng = np.random.default_rng(seed)
+    T = len(t2a)
+    slots = list(range(lay.n_slots)) if slots is None else slots
+    b = pool.batch_begin(t2a, stream)
+    perm, sa, ss = pool.batch_info(b)
+    o_perm, o_sa, o_ss = op.translate(t2a)
+    assert perm.tolist() == o_perm.tolist() and sa.tolist() == o_sa.tolist() and ss.tolist() == o_ss.tolist()
+    xs = [make_act(rng, T, lay.d_in[s], lay.dtype) for s in slots]
+    y0 = [make_act(rng, T, lay.d_out[s], lay.dtype) for s in slots]
+    xd = [raw_to_torch(a, "cuda") for a in xs]
+    yd = [raw_to_torch(a, "cuda") for a in y0]
+    vd = [torch.full((T, cfg["max_rank"]), float("nan"), device="cuda") for _ in slots]
+    i = 0
+    while i < len(slots):      # runs of consecutive slots, one call each
+        j = i
+        while j + 1 < len(slots) and slots[j + 1] == slots[j] + 1:
+            j += 1
+        pool.delta(b, slots[i], xd[i:j + 1], vd[i:j + 1], yd[i:j + 1], stream)
+        i = j + 1
+    pool.batch_end(b)
+    torch.cuda.synchronize()
+    sel = slice(None) if tok_sel is None else tok_sel
+    worst = 0.0
+    for q, s in enumerate(slots):
+        v_ref = op.shrink(s, xs[q], t2a, acc64=True, tok_sel=tok_sel, threads=threads)
+        y_ref = op.expand(s, v_ref, t2a, y0[q].copy(), acc64=True, tok_sel=tok_sel, threads=threads)
+        v_got = vd[q].cpu().numpy()
+        y_got = torch_to_raw(yd[q], lay.dtype)
+        ev = rel_err(v_got[sel], v_ref[sel])
+        ey = rel_err(from_elt(y_got[sel], lay.dtype), from_elt(y_ref[sel], lay.dtype))
+        assert ev <= TOL_V and ey <= TOL_Y[lay.dtype], "slot %d: err_v %.3g err_y %.3g" % (s, ev, ey)
+        worst = max(worst, ey)
+    return worst
+
+
+def test_policy_decisions_on_the_gpu_pool_match_the_oracle_and_decode_in_mid_churn(oracle_mod):
     import torch
     import bench
-    from paper_2512_20210_amd.prefetch import PrefetchManager, SyntheticPredictor
+    import paper_2512_20210_amd as P
+    from oracle.pool import max_threads
     cfg, lay, ranks, scales, pool, pinned, trace = bench.churn_setup("cfg3", blobs_per_rank=3)
+    pop, kb = cfg["population"], 3
+    blob = lambda i: pinned[(int(ranks[i]), i % kb)]
+    copy_stream, prefetch_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    stream = torch.cuda.current_stream().cuda_stream
+    mgr = P.ResidencyManager(pool, ranks, scales, blob, copy_stream=copy_stream.cuda_stream,
+                             prefetch_stream=prefetch_stream.cuda_stream)
+    op = oracle_mod.OraclePool(cfg["page_bytes"], cfg["n_pages"], lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
+    om = oracle_mod.OracleManager(op, pop)
+    for i in range(pop):
+        om.set_adapter(i, int(ranks[i]), float(scales[i]), blob(i).numpy().view(np.uint16))
+    popularity = zipf_probs(pop, 1.0)
+    pred = SyntheticPredictor(pop, popularity, 0.86, seed=2)
+    rng = np.random.default_rng(5)
+    n = 0
+    for w, win in enumerate(trace):
+        if w % 2:   # every other window is announced by a prediction
+            p_hat = pred.predict(win).astype(np.float32)
+            copy_stream.synchronize(); prefetch_stream.synchronize()
+            assert mgr.prefetch(p_hat) == len(om.prefetch(p_hat))
+        for aid in win:
+            copy_stream.synchronize(); prefetch_stream.synchronize()    # no victim is busy: decisions are the policy's alone
+            assert mgr.request(int(aid)) == om.request(int(aid)), "request %d" % n
+            n += 1
+        assert mgr.log() == om.log, "window %d: loads / evictions differ" % w
+        if w == 12:  # in the middle of the churn: a 512-token decode batch over the residents, every element checked
+            res = mgr.residents()
+            assert res.tolist() == om.residents()
+            p = popularity[res] / popularity[res].sum()
+            t2a = res[rng.choice(len(res), size=cfg["tokens"], p=p)].astype(np.int32)
+            worst = _decode_parity(pool, op, lay, cfg, t2a, stream, seed=7, threads=max_threads())
+            print("mid-churn decode: %d tokens over %d of %d residents, worst err_y %.3g" % (len(t2a), len(np.unique(t2a)), len(res), worst), flush=True)
+        if n >= 4000:
+            break
+    st = mgr.stats()
+    print("requests", n, {k: st[k] for k in ("hits", "misses", "loads", "evictions", "prefetch_loads", "useful_prefetches", "skipped_busy")}, flush=True)
+    assert st["skipped_busy"] == 0 and st["evictions"] > 200 and st["failed_loads"] == 0
+    for k in ("hits", "misses", "loads", "evictions", "prefetch_loads", "useful_prefetches", "wasted_prefetches"):
+        assert st[k] == getattr(om, k), k
+    assert mgr.scores() == om.scores()
+    assert st["byte_util_min"] == min(om.byte_util) >= 0.87
+    so, sg = op.stats(), pool.stats()
+    for k in ("used_pages", "free_pages", "resident_bytes", "loads", "evictions"):
+        assert so[k] == sg[k], k
+    res = mgr.residents()
+    p = popularity[res] / popularity[res].sum()
+    t2a = res[rng.choice(len(res), size=cfg["tokens"], p=p)].astype(np.int32)
+    _decode_parity(pool, op, lay, cfg, t2a, stream, seed=9, threads=max_threads())
+    mgr.close()
+    op.close()
+    pool.close()
+
+
+@pytest.mark.parametrize("name,quality,staged", [("cfg3", None, False), ("cfg3", 0.86, False), ("cfg3", 0.86, True),
+                                                 ("cfg3", "lstm", False), ("cfg3L", 0.86, False)])
+def test_churn_with_copies_in_flight(oracle_mod, name, quality, staged):
+    """Loads on demand only (quality None) or with threshold prefetching before every window, a decode
+    batch after every window while copies may still be in flight; staged: blobs whose pages are scattered go
+    through a staging buffer and the scatter kernel; "lstm": the prediction comes from the library's
+    predictor; cfg3L: adapters over all 32 layers."""
+    import torch
+    import bench
+    import paper_2512_20210_amd as P
+    from oracle.pool import max_threads
+    big = name == "cfg3L"
+    kb = 1 if big else 3
+    cfg, lay, ranks, scales, pool, pinned, trace = bench.churn_setup(name, blobs_per_rank=kb)
     pop = cfg["population"]
     if staged:
         pool.set_option("staging_bytes", lay.adapter_elems(cfg["max_rank"]) * 2)
         pool.set_option("staging_min_runs", 2)
-    kb = 3
     blob = lambda i: pinned[(int(ranks[i]), i % kb)]
     copy_stream, prefetch_stream = torch.cuda.Stream(), torch.cuda.Stream()
     stream = torch.cuda.current_stream().cuda_stream
-    pm = bench._PoolForManager(pool, lay)
-    mgr = PrefetchManager(pm, ranks, scales, blob, copy_stream=copy_stream.cuda_stream,
-                          prefetch_stream=prefetch_stream.cuda_stream)
+    mgr = P.ResidencyManager(pool, ranks, scales, blob, copy_stream=copy_stream.cuda_stream,
+                             prefetch_stream=prefetch_stream.cuda_stream)
     popularity = zipf_probs(pop, 1.0)
     if quality == "lstm":  # the library's predictor, learning online from the windows it has seen
-        import paper_2512_20210_amd as P
         pred = P.LstmPredictor(pop, window=4, hidden=16, layers=2, replay=200, batch=16, lr=3e-3, seed=2, threads=4)
     else:
         pred = SyntheticPredictor(pop, popularity, quality, seed=2) if quality is not None else None
     rng0 = np.random.default_rng(6)
     Tw = 64
-    xw = [raw_to_torch(make_act(rng0, Tw, d, lay.dtype), "cuda") for d in lay.d_in]
-    yw = [raw_to_torch(make_act(rng0, Tw, d, lay.dtype), "cuda") for d in lay.d_out]
-    vw = [torch.empty((Tw, cfg["max_rank"]), device="cuda") for _ in lay.d_in]
-    n = 0
+    wslots = [0, 1, 2, 3] if not big else [0, 1, 62, 127]
+    xw = [raw_to_torch(make_act(rng0, Tw, lay.d_in[s], lay.dtype), "cuda") for s in wslots[:2]]
+    yw = [raw_to_torch(make_act(rng0, Tw, lay.d_out[s], lay.dtype), "cuda") for s in wslots[:2]]
+    vw = [torch.empty((Tw, cfg["max_rank"]), device="cuda") for _ in wslots[:2]]
+    n, limit = 0, (600 if big else 3000)
     for win in trace:
         if pred is not None:
-            mgr.begin_interval(pred.predict(win))
+            mgr.prefetch(pred.predict(win))
         for aid in win:
             mgr.request(int(aid))
             n += 1
         if pred is not None:  # a decode batch over this window's adapters, some of them still being copied
             ids = np.unique(win)
-            ids = ids[np.isin(ids, np.fromiter(mgr.resident(), dtype=np.int32))]
+            ids = ids[np.isin(ids, mgr.residents())]
             t2a = ids[rng0.integers(0, len(ids), size=Tw)].astype(np.int32)
             b = pool.batch_begin(t2a, stream)
             pool.shrink(b, 0, xw, vw, stream)
             pool.expand(b, 0, vw, yw, stream)
             pool.batch_end(b)
-        if n >= 3000:
+        if n >= limit:
             break
     torch.cuda.synchronize()
-    print("requests", n, "hits", mgr.hits, "misses", mgr.misses, "evictions", mgr.evictions, flush=True)
-    assert mgr.evictions > 200 and mgr.failed == 0
-    if pred is not None:
-        print("prefetch loads", mgr.prefetch_loads, "useful", mgr.useful_prefetches, "wasted", mgr.wasted_prefetches, flush=True)
-        if quality != "lstm":  # (30 windows of an i.i.d. trace teach the LSTM little: only the mechanism is checked)
-            assert mgr.useful_prefetches > 0.7 * mgr.prefetch_loads
-    assert min(pm.byte_util) >= 0.87, "utilisation fell to %.3f" % min(pm.byte_util)
+    st = mgr.stats()
+    print(name, "requests", n, {k: st[k] for k in ("hits", "misses", "loads", "evictions", "prefetch_loads", "useful_prefetches",
+                                                   "wasted_prefetches", "skipped_busy", "failed_loads")}, flush=True)
+    assert st["evictions"] > (100 if big else 200) and st["failed_loads"] == 0
+    if pred is not None and quality != "lstm" and not big:
+        # (30 windows of an i.i.d. trace teach the LSTM little: only the mechanism is checked there)
+        assert st["useful_prefetches"] > 0.7 * st["prefetch_loads"]
+    assert st["byte_util_min"] >= 0.87, "utilisation fell to %.3f" % st["byte_util_min"]
     assert (pool.stats()["staged_loads"] > 100) == staged
 
     op = oracle_mod.OraclePool(cfg["page_bytes"], cfg["n_pages"], lay.d_in, lay.d_out, lay.dtype, pop, cfg["max_rank"])
-    for what, aid in mgr.log:
-        if what == "load":
+    for kind, aid in mgr.log():
+        if kind == 0:
             op.load(aid, int(ranks[aid]), float(scales[aid]), blob(aid).numpy().view(np.uint16))
         else:
             op.evict(aid)
     so, sg = op.stats(), pool.stats()
     for k in ("used_pages", "free_pages", "resident_bytes", "loads", "evictions"):
         assert so[k] == sg[k], k
-    res = np.array(sorted(mgr.resident()), dtype=np.int32)
-    # page tables of the survivors: the library hands out a pointer at load time only, so compare through
-    # a fresh load of one evicted adapter and through the decode below (which gathers through every table)
+    res = mgr.residents()
     rng = np.random.default_rng(5)
     T = 96
-    p = zipf_probs(pop, 1.0)[res]
+    p = popularity[res]
     t2a = res[rng.choice(len(res), size=T, p=p / p.sum())].astype(np.int32)
-    b = pool.batch_begin(t2a, stream)
-    perm, sa, ss = pool.batch_info(b)
-    o_perm, o_sa, o_ss = op.translate(t2a)
-    assert perm.tolist() == o_perm.tolist() and sa.tolist() == o_sa.tolist() and ss.tolist() == o_ss.tolist()
-    xs = [make_act(rng, T, d, lay.dtype) for d in lay.d_in]
-    y0 = [make_act(rng, T, d, lay.dtype) for d in lay.d_out]
-    xd = [raw_to_torch(a, "cuda") for a in xs]
-    yd = [raw_to_torch(a, "cuda") for a in y0]
-    vd = [torch.full((T, cfg["max_rank"]), float("nan"), device="cuda") for _ in xs]
-    pool.shrink(b, 0, xd, vd, stream)
-    pool.expand(b, 0, vd, yd, stream)
-    pool.batch_end(b)
-    torch.cuda.synchronize()
-    sel = np.arange(0, T, 5, dtype=np.int32)
-    for s in range(lay.n_slots):
-        v_ref = op.shrink(s, xs[s], t2a, acc64=True, tok_sel=sel)
-        y_ref = op.expand(s, v_ref, t2a, y0[s].copy(), acc64=True, tok_sel=sel)
-        v_got = vd[s].cpu().numpy()
-        y_got = torch_to_raw(yd[s], lay.dtype)
-        assert rel_err(v_got[sel], v_ref[sel]) <= TOL_V
-        assert rel_err(from_elt(y_got[sel], lay.dtype), from_elt(y_ref[sel], lay.dtype)) <= TOL_Y[lay.dtype]
+    _decode_parity(pool, op, lay, cfg, t2a, stream, seed=5, slots=wslots, threads=max_threads())
     # an evicted adapter comes back onto the same pages on both sides
     victim = int(res[0])
     pool.evict(victim)
@@ -118,5 +199,6 @@ def test_churn_tables_utilisation_and_decode(oracle_mod, quality, staged):
     pt_o = op.load(victim, int(ranks[victim]), float(scales[victim]), blob(victim).numpy().view(np.uint16))
     assert pt_g.tolist() == pt_o.tolist()
     torch.cuda.synchronize()
+    mgr.close()
     op.close()
     pool.close()

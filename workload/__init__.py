@@ -8,4 +8,5 @@ length distribution and Llama/Mistral projection shapes (Sec. V-A): only their s
 distributions are used.
 """
 from .gen import *  # noqa: F401,F403
+from .predict import SyntheticPredictor  # noqa: F401
 from .configs import CONFIGS, config_layout, BASE_SEED  # noqa: F401

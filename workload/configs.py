@@ -25,13 +25,20 @@ CONFIGS = {
     "cfg2x8": dict(seed=BASE_SEED + 2, dtype=DT_BF16, slots=[(4096, 4096)] * 32, requests=32, len_lo=64,
                    len_hi=256, n_adapters=128, ranks=None, rank_choices=[8, 16, 32, 64, 128], zipf=1.2,
                    scale=None, page_bytes=64 * KIB, n_pages=None, max_rank=128),
-    # churn: 2 GiB pool of 64 KiB pages, 10,000 load/evict-driving requests over a population of
-    # adapters with ranks in {4,...,128}, Zipf(1.0) popularity, bursts (x8 for 10% of windows),
-    # interleaved with 512-token bf16 decode batches at hidden 4096 (q,k,v,o of one layer)
+    # churn: 2 GiB pool of 64 KiB pages driven until 10,000 load / evict events have happened, by
+    # requests over a population of adapters with ranks in {4,...,128}, Zipf(1.0) popularity, bursts
+    # (x8 for 10% of windows), interleaved with 512-token bf16 decode batches at hidden 4096
+    # (q,k,v,o of one layer); max_requests bounds the trace that is drawn
     "cfg3": dict(seed=BASE_SEED + 3, dtype=DT_BF16, slots=[(4096, 4096)] * 4, tokens=512, population=4096,
                  ranks=None, rank_choices=[4, 8, 16, 32, 64, 128], zipf=1.0, scale=None,
-                 page_bytes=64 * KIB, n_pages=32768, max_rank=128, n_events=10000, window=100,
+                 page_bytes=64 * KIB, n_pages=32768, max_rank=128, n_events=10000, max_requests=80000, window=100,
                  burst_prob=0.1, burst_mult=8),
+    # the same with adapters that cover all 32 layers (128 slots): 8 .. 256 MiB each, two dozen of a
+    # population of 256 fit the 2 GiB pool (one rank-128 adapter is an eighth of it)
+    "cfg3L": dict(seed=BASE_SEED + 3, dtype=DT_BF16, slots=[(4096, 4096)] * 128, tokens=512, population=256,
+                  ranks=None, rank_choices=[4, 8, 16, 32, 64, 128], zipf=1.0, scale=None,
+                  page_bytes=64 * KIB, n_pages=32768, max_rank=128, n_events=10000, max_requests=80000, window=100,
+                  burst_prob=0.1, burst_mult=8),
     # cfg3 with a recurring request pattern (300 timer-like adapters with periods of 2 .. 12 windows on a
     # Zipf background) and a pool of a fifth of cfg3's size, so that long-period adapters are evicted
     # between two of their windows; for the traffic predictor (Sec. III-A)
