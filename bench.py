@@ -36,7 +36,7 @@ MEASURED_TRAFFIC = {
     "cfg2": dict(shrink=0.274e9, expand=0.400e9, profile="profiles/prefill_cfg2_kernels_traffic_and_mfma_activity.md", sources=None),
 }
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
-KCLASS = ["shrink", "expand"]
+KCLASS = ["shrink", "expand", "delta"]
 
 
 def kernel_sources_digest():
@@ -233,7 +233,9 @@ class GpuWorkload:
     def host_y0(self, s):
         return np.roll(self.y_host_base[self.lay.d_out[s]], -s - 1, axis=0)
 
-    def step(self, t2a, slots_per_call):
+    def step(self, t2a, slots_per_call, api="pair"):
+        """api "pair": plora_shrink then plora_expand per call; "delta": plora_delta (one call, and for small
+        calls one launch)."""
         pool, n = self.pool, self.lay.n_slots
         if len(t2a) > self.T:  # the library cannot see buffer sizes: never launch past the activations
             raise ValueError("batch of %d tokens but activation buffers hold %d" % (len(t2a), self.T))
@@ -242,8 +244,11 @@ class GpuWorkload:
         b = pool.batch_begin(t2a, self.stream)
         for s0 in range(0, n, slots_per_call):
             s1 = min(n, s0 + slots_per_call)
-            pool.shrink(b, s0, x[s0:s1], v[s0:s1], self.stream)
-            pool.expand(b, s0, v[s0:s1], y[s0:s1], self.stream)
+            if api == "delta":
+                pool.delta(b, s0, x[s0:s1], v[s0:s1], y[s0:s1], self.stream)
+            else:
+                pool.shrink(b, s0, x[s0:s1], v[s0:s1], self.stream)
+                pool.expand(b, s0, v[s0:s1], y[s0:s1], self.stream)
         pool.batch_end(b)
 
     def close(self):
@@ -559,6 +564,8 @@ def main():
     ap.add_argument("--coop-max-workgroups", type=int, default=-1,
                     help="calls of at most this many workgroups use the cooperative kernels (library defaults 192 for "
                          "shrink, 2500 for expand; 0 = never)")
+    ap.add_argument("--api", default="pair", choices=["pair", "delta"], help="plora_shrink + plora_expand per call, or plora_delta")
+    ap.add_argument("--opt", action="append", default=[], help="key=value passed to plora_pool_set_option (repeatable)")
     ap.add_argument("--no-probes", action="store_true", help="skip the streaming / copy probes and the per-layer-call leg")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
@@ -601,6 +608,9 @@ def main():
         w.pool.set_option("mfma_min_work_expand", 1 << 30)
     if args.xcd_remap >= 0:
         w.pool.set_option("xcd_remap", args.xcd_remap)
+    for kv in args.opt:
+        key, val = kv.split("=")
+        w.pool.set_option(key, int(val))
     rng = np.random.default_rng(cfg["seed"] + 7)
     n_draws = 1 if args.same_batch else args.steps + args.warmup
     batches = [draw_batch(cfg, rng, w.n_ad) for _ in range(n_draws)]
@@ -610,18 +620,18 @@ def main():
     all_slots = list(range(lay.n_slots))
 
     for i in range(args.warmup):
-        w.step(batches[i % n_draws], spc)
+        w.step(batches[i % n_draws], spc, args.api)
     torch.cuda.synchronize()
     if not args.no_kernel_events:
         w.pool.profile(True)
     timed = [batches[(args.warmup + i) % n_draws] for i in range(args.steps)]
     t0 = time.perf_counter()
     for t2a in timed:
-        w.step(t2a, spc)
+        w.step(t2a, spc, args.api)
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     elapsed = t1 - t0
-    kms, kn = ([0.0] * 2, [0] * 2)
+    kms, kn = ([0.0] * 3, [0] * 3)
     if not args.no_kernel_events:
         w.pool.profile(False)
         kms, kn = w.pool.profile_read()
@@ -636,17 +646,17 @@ def main():
     roof = None
     if not args.no_kernel_events and sum(kn):
         dom = int(np.argmax(kms))
-        kb = sum(a["shrink" if dom == 0 else "expand"] for a in ab)
+        kb = sum(a[("shrink", "expand", "total")[dom]] for a in ab)
         avg_ms = kms[dom] / kn[dom]
         per_launch = kb / kn[dom]
         ach = per_launch / (avg_ms * 1e-3) / 1e9
         default_draw = spc == lay.n_slots and SEED_OFFSET == 0 and not args.share_qkv_x
-        traffic, traffic_profile = measured_traffic(args.workload, KCLASS[dom], default_draw)
+        traffic, traffic_profile = measured_traffic(args.workload, KCLASS[dom], default_draw and dom < 2)
         roof = dict(bound="hbm", kernel=KCLASS[dom], achieved=round(ach, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                     frac=round(ach / HBM_PEAK_GBS, 4), traffic=traffic, traffic_profile=traffic_profile,
                     kernel_sources=kernel_sources_digest(), avg_launch_ms=round(avg_ms, 5),
                     launches=int(kn[dom]), algorithmic_bytes_per_launch=int(per_launch),
-                    all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(2) if kn[k]})
+                    all_kernels_ms_per_step={KCLASS[k]: round(kms[k] / args.steps, 5) for k in range(3) if kn[k]})
 
     out = {
         "metric": METRIC, "value": round(gbs, 1), "unit": "GB/s", "n_gpus": 1, "steps": args.steps,
@@ -654,7 +664,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": {0: "f16", 1: "bf16", 2: "f32"}[lay.dtype],
         "data": "synthetic",
         "config": {"workload": args.workload, "slots": lay.n_slots, "tokens": int(T), "adapters": int(w.n_ad),
-                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc), "seed": int(cfg["seed"]), "share_qkv_x": bool(args.share_qkv_x),
+                   "page_bytes": int(w.page_bytes), "pool_pages": int(w.n_pages), "slots_per_call": int(spc), "entry_points": args.api, "seed": int(cfg["seed"]), "share_qkv_x": bool(args.share_qkv_x),
                    "mean_unique_adapters": round(float(np.mean([a["n_unique"] for a in ab])), 1),
                    "mean_run_of_consecutive_pages": round(w.mean_run_pages, 1), "activation_sets": len(w.act_sets), "activation_bytes_per_set": int(w.act_bytes)},
         "tokens_per_s": round(tokens_total / elapsed, 1),
@@ -670,15 +680,15 @@ def main():
         if lay.n_slots > 4 and lay.n_slots % 4 == 0 and spc == lay.n_slots:
             n = min(args.steps, 200)
             for i in range(10):
-                w.step(timed[i % len(timed)], 4)
+                w.step(timed[i % len(timed)], 4, "delta")
             torch.cuda.synchronize()
             t0 = time.perf_counter()
             for i in range(n):
-                w.step(timed[i % len(timed)], 4)
+                w.step(timed[i % len(timed)], 4, "delta")
             torch.cuda.synchronize()
             dt = time.perf_counter() - t0
             b4 = sum(ab[i % len(timed)]["total"] for i in range(n))
-            out["per_layer_calls"] = {"slots_per_call": 4, "steps": n, "ms_per_step": round(dt / n * 1e3, 4),
+            out["per_layer_calls"] = {"slots_per_call": 4, "entry_points": "delta", "steps": n, "ms_per_step": round(dt / n * 1e3, 4),
                                       "value": round(b4 / dt / 1e9, 1), "unit": "GB/s",
                                       "pct_of_hbm_peak": round(100.0 * b4 / dt / 1e9 / HBM_PEAK_GBS, 2),
                                       "tokens_per_s": round(sum(len(timed[i % len(timed)]) for i in range(n)) / dt, 1)}

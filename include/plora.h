@@ -73,6 +73,9 @@ typedef struct {
   uint64_t h2d_copies; /* number of copy calls (one per run of physically consecutive pages) */
   double h2d_ms;       /* summed first-copy-start -> last-copy-end time of completed loads */
   uint64_t staged_loads; /* loads that went through a staging buffer and the scatter kernel */
+  uint64_t fused_launches; /* plora_delta calls that ran as one launch */
+  uint64_t fused_timeouts; /* expand tasks of such launches that gave up waiting for their slot's shrink tasks (their
+                              part of y was left as it was); stays 0 unless "fused_spin_limit" is set very low */
 } plora_stats;
 
 /* Pool of n_pages pages of page_bytes each (Sec. III-C "Page Structure"; the paper's default page is
@@ -157,7 +160,12 @@ int plora_expand(plora_pool* pool, const plora_batch* batch, int32_t slot0, int3
 
 /* Eq. 1's delta in one call: shrink, then expand, over the same slot range, as plora_shrink followed by
  * plora_expand with the same arguments would do (v is the workspace in between; its contents afterwards
- * are those plora_shrink leaves).  Nothing is queued if an argument is invalid. */
+ * are those plora_shrink leaves).  Nothing is queued if an argument is invalid.  With the option
+ * "fused_max_tasks" set, a call on the batch's own stream of at most 32 slots and that many workgroups'
+ * worth of work (not a batch of large groups, not a stream under graph capture) runs as ONE launch: the
+ * workgroups of a persistent grid run the shrink and then the expand work, an expand task waiting
+ * (bounded) until its slot's shrink tasks have finished; results are bit-identical to the two-launch
+ * form.  Such launches on one batch must not overlap, which the single stream guarantees. */
 int plora_delta(plora_pool* pool, const plora_batch* batch, int32_t slot0, int32_t n_slots, const void* const* x,
                 float* const* v, void* const* y, plora_stream stream);
 
@@ -210,6 +218,11 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * shrink item keeps in flight per wavefront; 0 lets the library choose per launch (2 when the batch's
  * matrix-core token tiles are at least half full on average, as in prefill, when a slot of the launch
  * has d_in > 4096, or when the launch has at most 2500 workgroups; else 1).  Results do not depend on it.
+ * "fused_max_tasks" (0 .. 2^30, default 0 = never): plora_delta calls of at most this many workgroup
+ * tasks run as one launch (see plora_delta; measured slower than the two launches on MI355X at every call
+ * size, hence off).  "fused_spin_limit" (0 .. 2^31, default 2^20): polls of a
+ * slot's completion counter before an expand task of such a launch gives up (counted in
+ * plora_stats.fused_timeouts); only a test has reason to lower it.
  * "staging_bytes" (0 .. 2^36, default 0 = off) and "staging_min_runs" (>= 1, default 3: with two runs the direct copies are as fast): staged loads
  * (Sec. III-B: loaded adapters arrive in a staging area before they are moved into place).  With
  * staging on, plora_load_adapter sends a blob of at most staging_bytes whose pages form at least
@@ -223,9 +236,9 @@ int plora_pool_set_option(plora_pool* pool, const char* key, int64_t value);
 /* Kernel timing for benchmarks.  plora_profile(pool, 1) makes plora_shrink / plora_expand attach a
  * pair of HIP events to the kernel dispatches of every call (start of its first kernel, end of its
  * last; nothing extra is queued on the stream); plora_profile(pool, 0) stops.
- * plora_profile_read waits for the recorded events and returns, per kernel (0 shrink, 1 expand), the
- * summed duration in ms and the number of launches since the last read, then clears the record.
- * ms and launches: host, 2 entries each. */
+ * plora_profile_read waits for the recorded events and returns, per kernel class (0 shrink, 1 expand,
+ * 2 the one-launch form of plora_delta), the summed duration in ms and the number of launches since the
+ * last read, then clears the record.  ms and launches: host, 3 entries each. */
 int plora_profile(plora_pool* pool, int enable);
 int plora_profile_read(plora_pool* pool, double* ms, uint64_t* launches);
 

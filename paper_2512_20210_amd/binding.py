@@ -45,7 +45,8 @@ class _Layout(C.Structure):
 class _Stats(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("page_bytes", "n_pages", "used_pages", "free_pages", "resident_adapters",
                                           "resident_bytes", "internal_frag_bytes", "loads", "evictions",
-                                          "nomem_failures", "h2d_bytes", "h2d_copies")] + [("h2d_ms", C.c_double), ("staged_loads", C.c_uint64)]
+                                          "nomem_failures", "h2d_bytes", "h2d_copies")] + [("h2d_ms", C.c_double), ("staged_loads", C.c_uint64), ("fused_launches", C.c_uint64),
+                                                                                        ("fused_timeouts", C.c_uint64)]
 
 
 _vp, _i32, _u32, _u64, _f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_float
@@ -229,9 +230,9 @@ def plora_profile(pool, enable):
 
 
 def plora_profile_read(pool):
-    """-> (status, ms[2], launches[2]) for the shrink and the expand kernel."""
-    ms = (C.c_double * 2)()
-    n = (C.c_uint64 * 2)()
+    """-> (status, ms[3], launches[3]) for the shrink kernels, the expand kernels and the one-launch form."""
+    ms = (C.c_double * 3)()
+    n = (C.c_uint64 * 3)()
     rc = lib.plora_profile_read(pool, ms, n)
     return rc, list(ms), list(n)
 

@@ -63,6 +63,42 @@ struct LaunchArgs {
   int32_t pad;
 };
 
+// One launch that does shrink and then expand over a few slots (plora_delta on small calls): workgroup w
+// of a persistent grid runs tasks w, w + grid, w + 2 grid, ... of a list that holds the shrink tasks of all
+// slots and then the expand tasks.  An expand task waits until its slot's shrink tasks have all finished:
+// every shrink task adds one to a per-slot counter, the one that completes the count publishes the
+// count in kFlagCopies flag words (on separate cache lines, so that the waiting workgroups do not all
+// poll one address), and expand tasks poll one of them.  The counters are never reset: the host keeps
+// the value each slot's counter will have reached after every launch and hands it over as the target.
+constexpr int kMaxSlotsFused = 32;
+constexpr int kFlagCopies = 8, kFlagStride = 32;  // words between the copies (128 bytes)
+constexpr int kQueueFlag0 = 64;                   // words [0, 32): counters; flags of slot q from kQueueFlag0 + q * kFlagCopies * kFlagStride
+constexpr int kQueueWords = kQueueFlag0 + kMaxSlotsFused * kFlagCopies * kFlagStride;
+struct FusedPtrs {
+  const void* x[kMaxSlotsFused];
+  float* v[kMaxSlotsFused];
+  void* y[kMaxSlotsFused];
+  int32_t slot[kMaxSlotsFused];
+  uint32_t target[kMaxSlotsFused];  // value of the slot's counter once this launch's shrink tasks are done
+};
+struct FusedArgs {
+  const uint8_t* slab;
+  const int32_t* perm;
+  const int32_t* pt;
+  const ItemRec* items_s;  // shrink list: blocks of 4 records, or (coop_s) single records
+  const ItemRec* items_e;  // expand list, likewise
+  const SlotRec* slots;
+  uint32_t* queue;         // kQueueWords words of the batch, zero when allocated and never reset
+  uint32_t* timeouts;      // one word in page-locked host memory: expand tasks given up, counted for the host
+  int64_t elems_per_rank;
+  int32_t n_s, n_e;        // workgroup tasks per slot: shrink; expand per 512-column chunk
+  int32_t chunks, n_slots;
+  int32_t log2_page, v_stride;
+  int32_t coop_s, coop_e;  // 1: the list holds single vector-ALU records that the four wavefronts share
+  uint32_t spin_limit;     // polls of a slot's flag before an expand task gives up (and counts a timeout)
+  int32_t pad;
+};
+
 // Runs of physically consecutive pages of one adapter, for the staged load's scatter kernel: run k
 // covers the virtual pages first_vpage[k] .. (first_vpage[k+1] or the launch's end) and starts at
 // physical page phys_page[k].
@@ -92,6 +128,9 @@ hipError_t launch_shrink(int dtype, const LaunchArgs& a, const SlotPtrs& p, int 
                          hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 hipError_t launch_expand(int dtype, const LaunchArgs& a, const SlotPtrs& p, int n_slots, int max_chunks, int mode,
                          hipStream_t st, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+
+hipError_t launch_delta_queue(int dtype, const FusedArgs& f, const FusedPtrs& p, hipStream_t st, hipEvent_t e0 = nullptr,
+                              hipEvent_t e1 = nullptr);
 
 // The library's static device array (plora_delta_static keeps v there): its size, and its address on
 // the current device (looked up once per device).

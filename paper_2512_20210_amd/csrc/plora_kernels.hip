@@ -207,6 +207,21 @@ constexpr int wave_sums_shift() { return N == 32 ? 1 : N == 16 ? 2 : N == 8 ? 3 
 
 __device__ __forceinline__ int imin(int a, int b) { return a < b ? a : b; }
 
+// v handed from shrink tasks to expand tasks inside one launch (k_delta_queue) crosses from one XCD's L2
+// to another's: there every access to v is a device-scope access (written through to, and read from,
+// the level all XCDs share), which costs little for so small an array and needs no cache flushes.
+// The separate kernels use ordinary accesses (the kernel boundary orders them).
+template <bool COH>
+__device__ __forceinline__ void st_v(float* p, float x) {
+  if constexpr (COH) __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else *p = x;
+}
+template <bool COH>
+__device__ __forceinline__ float ld_v(const float* p) {
+  if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  else return *p;
+}
+
 // Orders one wavefront's LDS writes before its later LDS reads (any lane).  LDS instructions of a
 // wavefront execute in order, so only the compiler has to be kept from moving them: no s_barrier,
 // which lets the wavefronts of a 256-thread workgroup run independent vector-ALU items.
@@ -273,7 +288,7 @@ __device__ __forceinline__ void shrink_valu_chunk(const LaunchArgs& a, const uin
   }
 }
 
-template <int DT, int NT, int ROWS, bool NTW>
+template <int DT, int NT, int ROWS, bool NTW, bool COH>
 __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt) {
@@ -300,7 +315,7 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
 #pragma unroll
     for (int i = 0; i < NT; ++i)
       if (i < it.ntok)
-        for (int j = r + lane; j < vs; j += kWave) v[tok[i] * vs + j] = 0.f;
+        for (int j = r + lane; j < vs; j += kWave) st_v<COH>(v + tok[i] * vs + j, 0.f);
   }
   if (r == 0) return;
   wave_sync();
@@ -322,20 +337,20 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
   const float total = wave_sums<ROWS * NT>(&acc[0][0], lane);
   const int idx = lane >> sh, jj = idx / NT, i = idx % NT;
   const int ti = i == 1 ? it.tok[1] : i == 2 ? it.tok[2] : i == 3 ? it.tok[3] : it.tok[0];
-  if ((lane & ((1 << sh) - 1)) == 0 && jj < nrows && i < it.ntok) v[(int64_t)ti * vs + it.j0 + jj] = total;
+  if ((lane & ((1 << sh) - 1)) == 0 && jj < nrows && i < it.ntok) st_v<COH>(v + (int64_t)ti * vs + it.j0 + jj, total);
 }
 
-template <int DT>
+template <int DT, bool COH = false>
 __device__ __forceinline__ void shrink_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
                                                  const uint8_t* x, float* v, int32_t* lds_pt) {
   if (item_once(it)) {
-    if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows, true>(a, it, sl, x, v, lds_pt);
-    else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows, true>(a, it, sl, x, v, lds_pt);
-    else shrink_valu_body<DT, kValuTok, kShrinkRows, true>(a, it, sl, x, v, lds_pt);
+    if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows, true, COH>(a, it, sl, x, v, lds_pt);
+    else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows, true, COH>(a, it, sl, x, v, lds_pt);
+    else shrink_valu_body<DT, kValuTok, kShrinkRows, true, COH>(a, it, sl, x, v, lds_pt);
   } else {
-    if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows, false>(a, it, sl, x, v, lds_pt);
-    else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows, false>(a, it, sl, x, v, lds_pt);
-    else shrink_valu_body<DT, kValuTok, kShrinkRows, false>(a, it, sl, x, v, lds_pt);
+    if (it.ntok <= 1) shrink_valu_body<DT, 1, kShrinkRows, false, COH>(a, it, sl, x, v, lds_pt);
+    else if (it.ntok == 2) shrink_valu_body<DT, 2, kShrinkRows, false, COH>(a, it, sl, x, v, lds_pt);
+    else shrink_valu_body<DT, kValuTok, kShrinkRows, false, COH>(a, it, sl, x, v, lds_pt);
   }
 }
 
@@ -363,10 +378,10 @@ __device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const ItemR
   }
 }
 
-template <int DT, int NT, bool NTW>
+template <int DT, int NT, bool NTW, bool COH>
 __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg,
-                                                 int chunk) {
+                                                 int chunk, float* lds_v = nullptr) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
   const int lane = lane_id();
   const int r = it.rank;
@@ -391,6 +406,13 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
     vrow[i] = v + (int64_t)it.tok[i] * vs;
     yp[i] = y + ((uint64_t)it.tok[i] * d_out + (ok ? n : n0w)) * EB;
     yq[i] = ldy16(yp[i]);  // requested now, used after the loop
+  }
+  if constexpr (COH) {
+    // the tokens' rows of v come through device-scope loads (a trip past the L2 each): all of them are
+    // requested here at once and parked in LDS (row i at lds_v + i * r), the loop below reads them from there
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+      for (int j = lane; j < r; j += kWave) lds_v[i * r + j] = ld_v<true>(vrow[i] + j);
   }
   wave_sync();
   float acc[NT][VEC];
@@ -417,7 +439,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
       unpack<DT>(wq[u], wf);
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
-        const float vj = vrow[i][j + u];
+        const float vj = COH ? lds_v[i * r + j + u] : vrow[i][j + u];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[i][e] = __builtin_fmaf(vj, wf[e], acc[i][e]);
       }
@@ -432,7 +454,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
     unpack<DT>(ldw16<NTW>(a.slab + (pg << lp) + (inpage & pmask)), wf);
 #pragma unroll
     for (int i = 0; i < NT; ++i) {
-      const float vj = vrow[i][j];
+      const float vj = COH ? lds_v[i * r + j] : vrow[i][j];
 #pragma unroll
       for (int e = 0; e < VEC; ++e) acc[i][e] = __builtin_fmaf(vj, wf[e], acc[i][e]);
     }
@@ -450,17 +472,17 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
   }
 }
 
-template <int DT>
+template <int DT, bool COH = false>
 __device__ __forceinline__ void expand_valu_item(const LaunchArgs& a, const ItemRec& it, const SlotRec& sl,
-                                                 const float* v, uint8_t* y, int2* lds_pg, int chunk) {
+                                                 const float* v, uint8_t* y, int2* lds_pg, int chunk, float* lds_v = nullptr) {
   if (item_once(it)) {
-    if (it.ntok <= 1) expand_valu_body<DT, 1, true>(a, it, sl, v, y, lds_pg, chunk);
-    else if (it.ntok == 2) expand_valu_body<DT, 2, true>(a, it, sl, v, y, lds_pg, chunk);
-    else expand_valu_body<DT, kValuTok, true>(a, it, sl, v, y, lds_pg, chunk);
+    if (it.ntok <= 1) expand_valu_body<DT, 1, true, COH>(a, it, sl, v, y, lds_pg, chunk, lds_v);
+    else if (it.ntok == 2) expand_valu_body<DT, 2, true, COH>(a, it, sl, v, y, lds_pg, chunk, lds_v);
+    else expand_valu_body<DT, kValuTok, true, COH>(a, it, sl, v, y, lds_pg, chunk, lds_v);
   } else {
-    if (it.ntok <= 1) expand_valu_body<DT, 1, false>(a, it, sl, v, y, lds_pg, chunk);
-    else if (it.ntok == 2) expand_valu_body<DT, 2, false>(a, it, sl, v, y, lds_pg, chunk);
-    else expand_valu_body<DT, kValuTok, false>(a, it, sl, v, y, lds_pg, chunk);
+    if (it.ntok <= 1) expand_valu_body<DT, 1, false, COH>(a, it, sl, v, y, lds_pg, chunk, lds_v);
+    else if (it.ntok == 2) expand_valu_body<DT, 2, false, COH>(a, it, sl, v, y, lds_pg, chunk, lds_v);
+    else expand_valu_body<DT, kValuTok, false, COH>(a, it, sl, v, y, lds_pg, chunk, lds_v);
   }
 }
 
@@ -490,7 +512,7 @@ __device__ __forceinline__ f32x4 mfma16(const uint4 a, const uint4 b, const f32x
 constexpr int kSmTok = 32, kSmRows = 32, kSmPitch = 144;  // 128 data bytes + 16 pad per LDS row
 static_assert(kMfmaTokS == kSmTok && kMfmaRows == kSmRows, "host work items must match the kernel's tile");
 
-template <int DT, bool NTW, int DEPTH>
+template <int DT, bool NTW, int DEPTH, bool COH = false>
 __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                   const uint8_t* __restrict__ x, float* __restrict__ v,
                                                   uint8_t (*tile)[2][kSmRows * kSmPitch], int32_t* lds_pt) {
@@ -521,7 +543,7 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
   if (it.j0 == 0) {  // clear v[t, r .. v_stride) for the item's tokens
     for (int i = wave; i < it.ntok; i += 4) {
       const int64_t t = perm[i];
-      for (int j = r + lane; j < vs; j += kWave) v[t * vs + j] = 0.f;
+      for (int j = r + lane; j < vs; j += kWave) st_v<COH>(v + t * vs + j, 0.f);
     }
   }
   __syncthreads();
@@ -662,7 +684,7 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       const int ti = 16 * mt + 4 * g + i;
-      if (ti < it.ntok) v[(int64_t)perm[ti] * vs + it.j0 + 16 * nt + c] = sum[i];
+      if (ti < it.ntok) st_v<COH>(v + (int64_t)perm[ti] * vs + it.j0 + 16 * nt + c, sum[i]);
     }
   }
 }
@@ -693,12 +715,13 @@ __device__ __forceinline__ void split_hi_lo(const float* f, uint4& hi, uint4& lo
 // values of operand row c it will load later (8 of every 32, from 8 g) and the four lane groups
 // combine.  Returns the biased exponent e of the row's largest magnitude, clamped to [1, 253]:
 // scale = 2^(127 - e), inverse = 2^(e - 127).  bf16 shares fp32's exponent range and needs none of this.
+template <bool COH>
 __device__ __forceinline__ uint32_t row_exponent(const float* vrow, int r, int g) {
   float m = 0.f;
   for (int j = 8 * g; j < r; j += 32)
 #pragma unroll
     for (int e = 0; e < 8; ++e)
-      if (j + e < r) m = fmaxf(m, fabsf(vrow[j + e]));
+      if (j + e < r) m = fmaxf(m, fabsf(ld_v<COH>(vrow + j + e)));
   m = fmaxf(m, __shfl_xor(m, 16, 64));
   m = fmaxf(m, __shfl_xor(m, 32, 64));
   uint32_t ex = (__float_as_uint(m) >> 23) & 0xffu;
@@ -709,7 +732,7 @@ __device__ __forceinline__ float exp_scale(uint32_t ex) { return __uint_as_float
 __device__ __forceinline__ float exp_inverse(uint32_t ex) { return __uint_as_float(ex << 23); }
 
 // One K-step (32 rows of B) of the matrix-core expand for one 128-column pass.
-template <int DT, int MT, bool TAIL, bool NTW>
+template <int DT, int MT, bool TAIL, bool NTW, bool COH>
 __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int2* lds_pg, const float* const* vrow,
                                                   uint64_t base, uint64_t rowb, uint32_t lane_b, int r, int jb,
                                                   const float* rs, f32x4 (*acc)[8]) {
@@ -721,7 +744,10 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
   float vf[MT][8];
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
-    if ((!TAIL || j8 + 8 <= r) && (vs & 3) == 0) {
+    if (COH) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) vf[mt][e] = (!TAIL || j8 + e < r) ? ld_v<COH>(vrow[mt] + j8 + e) : 0.f;
+    } else if ((!TAIL || j8 + 8 <= r) && (vs & 3) == 0) {
       const float4 va = *reinterpret_cast<const float4*>(vrow[mt] + j8);
       const float4 vb = *reinterpret_cast<const float4*>(vrow[mt] + j8 + 4);
       vf[mt][0] = va.x; vf[mt][1] = va.y; vf[mt][2] = va.z; vf[mt][3] = va.w;
@@ -781,7 +807,7 @@ __device__ __forceinline__ void expand_mfma_kstep(const LaunchArgs& a, const int
 // 512-column chunk and all MT token tiles, loads its tile of B straight into registers (each tile is
 // used by one wavefront only, so nothing is shared and there is no barrier after the page staging),
 // transposes and multiplies.
-template <int DT, int MT, bool NTW>
+template <int DT, int MT, bool NTW, bool COH>
 __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                       const float* __restrict__ v, uint8_t* __restrict__ y,
                                                       const int2* lds_pg, int chunk, uint64_t base, uint64_t rowb) {
@@ -808,7 +834,7 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
 #pragma unroll
     for (int i = 0; i < 4; ++i) inv[mt][i] = 1.f;
     if constexpr (DT == 0) {
-      const uint32_t ex = row_exponent(vrow[mt], r, g);
+      const uint32_t ex = row_exponent<COH>(vrow[mt], r, g);
       rs[mt] = exp_scale(ex);
 #pragma unroll
       for (int i = 0; i < 4; ++i) inv[mt][i] = exp_inverse((uint32_t)__shfl((int)ex, g * 4 + i, 64));
@@ -826,8 +852,8 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
 #pragma unroll
     for (int i = 0; i < 4; ++i) yq[mt][i] = ldy16(y + ((uint64_t)trow[mt][i] * d_out + nn) * EB);
   int jb = 0;
-  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, rs, acc);
-  if (jb < r) expand_mfma_kstep<DT, MT, true, NTW>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, rs, acc);
+  for (; jb + 32 <= r; jb += 32) expand_mfma_kstep<DT, MT, false, NTW, COH>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, rs, acc);
+  if (jb < r) expand_mfma_kstep<DT, MT, true, NTW, COH>(a, lds_pg, vrow, base, rowb, lane_b, r, jb, rs, acc);
   if (!ok) return;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt) {
@@ -864,7 +890,7 @@ __device__ __forceinline__ void expand_stage_pages(const LaunchArgs& a, const It
 
 // expand, matrix-core item of at most kMfmaTokCols tokens, by a workgroup of 4 wavefronts: stage the
 // page pairs, then every wavefront takes its 128 columns (column-split form above).
-template <int DT>
+template <int DT, bool COH = false>
 __device__ __forceinline__ void expand_mfma_cols_item(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                       const float* __restrict__ v, uint8_t* __restrict__ y,
                                                       int2* lds_pg, int chunk) {
@@ -875,8 +901,8 @@ __device__ __forceinline__ void expand_mfma_cols_item(const LaunchArgs& a, const
   const uint64_t base = (uint64_t)it.rank * EB * ((uint64_t)sl.cum + (uint64_t)sl.d_in) + (uint64_t)n0i * EB;
   expand_stage_pages(a, it, lds_pg, base, rowb, EB);
   __syncthreads();
-  if (item_once(it)) expand_mfma_cols_body<DT, 1, true>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
-  else expand_mfma_cols_body<DT, 1, false>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+  if (item_once(it)) expand_mfma_cols_body<DT, 1, true, COH>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
+  else expand_mfma_cols_body<DT, 1, false, COH>(a, it, sl, v, y, lds_pg, chunk, base, rowb);
 }
 
 // expand, matrix-core item of 17 .. 64 tokens (batches with many large groups: prefill):
@@ -918,7 +944,7 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
   for (int i = 0; i < 4; ++i) trow[i] = __shfl(tc, g * 4 + i, 64);
   float rs = 1.f, inv[4] = {1.f, 1.f, 1.f, 1.f};         // fp16: scale of operand row c, inverses of the result rows
   if constexpr (DT == 0) {
-    const uint32_t ex = row_exponent(vrow, r, g);
+    const uint32_t ex = row_exponent<false>(vrow, r, g);
     rs = exp_scale(ex);
 #pragma unroll
     for (int i = 0; i < 4; ++i) inv[i] = exp_inverse((uint32_t)__shfl((int)ex, g * 4 + i, 64));
@@ -1127,7 +1153,7 @@ __global__ __launch_bounds__(256, kWgPerCu) void k_expand_panel(const LaunchArgs
 // rows (expand) and add their partial sums through LDS in wavefront order, so the result does not
 // depend on timing.
 // ------------------------------------------------------------------------------------------
-template <int DT, int NT, bool NTW>
+template <int DT, int NT, bool NTW, bool COH = false>
 __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const uint8_t* __restrict__ x, float* __restrict__ v,
                                                  int32_t* lds_pt, float (*red)[kShrinkRows * kValuTok]) {
@@ -1143,7 +1169,7 @@ __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const Item
 #pragma unroll
     for (int i = 0; i < NT; ++i)
       if (i < it.ntok)
-        for (int j = r + lane; j < vs; j += kWave) v[tok[i] * vs + j] = 0.f;
+        for (int j = r + lane; j < vs; j += kWave) st_v<COH>(v + tok[i] * vs + j, 0.f);
   }
   if (r == 0) return;  // uniform over the workgroup
 
@@ -1178,7 +1204,7 @@ __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const Item
     const int jj = lane / NT, i = lane % NT;
     const float sum = ((red[0][lane] + red[1][lane]) + red[2][lane]) + red[3][lane];
     const int ti = i == 1 ? it.tok[1] : i == 2 ? it.tok[2] : i == 3 ? it.tok[3] : it.tok[0];
-    if (jj < nrows && i < it.ntok) v[(int64_t)ti * vs + it.j0 + jj] = sum;
+    if (jj < nrows && i < it.ntok) st_v<COH>(v + (int64_t)ti * vs + it.j0 + jj, sum);
   }
 }
 
@@ -1203,10 +1229,10 @@ __global__ __launch_bounds__(256) void k_shrink_coop(const LaunchArgs a, const S
   }
 }
 
-template <int DT, int NT>
+template <int DT, int NT, bool COH = false>
 __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                  const float* __restrict__ v, uint8_t* __restrict__ y, int2* lds_pg,
-                                                 float* red, int chunk) {
+                                                 float* red, int chunk, float* lds_v = nullptr) {
   constexpr int EB = Elt<DT>::B, VEC = Elt<DT>::VEC;
   const int wave = wave_id(), lane = lane_id();
   const int r = it.rank;
@@ -1240,6 +1266,11 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
   const float* vrow[NT];
 #pragma unroll
   for (int i = 0; i < NT; ++i) vrow[i] = v + (int64_t)it.tok[i] * vs;
+  if constexpr (COH) {  // the tokens' rows of v through device-scope loads, once, into LDS (row i at lds_v + i * r)
+#pragma unroll
+    for (int i = 0; i < NT; ++i)
+      for (int j = threadIdx.x; j < r; j += 256) lds_v[i * r + j] = ld_v<true>(vrow[i] + j);
+  }
   __syncthreads();
 
   float acc[NT][VEC];
@@ -1266,7 +1297,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
       unpack<DT>(wq[u], wf);
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
-        const float vj = vrow[i][j + u];
+        const float vj = COH ? lds_v[i * r + j + u] : vrow[i][j + u];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[i][e] = __builtin_fmaf(vj, wf[e], acc[i][e]);
       }
@@ -1282,7 +1313,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
       unpack<DT>(ldw16<false>(a.slab + (pg << lp) + (inpage & pmask)), wf);
 #pragma unroll
       for (int i = 0; i < NT; ++i) {
-        const float vj = vrow[i][j];
+        const float vj = COH ? lds_v[i * r + j] : vrow[i][j];
 #pragma unroll
         for (int e = 0; e < VEC; ++e) acc[i][e] = __builtin_fmaf(vj, wf[e], acc[i][e]);
       }
@@ -1322,6 +1353,140 @@ __global__ __launch_bounds__(256) void k_expand_coop(const LaunchArgs a, const S
   if (it.ntok <= 1) expand_coop_body<DT, 1>(a, it, sl, v, y, lds_pg, red, chunk);
   else if (it.ntok == 2) expand_coop_body<DT, 2>(a, it, sl, v, y, lds_pg, red, chunk);
   else expand_coop_body<DT, kValuTok>(a, it, sl, v, y, lds_pg, red, chunk);
+}
+
+// ------------------------------------------------------------------------------------------
+// Shrink and expand of a small call in one launch.  Workgroup w of a persistent grid of 256-thread
+// workgroups runs tasks w, w + grid, ...: first the shrink tasks of all slots, slot after slot, then the
+// expand tasks; each task is one workgroup's worth of an ordinary launch (a block of 4 records, or one
+// cooperative record, times the 512-column chunk for expand).  An expand task needs every row of v of
+// its slot: a shrink task adds one to its slot's counter once its stores of v have been performed, the
+// task that completes the count publishes it in a few flag words, and an expand task polls one of
+// them before it starts.  A workgroup's tasks ascend, so every shrink task comes behind shrink tasks
+// only and runs without waiting for anything; the grid is no larger than what is resident together.
+// The poll is bounded all the same (spin_limit polls, then the task is given up, counted for the host,
+// and the workgroup goes on).  The sums are those of the separate kernels, in the same order.
+// ------------------------------------------------------------------------------------------
+constexpr int kFusedPg = 4 * kMaxRank * sizeof(int2);                  // expand block: page pairs of four vector-ALU items
+constexpr int kFusedV = kValuTok * kMaxRank * sizeof(float);           // rows of v of one vector-ALU item
+constexpr int kFusedLds = kFusedPg + 4 * kFusedV;                      // the expand block with its four items' rows of v: the largest user
+static_assert(kFusedLds >= 4 * 2 * kSmRows * kSmPitch + kPtWindow * 4, "shrink block: tiles and page-table window");
+static_assert(kFusedLds >= (int)(kMaxRank * sizeof(int2) + 4 * kValuTok * 8 * kWave * sizeof(float)) + kFusedV, "cooperative expand: page pairs, partial sums, rows of v");
+
+template <int DT>
+__global__ __launch_bounds__(256, kWgPerCu) void k_delta_queue(const FusedArgs f, const FusedPtrs p) {
+  __shared__ __align__(16) uint8_t lds[kFusedLds];
+  __shared__ int s_ready;
+  LaunchArgs a;
+  a.slab = f.slab; a.perm = f.perm; a.pt = f.pt; a.items = nullptr; a.slots = f.slots;
+  a.elems_per_rank = f.elems_per_rank; a.n_items = 0; a.pad0 = 0; a.log2_page = f.log2_page; a.v_stride = f.v_stride;
+  a.slot_fastest = 0; a.pad = 0;
+  const int per_slot_e = f.n_e * f.chunks;
+  const int total_s = f.n_s * f.n_slots;
+  const int total = total_s + per_slot_e * f.n_slots;
+  const int wave = wave_id();
+  for (int t = blockIdx.x; t < total; t += gridDim.x) {
+    __syncthreads();  // the previous task is done with the LDS space
+    const bool is_shrink = t < total_s;
+    const int q = is_shrink ? t / f.n_s : (t - total_s) / per_slot_e;
+    const int w = is_shrink ? t - q * f.n_s : (t - total_s) - q * per_slot_e;
+    const SlotRec sl = f.slots[p.slot[q]];
+    if (is_shrink) {
+      // ---- a shrink task of slot q
+      const uint8_t* x = (const uint8_t*)p.x[q];
+      float* v = p.v[q];
+      if (f.coop_s) {
+        int32_t* lds_pt = reinterpret_cast<int32_t*>(lds);
+        auto red = reinterpret_cast<float(*)[kShrinkRows * kValuTok]>(lds + (kPtWindow / 4) * 4);
+        const ItemRec it = load_item(f.items_s + w);
+        if (item_kind(it) == 0) {
+          if (item_once(it)) {
+            if (it.ntok <= 1) shrink_coop_body<DT, 1, true, true>(a, it, sl, x, v, lds_pt, red);
+            else if (it.ntok == 2) shrink_coop_body<DT, 2, true, true>(a, it, sl, x, v, lds_pt, red);
+            else shrink_coop_body<DT, kValuTok, true, true>(a, it, sl, x, v, lds_pt, red);
+          } else {
+            if (it.ntok <= 1) shrink_coop_body<DT, 1, false, true>(a, it, sl, x, v, lds_pt, red);
+            else if (it.ntok == 2) shrink_coop_body<DT, 2, false, true>(a, it, sl, x, v, lds_pt, red);
+            else shrink_coop_body<DT, kValuTok, false, true>(a, it, sl, x, v, lds_pt, red);
+          }
+        }
+      } else {
+        auto tile = reinterpret_cast<uint8_t(*)[2][kSmRows * kSmPitch]>(lds);
+        int32_t* lds_pt = reinterpret_cast<int32_t*>(lds + 4 * 2 * kSmRows * kSmPitch);
+        const ItemRec first = load_item(f.items_s + 4 * w);
+        bool matrix = false;
+        if constexpr (DT != 2) {
+          if (item_kind(first) == 1) {
+            matrix = true;
+            if (item_once(first)) shrink_mfma4_body<DT, true, 2, true>(a, first, sl, x, v, tile, lds_pt);
+            else shrink_mfma4_body<DT, false, 2, true>(a, first, sl, x, v, tile, lds_pt);
+          }
+        }
+        if (!matrix) {
+          const ItemRec it = load_item(f.items_s + 4 * w + wave);
+          if (it.kind >= 0) shrink_valu_item<DT, true>(a, it, sl, x, v, lds_pt + wave * (kPtWindow / 4));
+        }
+      }
+      // the stores of v are device-scope stores; the barrier waits until every wavefront's have been performed,
+      // then one thread counts the task, and the last one of the slot raises the slot's flags
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        const uint32_t done = atomicAdd(&f.queue[q], 1u) + 1u;
+        if (done == p.target[q]) {
+#pragma unroll
+          for (int k = 0; k < kFlagCopies; ++k)
+            __hip_atomic_store(&f.queue[kQueueFlag0 + (q * kFlagCopies + k) * kFlagStride], done, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
+    } else {
+      // ---- an expand task of slot q: wait for the slot's rows of v
+      if (threadIdx.x == 0) {
+        int ready = 0;
+        const uint32_t* flag = &f.queue[kQueueFlag0 + (q * kFlagCopies + (int)(blockIdx.x % kFlagCopies)) * kFlagStride];
+        const uint32_t target = p.target[q];
+        for (uint32_t n = 0; n <= f.spin_limit; ++n) {
+          // (the counters only grow; the difference is taken so that a wrap after 2^32 tasks does no harm)
+          if ((int32_t)(__hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) >= 0) { ready = 1; break; }
+          __builtin_amdgcn_s_sleep(8);
+        }
+        if (!ready) __hip_atomic_fetch_add(f.timeouts, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        s_ready = ready;
+      }
+      __syncthreads();
+      const int ready = __builtin_amdgcn_readfirstlane(s_ready);
+      if (!ready) continue;  // given up: y of this task stays as it was, the host finds the count
+      // (v is read with device-scope loads, issued after the barrier above: they see what the counter covers)
+      const int blk = w / f.chunks, chunk = w - blk * f.chunks;
+      const float* v = p.v[q];
+      uint8_t* y = (uint8_t*)p.y[q];
+      if (f.coop_e) {
+        int2* lds_pg = reinterpret_cast<int2*>(lds);
+        float* red = reinterpret_cast<float*>(lds + kMaxRank * sizeof(int2));
+        float* lds_v = reinterpret_cast<float*>(lds + kMaxRank * sizeof(int2) + 4 * kValuTok * 8 * kWave * sizeof(float));
+        const ItemRec it = load_item(f.items_e + blk);
+        if (item_kind(it) == 0) {
+          if (it.ntok <= 1) expand_coop_body<DT, 1, true>(a, it, sl, v, y, lds_pg, red, chunk, lds_v);
+          else if (it.ntok == 2) expand_coop_body<DT, 2, true>(a, it, sl, v, y, lds_pg, red, chunk, lds_v);
+          else expand_coop_body<DT, kValuTok, true>(a, it, sl, v, y, lds_pg, red, chunk, lds_v);
+        }
+      } else {
+        int2* my_pg = reinterpret_cast<int2*>(lds);
+        const ItemRec first = load_item(f.items_e + 4 * blk);
+        bool matrix = false;
+        if constexpr (DT != 2) {
+          if (item_kind(first) == 1) {
+            matrix = true;
+            expand_mfma_cols_item<DT, true>(a, first, sl, v, y, my_pg, chunk);
+          }
+        }
+        if (!matrix) {
+          const ItemRec it = load_item(f.items_e + 4 * blk + wave);
+          if (it.kind >= 0)
+            expand_valu_item<DT, true>(a, it, sl, v, y, my_pg + wave * kMaxRank, chunk, reinterpret_cast<float*>(lds + kFusedPg + wave * kFusedV));
+        }
+      }
+    }
+  }
 }
 
 // Staged load (Sec. III-B: adapters arrive in a staging area and are then moved into their pages):
@@ -1442,6 +1607,35 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
                     : a.slot_fastest == 2 ? dim3(max_chunks, nb, n_slots) : dim3(nb, max_chunks, n_slots);
     launch(table[mode][dtype], grid, dim3(256), st, first == 0 ? e0 : nullptr, first + step >= n_blocks ? e1 : nullptr, a, p);
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_delta_queue(int dtype, const FusedArgs& f, const FusedPtrs& p, hipStream_t st, hipEvent_t e0, hipEvent_t e1) {
+  typedef void (*Fn)(const FusedArgs, const FusedPtrs);
+  static const Fn table[3] = {k_delta_queue<0>, k_delta_queue<1>, k_delta_queue<2>};
+  if (dtype < 0 || dtype > 2 || f.n_slots < 1 || f.n_slots > kMaxSlotsFused || f.n_s < 0 || f.n_e < 0 || f.chunks < 1 || !f.queue || !f.timeouts)
+    return hipErrorInvalidValue;
+  const int64_t total = ((int64_t)f.n_s + (int64_t)f.n_e * f.chunks) * f.n_slots;
+  if (total <= 0) return hipSuccess;
+  if (total > (1 << 30)) return hipErrorInvalidValue;
+  // a persistent grid: as many workgroups as stay resident together on this device, or fewer if the tasks are fewer
+  static int resident_of[64] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+  if (resident_of[dev] == 0) {
+    int cus = 0, per_cu = 0;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e == hipSuccess) e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, table[dtype], 256, 0);
+    if (e != hipSuccess) return e;
+    if (cus < 1 || per_cu < 1) return hipErrorInvalidValue;
+    resident_of[dev] = cus * (per_cu < kWgPerCu ? per_cu : kWgPerCu);
+  }
+  const int64_t resident = resident_of[dev];
+  const dim3 grid((unsigned)(total < resident ? total : resident));
+  if (e0 || e1) hipExtLaunchKernelGGL(table[dtype], grid, dim3(256), 0, st, e0, e1, 0, f, p);
+  else hipLaunchKernelGGL(table[dtype], grid, dim3(256), 0, st, f, p);
   return hipGetLastError();
 }
 

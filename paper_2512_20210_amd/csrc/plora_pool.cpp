@@ -83,6 +83,10 @@ struct plora_batch {
   size_t cap = 0;
   // offsets inside the image
   size_t off_perm = 0, off_pt = 0;
+  // state of the one-launch form of plora_delta: counters and flags on the device (zero when allocated,
+  // never reset), and the value each slot position's counter will have reached after the launches so far
+  uint32_t* d_queue = nullptr;
+  mutable uint32_t q_target[kMaxSlotsFused] = {};
   // work lists (blocks of 4 records): [op][layout], op 0 = shrink, 1 = expand; layout 0 = longest
   // first (for launches whose fastest grid dimension is the slot), 1 = dealt into 8 interleaved XCD
   // queues
@@ -146,6 +150,13 @@ struct plora_pool {
   hipStream_t aux = nullptr;  // pool-owned side stream that carries the batch images
   std::vector<std::pair<int, int>> run_order;  // scratch of a shrink / expand call, n_slots entries (never grows)
   std::vector<float*> static_v;                // scratch of plora_delta_static, n_slots entries (never grows)
+  // plora_delta on small calls: one launch whose workgroups take shrink and then expand tasks from a queue
+  int64_t fused_max_tasks = 0;        // calls of at most this many workgroup tasks (shrink + expand) take it (0 = never, the
+                                      // default: on this GPU two launches are faster at every call size measured)
+  int64_t fused_spin_limit = 1 << 20; // polls before an expand task gives up waiting for its slot's shrink tasks
+  uint32_t* h_timeouts = nullptr;     // page-locked word the kernel counts given-up tasks in
+  uint32_t* d_timeouts = nullptr;     // the same word as the device sees it
+  uint64_t fused_launches = 0;
   int mfma_shrink_depth = 0;  // runs in flight per matrix-core shrink item: 1, 2, or 0 = by batch and slot shape
   int64_t deep_max_workgroups = 2500;  // shrink launches of at most this many workgroups take the two-runs-in-flight kernel
   int64_t coop_max_workgroups[2] = {192, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
@@ -353,10 +364,16 @@ int plora_pool_create(size_t page_bytes, uint32_t n_pages, const plora_layout* l
     if (e == hipSuccess) e = hipMalloc((void**)&p->d_slots, sizeof(SlotRec) * slots.size());
     if (e == hipSuccess) e = hipStreamCreateWithFlags(&p->aux, hipStreamNonBlocking);
     if (e == hipSuccess) e = hipMemcpy(p->d_slots, slots.data(), sizeof(SlotRec) * slots.size(), hipMemcpyHostToDevice);
+    if (e == hipSuccess) e = hipHostMalloc((void**)&p->h_timeouts, 256, hipHostMallocDefault);
+    if (e == hipSuccess) {
+      *p->h_timeouts = 0;
+      e = hipHostGetDevicePointer((void**)&p->d_timeouts, p->h_timeouts, 0);
+    }
     if (e != hipSuccess) {
       g_last_hip = (int)e; (void)hipGetLastError();
       if (p->own_slab) (void)hipFree(p->slab);
       if (p->d_slots) (void)hipFree(p->d_slots);
+      if (p->h_timeouts) (void)hipHostFree(p->h_timeouts);
       if (p->aux) (void)hipStreamDestroy(p->aux);
       delete p;
       return PLORA_ERR_HIP;
@@ -377,6 +394,7 @@ int plora_pool_destroy(plora_pool* p) {
     }
     if (p->own_slab) (void)hipFree(p->slab);
     if (p->d_slots) (void)hipFree(p->d_slots);
+    if (p->h_timeouts) (void)hipHostFree(p->h_timeouts);
     if (p->aux) (void)hipStreamDestroy(p->aux);
     for (auto& r : p->prof) { (void)hipEventDestroy(r.e0); (void)hipEventDestroy(r.e1); }
     for (hipEvent_t e : p->prof_free) (void)hipEventDestroy(e);
@@ -388,6 +406,7 @@ int plora_pool_destroy(plora_pool* p) {
   for (plora_batch* b : p->batches) {
     if (b->h_img) { if (p->placement_only) ::operator delete(b->h_img); else (void)hipHostFree(b->h_img); }
     if (b->d_img) (void)hipFree(b->d_img);
+    if (b->d_queue) (void)hipFree(b->d_queue);
     if (b->ev_img) (void)hipEventDestroy(b->ev_img);
     for (hipEvent_t e : b->ev_other) (void)hipEventDestroy(e);
     delete b;
@@ -561,6 +580,8 @@ int plora_pool_stats(plora_pool* p, plora_stats* o) {
   o->internal_frag_bytes = o->used_pages * p->P - p->resident_bytes;
   o->loads = p->loads; o->evictions = p->evictions; o->nomem_failures = p->nomem;
   o->h2d_bytes = p->h2d_bytes; o->h2d_copies = p->h2d_copies; o->h2d_ms = p->h2d_ms; o->staged_loads = p->staged_loads;
+  o->fused_launches = p->fused_launches;
+  o->fused_timeouts = p->h_timeouts ? *(volatile uint32_t*)p->h_timeouts : 0;
   return PLORA_OK;
 }
 
@@ -613,6 +634,16 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
   if (k == "mfma_cols_max_group") {
     if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
     p->cols_max_group = (int)value;
+    return PLORA_OK;
+  }
+  if (k == "fused_max_tasks") {
+    if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
+    p->fused_max_tasks = value;
+    return PLORA_OK;
+  }
+  if (k == "fused_spin_limit") {
+    if (value < 0 || value > ((int64_t)1 << 31)) return PLORA_ERR_INVAL;
+    p->fused_spin_limit = value;
     return PLORA_OK;
   }
   if (k == "mfma_shrink_depth") {
@@ -875,6 +906,10 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       b->cap = 0;
       HIP_TRY(hipHostMalloc((void**)&b->h_img, cap, hipHostMallocDefault));
       HIP_TRY(hipMalloc((void**)&b->d_img, cap));
+      if (!b->d_queue) {
+        HIP_TRY(hipMalloc((void**)&b->d_queue, kQueueWords * sizeof(uint32_t)));
+        HIP_TRY(hipMemsetAsync(b->d_queue, 0, kQueueWords * sizeof(uint32_t), p->aux));  // ahead of the image copy below
+      }
     }
     b->cap = cap;
   }
@@ -1054,6 +1089,70 @@ int plora_expand(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_s
   return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);
 }
 
+// plora_delta on a small call: shrink and expand as tasks of one persistent launch (k_delta_queue).  Taken
+// when the call is on the batch's own stream (launches on one stream cannot overlap, and they share the
+// batch's queue state), covers at most kMaxSlotsFused slots and at most fused_max_tasks tasks, and the
+// batch has no panel blocks.  Returns 0 = launched, 1 = not applicable (use the two launches), < 0 = error.
+static int delta_in_one_launch(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* x,
+                               float* const* v, void* const* y, plora_stream s) {
+  if (p->fused_max_tasks <= 0 || n_slots > kMaxSlotsFused || (hipStream_t)s != b->stream || !b->d_queue) return 1;
+  if (b->panel && b->n_heavy[1] > 0) return 1;
+  {
+    // a captured launch would be replayed with this call's counter targets: graphs take the two launches
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing((hipStream_t)s, &cap) != hipSuccess) { (void)hipGetLastError(); return 1; }
+    if (cap != hipStreamCaptureStatusNone) return 1;
+  }
+  for (int q = 0; q < n_slots; ++q)
+    if (!x[q] || !v[q] || ((uintptr_t)x[q] & 15) || ((uintptr_t)v[q] & 15)) return PLORA_ERR_INVAL;
+  const int vec = 16 / p->elt;
+  int chunks = 1;
+  for (int q = 0; q < n_slots; ++q) chunks = std::max(chunks, (int)((p->slots[slot0 + q].d_out + kWave * vec - 1) / (kWave * vec)));
+  FusedArgs f;
+  // the same choice of lists as the separate launches make: cooperative records for the smallest calls
+  const bool coop_s = p->coop_max_workgroups[0] > 0 && b->n_items[0][2] > 0 &&
+                      (int64_t)n_slots * (b->n_items[0][0] / 4) <= p->coop_max_workgroups[0];
+  const bool coop_e = p->coop_max_workgroups[1] > 0 && b->n_items[1][2] > 0 &&
+                      (int64_t)n_slots * (b->n_items[1][0] / 4) * chunks <= p->coop_max_workgroups[1];
+  f.coop_s = coop_s; f.coop_e = coop_e;
+  f.n_s = coop_s ? b->n_items[0][2] : b->n_items[0][0] / 4;
+  f.n_e = coop_e ? b->n_items[1][2] : b->n_items[1][0] / 4;
+  const int64_t tasks = ((int64_t)f.n_s + (int64_t)f.n_e * chunks) * n_slots;
+  if (tasks > p->fused_max_tasks) return 1;
+  if (tasks == 0) return 0;
+  f.items_s = (const ItemRec*)(b->d_img + b->off_items[0][coop_s ? 2 : 0]);
+  f.items_e = (const ItemRec*)(b->d_img + b->off_items[1][coop_e ? 2 : 0]);
+  f.slab = p->slab;
+  f.perm = (const int32_t*)(b->d_img + b->off_perm);
+  f.pt = (const int32_t*)(b->d_img + b->off_pt);
+  f.slots = p->d_slots;
+  f.queue = b->d_queue;
+  f.timeouts = p->d_timeouts;
+  f.elems_per_rank = p->C;
+  f.chunks = chunks; f.n_slots = n_slots;
+  f.log2_page = p->log2P; f.v_stride = p->max_rank;
+  f.spin_limit = (uint32_t)std::min<int64_t>(p->fused_spin_limit, 0xffffffffll);
+  f.pad = 0;
+  FusedPtrs ptrs;
+  for (int q = 0; q < n_slots; ++q) {
+    ptrs.x[q] = x[q]; ptrs.v[q] = v[q]; ptrs.y[q] = y[q]; ptrs.slot[q] = slot0 + q;
+    ptrs.target[q] = b->q_target[q] + (uint32_t)f.n_s;
+  }
+  for (int q = n_slots; q < kMaxSlotsFused; ++q) { ptrs.x[q] = nullptr; ptrs.v[q] = nullptr; ptrs.y[q] = nullptr; ptrs.slot[q] = 0; ptrs.target[q] = 0; }
+  plora_pool::ProfRec rec{2, nullptr, nullptr};
+  if (p->profiling) {
+    for (hipEvent_t* ev : {&rec.e0, &rec.e1}) {
+      if (!p->prof_free.empty()) { *ev = p->prof_free.back(); p->prof_free.pop_back(); }
+      else HIP_TRY(hipEventCreate(ev));
+    }
+  }
+  HIP_TRY(launch_delta_queue(p->dtype, f, ptrs, (hipStream_t)s, rec.e0, rec.e1));
+  for (int q = 0; q < n_slots; ++q) b->q_target[q] = ptrs.target[q];  // the launch is queued: its shrink tasks will count
+  if (p->profiling) p->prof.push_back(rec);
+  p->fused_launches++;
+  return 0;
+}
+
 int plora_delta(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_slots, const void* const* x, float* const* v,
                 void* const* y, plora_stream s) {
   if (!p || !b || !b->open || b->pool != p || p->placement_only) return PLORA_ERR_INVAL;
@@ -1062,6 +1161,8 @@ int plora_delta(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t n_sl
   if (!x || !v || !y) return PLORA_ERR_INVAL;
   for (int q = 0; q < n_slots; ++q)  // the second half's arguments, before anything is queued
     if (!y[q] || ((uintptr_t)y[q] & 15)) return PLORA_ERR_INVAL;
+  const int fused = delta_in_one_launch(p, b, slot0, n_slots, x, v, y, s);
+  if (fused != 1) return fused < 0 ? fused : PLORA_OK;  // done in one launch, or an error
   const int rc = run_slots(p, b, slot0, n_slots, x, (void* const*)v, s, true);
   if (rc != PLORA_OK) return rc;
   return run_slots(p, b, slot0, n_slots, (const void* const*)v, y, s, false);
@@ -1089,7 +1190,7 @@ int plora_profile(plora_pool* p, int enable) {
 
 int plora_profile_read(plora_pool* p, double* ms, uint64_t* launches) {
   if (!p || !ms || !launches || p->placement_only) return PLORA_ERR_INVAL;
-  for (int k = 0; k < 2; ++k) { ms[k] = 0.0; launches[k] = 0; }
+  for (int k = 0; k < 3; ++k) { ms[k] = 0.0; launches[k] = 0; }
   for (auto& r : p->prof) {
     HIP_TRY(hipEventSynchronize(r.e1));
     float t = 0.f;

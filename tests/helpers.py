@@ -96,15 +96,19 @@ class Case:
               for s in slots]
         if y0_fill is not None:
             y0 = [np.full_like(y, y0_fill) for y in y0]
-        # GPU side: with the cooperative kernels of small calls; with the panel kernel for every large
-        # group (as in a prefill batch) and two runs in flight in every matrix-core shrink item, through
-        # the one-call form plora_delta; and with the library's own choices last (its outputs are
-        # returned).  Each entry: (cooperative limit, panel_min_blocks, mfma_shrink_depth, entry points).
-        for coop, panel, depth, api in getattr(self, "kernel_modes", ((1 << 30, 8, 1, "pair"), (0, 1, 2, "delta"), (0, 8, 0, "pair"))):
+        # GPU side: with the cooperative kernels of small calls, as two calls and through the one-call form
+        # plora_delta (one launch over a task queue); with the panel kernel for every large group (as in a
+        # prefill batch) and two runs in flight in every matrix-core shrink item, through plora_delta
+        # (block lists in the one launch when the batch has no panel blocks); and with the library's own
+        # choices last (its outputs are returned).  Each entry: (cooperative limit, panel_min_blocks,
+        # mfma_shrink_depth, entry points).
+        for coop, panel, depth, api in getattr(self, "kernel_modes", ((1 << 30, 8, 1, "pair"), (1 << 30, 8, 1, "delta"), (0, 1, 2, "delta"),
+                                                                      (0, 8, 0, "pair"))):
             self.gpool.set_option("coop_max_workgroups_shrink", coop)
             self.gpool.set_option("coop_max_workgroups_expand", coop)
             self.gpool.set_option("panel_min_blocks", panel)
             self.gpool.set_option("mfma_shrink_depth", depth)
+            self.gpool.set_option("fused_max_tasks", 1 << 20 if api == "delta" else 0)  # plora_delta as one launch where it applies
             out = self._run_gpu(t2a, slots, xs, y0, check, api)
         return out
 

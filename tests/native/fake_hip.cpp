@@ -235,6 +235,24 @@ hipError_t hipHostMalloc(void** ptr, size_t size, unsigned int) {
   return hipSuccess;
 }
 
+hipError_t hipStreamIsCapturing(hipStream_t, hipStreamCaptureStatus* status) {
+  *status = hipStreamCaptureStatusNone;
+  return hipSuccess;
+}
+
+hipError_t hipMemsetAsync(void* dst, int value, size_t n, hipStream_t stream) {
+  Op op;
+  op.kind = Op::KERNEL;
+  op.fn = [=] { std::memset(dst, value, n); };
+  S(stream)->q.push_back(std::move(op));
+  return hipSuccess;
+}
+
+hipError_t hipHostGetDevicePointer(void** dev, void* host, unsigned int) {
+  *dev = host;  // "device" memory is host memory here
+  return hipSuccess;
+}
+
 hipError_t hipFree(void* ptr) {
   if (!ptr) return hipSuccess;
   fakehip::drain();  // frees synchronise with the device

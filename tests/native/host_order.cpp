@@ -81,6 +81,18 @@ hipError_t launch_expand(int, const LaunchArgs& a, const SlotPtrs&, int, int, in
   fakehip::enqueue_kernel(st, [a, expect] { kernel_body(a, expect); });
   return hipSuccess;
 }
+// The one-launch form reads both lists (and the same pages) on its stream.
+hipError_t launch_delta_queue(int, const FusedArgs& f, const FusedPtrs&, hipStream_t st, hipEvent_t, hipEvent_t) {
+  auto expect = g_expect;
+  for (int op = 0; op < 2; ++op) {
+    LaunchArgs a{};
+    a.slab = f.slab; a.perm = f.perm; a.pt = f.pt; a.slots = f.slots; a.elems_per_rank = f.elems_per_rank; a.log2_page = f.log2_page;
+    a.items = op ? f.items_e : f.items_s;
+    a.n_items = (op ? f.n_e : f.n_s) * ((op ? f.coop_e : f.coop_s) ? 1 : 4);
+    fakehip::enqueue_kernel(st, [a, expect] { kernel_body(a, expect); });
+  }
+  return hipSuccess;
+}
 // The scatter of a staged load, done for real when the stream reaches it (device memory is host memory here).
 hipError_t launch_scatter(const uint8_t* staging, uint8_t* slab, int log2_page, uint64_t bytes, const int32_t* pt,
                           uint32_t n_pages, hipStream_t st) {

@@ -16,6 +16,7 @@ namespace plora {
 hipError_t launch_shrink(int, const LaunchArgs&, const SlotPtrs&, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 hipError_t launch_expand(int, const LaunchArgs&, const SlotPtrs&, int, int, int, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 hipError_t launch_scatter(const uint8_t*, uint8_t*, int, uint64_t, const int32_t*, uint32_t, hipStream_t) { return hipSuccess; }
+hipError_t launch_delta_queue(int, const FusedArgs&, const FusedPtrs&, hipStream_t, hipEvent_t, hipEvent_t) { return hipSuccess; }
 uint64_t static_scratch_bytes() { return 0; }
 hipError_t static_scratch(void**) { return hipErrorNotSupported; }
 }  // namespace plora
