@@ -309,6 +309,22 @@ int plora_manager_state(plora_manager* manager, int32_t id);
 int plora_manager_get_stats(plora_manager* manager, plora_manager_stats* out);
 int plora_manager_log(plora_manager* manager, int32_t* out, int64_t cap_pairs, int64_t* n_pairs, int32_t clear);
 
+/* Page size from workload characteristics (the paper's discussion section names adaptive page sizes as
+ * future work and says no more; Sec. III-C fixes only that an adapter of S bytes takes ceil(S / P) pages).
+ * This library's reading: among the powers of two in [min_page, max_page], take the LARGEST page size whose
+ * expected internal fragmentation,
+ *     frag(P) = sum_k weight_k * (ceil(S_k / P) * P - S_k)  /  sum_k weight_k * ceil(S_k / P) * P ,
+ * over the ranks the workload is expected to hold (S_k = bytes of a rank-ranks[k] adapter of this layout,
+ * weight_k >= 0 its expected share of the resident adapters) stays at or below max_internal_frag: larger
+ * pages mean fewer page-table entries per batch and fewer, longer copies per load, and the bound keeps what
+ * they waste in check.  If no candidate meets the bound, the candidate with the smallest frag (the smaller
+ * page on a tie).  Host only.  page_bytes_out / frag_out (may be NULL): the choice and its frag.
+ * INVAL for n < 1, a rank < 1, a negative or all-zero weight vector, page bounds that are not powers of two
+ * >= 4096 with min_page <= max_page, or a bound outside [0, 1). */
+int plora_suggest_page_bytes(const plora_layout* layout, const int32_t* ranks, const double* weights, int32_t n,
+                             double max_internal_frag, size_t min_page, size_t max_page, size_t* page_bytes_out,
+                             double* frag_out);
+
 /* Measurement aids for benchmarks; no part of the method (Sec. V-A asks for throughput and memory
  * figures, which want a roof measured on the same GPU beside the published peaks).
  * plora_probe_stream runs a bare kernel, 3 warm-up launches and then `iters` timed ones on `stream`,

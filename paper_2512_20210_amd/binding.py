@@ -22,7 +22,8 @@ __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS",
            "plora_predictor_loss_grad", "plora_predictor_set_threads", "LstmPredictor",
            "plora_manager_create", "plora_manager_destroy", "plora_manager_set_adapter", "plora_manager_set_prediction",
            "plora_manager_request", "plora_manager_prefetch", "plora_manager_scores", "plora_manager_residents",
-           "plora_manager_state", "plora_manager_get_stats", "plora_manager_log", "ResidencyManager"]
+           "plora_manager_state", "plora_manager_get_stats", "plora_manager_log", "ResidencyManager",
+           "plora_suggest_page_bytes"]
 
 PLORA_OK, PLORA_ERR_INVAL, PLORA_ERR_NOMEM, PLORA_ERR_EXISTS = 0, -1, -2, -3
 PLORA_ERR_NOTFOUND, PLORA_ERR_BUSY, PLORA_ERR_HIP, PLORA_ERR_LIMIT = -4, -5, -6, -7
@@ -99,6 +100,8 @@ lib.plora_manager_residents.argtypes = [_vp, _vp, _i32, C.POINTER(_i32)]
 lib.plora_manager_state.argtypes = [_vp, _i32]
 lib.plora_manager_get_stats.argtypes = [_vp, C.POINTER(_ManagerStats)]
 lib.plora_manager_log.argtypes = [_vp, _vp, C.c_int64, C.POINTER(C.c_int64), _i32]
+lib.plora_suggest_page_bytes.argtypes = [C.POINTER(_Layout), _vp, _vp, _i32, C.c_double, C.c_size_t, C.c_size_t,
+                                         C.POINTER(C.c_size_t), C.POINTER(C.c_double)]
 
 
 class _PredictorConfig(C.Structure):
@@ -597,3 +600,18 @@ class ResidencyManager:
         rc, a = plora_manager_log(self.h, clear)
         _check("plora_manager_log", rc)
         return [tuple(x) for x in a.tolist()]
+
+
+def plora_suggest_page_bytes(d_in, d_out, dtype, ranks, weights, max_internal_frag=0.02, min_page=4096, max_page=2 << 20):
+    """-> (status, page_bytes, expected internal fragmentation at that page size)."""
+    di = np.ascontiguousarray(d_in, dtype=np.int32)
+    do = np.ascontiguousarray(d_out, dtype=np.int32)
+    lay = _Layout(len(di), di.ctypes.data_as(C.POINTER(C.c_int32)), do.ctypes.data_as(C.POINTER(C.c_int32)), dtype, 1, 1)
+    r = np.ascontiguousarray(ranks, dtype=np.int32)
+    w = np.ascontiguousarray(weights, dtype=np.float64)
+    if len(r) != len(w):
+        return PLORA_ERR_INVAL, 0, 0.0
+    page, frag = C.c_size_t(0), C.c_double(0.0)
+    rc = lib.plora_suggest_page_bytes(C.byref(lay), r.ctypes.data, w.ctypes.data, len(r), max_internal_frag, min_page, max_page,
+                                      C.byref(page), C.byref(frag))
+    return rc, page.value, frag.value

@@ -173,6 +173,45 @@ int load_with_eviction(plora_manager* m, int32_t id, plora_stream stream, bool s
 
 extern "C" {
 
+int plora_suggest_page_bytes(const plora_layout* lay, const int32_t* ranks, const double* weights, int32_t n,
+                             double max_frag, size_t min_page, size_t max_page, size_t* page_out, double* frag_out) {
+  if (!lay || !lay->d_in || !lay->d_out || lay->n_slots < 1 || !ranks || !weights || n < 1) return PLORA_ERR_INVAL;
+  if (!(max_frag >= 0.0) || !(max_frag < 1.0)) return PLORA_ERR_INVAL;
+  if (min_page < 4096 || (min_page & (min_page - 1)) || (max_page & (max_page - 1)) || max_page < min_page) return PLORA_ERR_INVAL;
+  if (lay->dtype < 0 || lay->dtype > 2) return PLORA_ERR_INVAL;
+  const uint64_t elt = lay->dtype == PLORA_F32 ? 4 : 2;
+  uint64_t c = 0;
+  for (int s = 0; s < lay->n_slots; ++s) {
+    if (lay->d_in[s] <= 0 || lay->d_out[s] <= 0) return PLORA_ERR_INVAL;
+    c += (uint64_t)lay->d_in[s] + (uint64_t)lay->d_out[s];
+  }
+  double wsum = 0.0;
+  for (int32_t k = 0; k < n; ++k) {
+    if (ranks[k] < 1 || !(weights[k] >= 0.0)) return PLORA_ERR_INVAL;
+    wsum += weights[k];
+  }
+  if (!(wsum > 0.0)) return PLORA_ERR_INVAL;
+  size_t best = 0, least = 0;
+  double best_frag = 0.0, least_frag = 2.0;
+  for (size_t P = min_page;; P <<= 1) {
+    double wasted = 0.0, held = 0.0;
+    for (int32_t k = 0; k < n; ++k) {
+      const uint64_t S = (uint64_t)ranks[k] * elt * c;
+      const uint64_t pages = (S + P - 1) / P;
+      wasted += weights[k] * (double)(pages * P - S);
+      held += weights[k] * (double)(pages * P);
+    }
+    const double frag = wasted / held;
+    if (frag <= max_frag) { best = P; best_frag = frag; }            // candidates ascend: the last that meets the bound is the largest
+    if (frag < least_frag) { least = P; least_frag = frag; }         // strict: the smaller page wins a tie
+    if (P >= max_page) break;
+  }
+  if (!best) { best = least; best_frag = least_frag; }
+  if (page_out) *page_out = best;
+  if (frag_out) *frag_out = best_frag;
+  return PLORA_OK;
+}
+
 int plora_manager_create(plora_pool* pool, int32_t n_adapters, const plora_manager_config* cfg, plora_manager** out) {
   if (!pool || !cfg || !out || n_adapters < 1) return PLORA_ERR_INVAL;
   if (!(cfg->alpha >= 0.0) || !(cfg->beta >= 0.0) || !(cfg->gamma >= 0.0) || cfg->window < 1 || !(cfg->theta >= 0.0) || !(cfg->theta <= 1.0))

@@ -11,11 +11,13 @@ namespace {
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
-// Every workgroup walks over tiles of the two buffers in turn, grid-stride: a tile of `w_tile` bytes of
-// `w` is read with streaming 16-byte loads (the weights of an item), then a tile of `y_tile` bytes of `y`
-// is read, changed and written back with streaming accesses (the rows of y of the item's tokens).
-// y_tile = 0 gives the plain streaming read.  What is read is folded into a value that is stored only
-// if it has a bit pattern that does not occur, so the loads cannot be dropped.
+// Every workgroup walks over tiles of the two buffers in turn, grid-stride.  For a tile it first requests
+// its piece of `y` (y_tile bytes, at most 16 bytes per thread and pass), then reads its piece of `w`
+// (w_tile bytes) with streaming 16-byte loads, four in flight per thread, and finally writes the changed
+// piece of y back with streaming stores: the order in which the expand kernels touch the rows of y of an
+// item's tokens and the item's weights.  y_tile = 0 gives the plain streaming read.  What is read is
+// folded into a value that is stored only if it has a bit pattern that does not occur, so the loads cannot
+// be dropped.
 __global__ __launch_bounds__(256) void k_probe(const uint8_t* __restrict__ w, uint64_t w_bytes, uint32_t w_tile,
                                                 uint8_t* __restrict__ y, uint64_t y_bytes, uint32_t y_tile,
                                                 uint32_t* __restrict__ sink) {
@@ -23,22 +25,27 @@ __global__ __launch_bounds__(256) void k_probe(const uint8_t* __restrict__ w, ui
   u32x4_t fold = {0u, 0u, 0u, 0u};
   for (uint64_t t = blockIdx.x; t < n_tiles; t += gridDim.x) {
     const uint8_t* wp = w + t * w_tile;
-    for (uint32_t o = threadIdx.x * 16u; o < w_tile; o += 256u * 16u * 4u) {
-      u32x4_t q[4];
+    uint8_t* yp = y_tile ? y + (t * y_tile) % y_bytes : nullptr;
+    for (uint32_t yo = 0; yo < (y_tile ? y_tile : 1u); yo += 256u * 16u) {
+      const uint32_t mine = yo + threadIdx.x * 16u;
+      const bool has_y = y_tile && mine < y_tile;
+      u32x4_t yq = {0u, 0u, 0u, 0u};
+      if (has_y) yq = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(yp + mine));
+      if (yo == 0) {  // the weights of the tile go with the first pass over y
+        for (uint32_t o = threadIdx.x * 16u; o < w_tile; o += 256u * 16u * 4u) {
+          u32x4_t q[4];
 #pragma unroll
-      for (int u = 0; u < 4; ++u) {
-        const uint32_t ou = o + (uint32_t)u * 256u * 16u;
-        q[u] = ou < w_tile ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wp + ou)) : fold;
+          for (int u = 0; u < 4; ++u) {
+            const uint32_t ou = o + (uint32_t)u * 256u * 16u;
+            q[u] = ou < w_tile ? __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(wp + ou)) : fold;
+          }
+#pragma unroll
+          for (int u = 0; u < 4; ++u) fold ^= q[u];
+        }
       }
-#pragma unroll
-      for (int u = 0; u < 4; ++u) fold ^= q[u];
-    }
-    if (y_tile) {
-      uint8_t* yp = y + (t * y_tile) % y_bytes;
-      for (uint32_t o = threadIdx.x * 16u; o < y_tile; o += 256u * 16u) {
-        u32x4_t q = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(yp + o));
-        q += fold.x & 1u;
-        __builtin_nontemporal_store(q, reinterpret_cast<u32x4_t*>(yp + o));
+      if (has_y) {
+        yq += fold.x & 1u;
+        __builtin_nontemporal_store(yq, reinterpret_cast<u32x4_t*>(yp + mine));
       }
     }
   }
