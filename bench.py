@@ -566,7 +566,8 @@ def main():
                          "shrink, 2500 for expand; 0 = never)")
     ap.add_argument("--api", default="pair", choices=["pair", "delta"], help="plora_shrink + plora_expand per call, or plora_delta")
     ap.add_argument("--opt", action="append", default=[], help="key=value passed to plora_pool_set_option (repeatable)")
-    ap.add_argument("--no-probes", action="store_true", help="skip the streaming / copy probes and the per-layer-call leg")
+    ap.add_argument("--no-probes", action="store_true", help="skip the streaming / copy probes")
+    ap.add_argument("--no-per-layer", action="store_true", help="skip the leg that repeats the steps with one call per layer (4 slots)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true")
     ap.add_argument("--share-qkv-x", action="store_true", help="k and v slots of a layer read the q slot's x buffer (as in a transformer layer); x is then counted once per group")
@@ -675,7 +676,7 @@ def main():
         "pool_page_util": round(w.stats_after_load["used_pages"] / w.stats_after_load["n_pages"], 4),
         "roofline": roof,
     }
-    if not args.no_probes:
+    if not args.no_per_layer:
         # the same steps as a layer-by-layer decoder has to issue them: one call per layer (4 slots)
         if lay.n_slots > 4 and lay.n_slots % 4 == 0 and spc == lay.n_slots:
             n = min(args.steps, 200)
@@ -692,6 +693,7 @@ def main():
                                       "value": round(b4 / dt / 1e9, 1), "unit": "GB/s",
                                       "pct_of_hbm_peak": round(100.0 * b4 / dt / 1e9 / HBM_PEAK_GBS, 2),
                                       "tokens_per_s": round(sum(len(timed[i % len(timed)]) for i in range(n)) / dt, 1)}
+    if not args.no_probes:
         probes = streaming_probes(w.P, w.stream, lay, ab[0])
         out["streaming_roof"] = probes
         if probes.get("read_gbs"):

@@ -218,6 +218,10 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * shrink item keeps in flight per wavefront; 0 lets the library choose per launch (2 when the batch's
  * matrix-core token tiles are at least half full on average, as in prefill, when a slot of the launch
  * has d_in > 4096, or when the launch has at most 2500 workgroups; else 1).  Results do not depend on it.
+ * "contig_fast_path" (0 or 1, default 1; for adapters loaded afterwards): an adapter whose pages are
+ * physically consecutive is handed to the kernels by its first page instead of its page table (no table
+ * entries in the batch's image, one dependent read less at the head of every work item); 0 treats every
+ * adapter alike.  Results do not depend on it.
  * "fused_max_tasks" (0 .. 2^30, default 0 = never): plora_delta calls of at most this many workgroup
  * tasks run as one launch (see plora_delta; measured slower than the two launches on MI355X at every call
  * size, hence off).  "fused_spin_limit" (0 .. 2^31, default 2^20): polls of a

@@ -20,6 +20,8 @@ constexpr int kMfmaCols = 128;          // columns of B per matrix-core expand p
 constexpr int kPtWindow = 1024;         // page-table entries a shrink item may stage in LDS
 constexpr int kMaxRank = 512;           // rows of B an expand item may stage page pairs for (4 KiB of LDS)
 constexpr int kItemOnce = 0x100;        // flag in ItemRec::kind
+constexpr int kItemContig = 0x200;      // flag in ItemRec::kind: the adapter's pages are physically consecutive and pt_off
+                                        // is its first physical page (no page table to read)
 constexpr int kXcds = 8;                // consecutive workgroups go to consecutive XCDs
 
 // One wavefront's worth of work, self-contained so that a wavefront needs a single 32-byte read
@@ -31,7 +33,7 @@ struct ItemRec {
   int16_t rank;    // rank of the adapter (0 = tokens without adapter: shrink only clears v)
   int16_t j0;      // shrink: first row of A;  expand: unused
   float scale;
-  int32_t pt_off;  // first entry of the adapter's page table in the batch's table array
+  int32_t pt_off;  // first entry of the adapter's page table in the batch's table array (kItemContig: first physical page)
   int32_t tok[4];  // vector-ALU item (kValuTok <= 4): the token indices (unused entries repeat the last one);
                    // matrix-core item: tok[0] = index of the item's first token in perm
 };

@@ -102,6 +102,10 @@ __device__ __forceinline__ int item_kind(const ItemRec& it) { return it.kind < 0
 __device__ __forceinline__ bool item_once(const ItemRec& it) {
   return it.kind >= 0 && (it.kind & kItemOnce) != 0;
 }
+// Record flag: the adapter lies on consecutive physical pages from page pt_off on, so its page-table
+// entries follow from their index and need not be fetched (one dependent trip to memory less at the
+// head of the item).
+__device__ __forceinline__ bool item_contig(const ItemRec& it) { return it.kind >= 0 && (it.kind & kItemContig) != 0; }
 // y is read once and written once per step: streaming (non-temporal) loads and stores, so that its
 // lines neither stay in the caches nor wait there to be written back during the next kernel.
 __device__ __forceinline__ uint4 ldy16(const void* p) {
@@ -309,7 +313,9 @@ __device__ __forceinline__ void shrink_valu_body(const LaunchArgs& a, const Item
   if (r > 0) {
     const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
     const int32_t* ptg = a.pt + it.pt_off + win0;
-    for (uint32_t i = lane; i < win_n; i += kWave) lds_pt[i] = ptg[i];
+    const bool contig = item_contig(it);
+    const int32_t page0 = it.pt_off + (int32_t)win0;
+    for (uint32_t i = lane; i < win_n; i += kWave) lds_pt[i] = contig ? page0 + (int32_t)i : ptg[i];
   }
   if (it.j0 == 0) {  // the first row block of a token group also clears the unused tail of v
 #pragma unroll
@@ -370,11 +376,12 @@ __device__ __forceinline__ void stage_row_pages(const LaunchArgs& a, const ItemR
                                                 uint64_t rowb, uint32_t piece_bytes, int2* lds_pg) {
   const int lp = a.log2_page;
   const int32_t* ptg = a.pt + it.pt_off;
+  const bool contig = item_contig(it);
   for (int j = lane_id(); j < it.rank; j += kWave) {
     const uint64_t vo = base + (uint64_t)j * rowb;
     const uint32_t q0 = (uint32_t)(vo >> lp);
     const uint32_t q1 = imin((int)((vo + piece_bytes - 1) >> lp), n_pt - 1);
-    lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
+    lds_pg[j] = contig ? make_int2(it.pt_off + (int)q0, it.pt_off + (int)q1) : make_int2(ptg[q0], ptg[q1]);
   }
 }
 
@@ -531,7 +538,11 @@ __device__ __forceinline__ void shrink_mfma4_body(const LaunchArgs& a, const Ite
   const uint32_t win0 = (uint32_t)(base >> lp);
   const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
   const int32_t* ptg = a.pt + it.pt_off + win0;
-  for (uint32_t i = tid; i < win_n; i += 256) lds_pt[i] = ptg[i];
+  {
+    const bool contig = item_contig(it);
+    const int32_t page0 = it.pt_off + (int32_t)win0;
+    for (uint32_t i = tid; i < win_n; i += 256) lds_pt[i] = contig ? page0 + (int32_t)i : ptg[i];
+  }
 
   uint64_t wrow[4];          // virtual offsets of the 4 rows of A this lane stages
   const uint8_t* xrow[4];    // and of its 4 token rows
@@ -880,11 +891,12 @@ __device__ __forceinline__ void expand_stage_pages(const LaunchArgs& a, const It
   const int r = it.rank, lp = a.log2_page;
   const int n_pt = table_len(a, r, EB);
   const int32_t* ptg = a.pt + it.pt_off;
+  const bool contig = item_contig(it);
   for (int j = threadIdx.x; j < r; j += 256) {
     const uint64_t vo = base + (uint64_t)j * rowb;
     const uint32_t q0 = (uint32_t)(vo >> lp);
     const uint32_t q1 = imin((int)((vo + 1023) >> lp), n_pt - 1);
-    lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
+    lds_pg[j] = contig ? make_int2(it.pt_off + (int)q0, it.pt_off + (int)q1) : make_int2(ptg[q0], ptg[q1]);
   }
 }
 
@@ -1180,7 +1192,11 @@ __device__ __forceinline__ void shrink_coop_body(const LaunchArgs& a, const Item
   const uint32_t win0 = (uint32_t)(base >> lp);
   const uint32_t win_n = (uint32_t)((base + (uint64_t)nrows * rowb - 1) >> lp) - win0 + 1;
   const int32_t* ptg = a.pt + it.pt_off + win0;
-  for (uint32_t i = threadIdx.x; i < win_n; i += 256) lds_pt[i] = ptg[i];
+  {
+    const bool contig = item_contig(it);
+    const int32_t page0 = it.pt_off + (int32_t)win0;
+    for (uint32_t i = threadIdx.x; i < win_n; i += 256) lds_pt[i] = contig ? page0 + (int32_t)i : ptg[i];
+  }
   __syncthreads();
 
   float acc[kShrinkRows][NT];
@@ -1250,11 +1266,12 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
   {
     const int n_pt = table_len(a, r, EB);
     const int32_t* ptg = a.pt + it.pt_off;
+    const bool contig = item_contig(it);
     for (int j = threadIdx.x; j < r; j += 256) {
       const uint64_t vo = base + (uint64_t)j * rowb;
       const uint32_t q0 = (uint32_t)(vo >> lp);
       const uint32_t q1 = imin((int)((vo + kWave * 16 - 1) >> lp), n_pt - 1);
-      lds_pg[j] = make_int2(ptg[q0], ptg[q1]);
+      lds_pg[j] = contig ? make_int2(it.pt_off + (int)q0, it.pt_off + (int)q1) : make_int2(ptg[q0], ptg[q1]);
     }
   }
   // wavefront w finishes token w: its row of y is requested now

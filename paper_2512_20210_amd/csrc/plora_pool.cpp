@@ -44,6 +44,7 @@ struct Adapter {
   float scale = 0.f;
   uint64_t bytes = 0;
   std::vector<int32_t> pt;
+  bool contig = false;  // the pages are physically consecutive: kernels derive the table from pt[0]
   hipEvent_t ev_start = nullptr, ev_ready = nullptr;  // created on first use, reused
   bool copy_pending = false;                          // ready event not yet observed complete
   int pins = 0;
@@ -157,6 +158,7 @@ struct plora_pool {
   uint32_t* h_timeouts = nullptr;     // page-locked word the kernel counts given-up tasks in
   uint32_t* d_timeouts = nullptr;     // the same word as the device sees it
   uint64_t fused_launches = 0;
+  int contig_fast_path = 1;   // adapters on consecutive pages: their items carry the first page instead of a table offset
   int mfma_shrink_depth = 0;  // runs in flight per matrix-core shrink item: 1, 2, or 0 = by batch and slot shape
   int64_t deep_max_workgroups = 2500;  // shrink launches of at most this many workgroups take the two-runs-in-flight kernel
   int64_t coop_max_workgroups[2] = {192, 2500};  // [shrink, expand]: calls whose ordinary launch would have at
@@ -511,6 +513,7 @@ int plora_load_adapter(plora_pool* p, int32_t id, int32_t rank, float scale, con
     p->h2d_bytes += S;
   }
   a.present = true; a.rank = rank; a.scale = scale; a.bytes = S; a.pins = 0; a.last_use.clear();
+  a.contig = p->contig_fast_path && a.pt.back() - a.pt.front() + 1 == (int32_t)a.pt.size();
   p->loads++; p->resident_adapters++; p->resident_bytes += S;
   if (pt_out) *pt_out = a.pt.data();
   if (n_out) *n_out = (uint32_t)m;
@@ -646,6 +649,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->fused_spin_limit = value;
     return PLORA_OK;
   }
+  if (k == "contig_fast_path") {
+    if (value != 0 && value != 1) return PLORA_ERR_INVAL;
+    p->contig_fast_path = (int)value;
+    return PLORA_OK;
+  }
   if (k == "mfma_shrink_depth") {
     if (value < 0 || value > 2) return PLORA_ERR_INVAL;
     p->mfma_shrink_depth = (int)value;
@@ -745,12 +753,12 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     for (int k = 0; k < 2; ++k) wl[op][k].clear();
   std::vector<ItemRec>& tg = p->wl_tg;  // one vector-ALU record per token group of the current adapter
   // the vector-ALU records of one adapter group: token groups of kValuTok tokens
-  auto token_groups = [&](int16_t rank, float scale, int32_t pt_off, int32_t start, int32_t n) {
+  auto token_groups = [&](int16_t rank, float scale, int32_t pt_off, int16_t contig, int32_t start, int32_t n) {
     tg.clear();
     for (int32_t t0 = 0; t0 < n; t0 += kValuTok) {
       const int16_t nt = (int16_t)std::min(kValuTok, n - t0);
       // one token group: nobody else reads the group's weights
-      ItemRec it{(int16_t)(n <= kValuTok ? kItemOnce : 0), nt, rank, 0, scale, pt_off, {0, 0, 0, 0}};
+      ItemRec it{(int16_t)((n <= kValuTok ? kItemOnce : 0) | contig), nt, rank, 0, scale, pt_off, {0, 0, 0, 0}};
       for (int i = 0; i < 4; ++i) it.tok[i] = b->perm[start + t0 + std::min<int>(i, nt - 1)];
       tg.push_back(it);
     }
@@ -779,8 +787,10 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     const Adapter& a = p->ad[touched[u]];
     const int32_t n = p->count[touched[u]];
     const int32_t start = b->seg_start[u];
-    const int32_t pt_off = (int32_t)n_pt_total;
-    n_pt_total += a.pt.size();
+    // an adapter on consecutive pages needs no table in the image: its records carry its first page
+    const int16_t contig = (int16_t)(a.contig ? kItemContig : 0);
+    const int32_t pt_off = a.contig ? a.pt[0] : (int32_t)n_pt_total;
+    if (!a.contig) n_pt_total += a.pt.size();
     const int16_t rank = (int16_t)a.rank;
     const bool mf_s = mfma_ok && p->mfma_min_tokens > 0 &&
                       (n >= p->mfma_min_tokens || (int64_t)n * a.rank >= p->mfma_min_work);
@@ -794,7 +804,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       if (mf_s) {
         double cost = 0.0;
         // the rows of A are read by one item only when the group is a single token tile
-        const int16_t kind = (int16_t)(n <= kMfmaTokS ? 1 | kItemOnce : 1);
+        const int16_t kind = (int16_t)((n <= kMfmaTokS ? 1 | kItemOnce : 1) | contig);
         for (int32_t j0 = 0; j0 < a.rank; j0 += kMfmaRows)
           for (int32_t t0 = b0; t0 < b1; t0 += kMfmaTokS) {
             const int16_t nt = (int16_t)std::min(kMfmaTokS, b1 - t0);
@@ -807,7 +817,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       }
       if (mf_e) {
         double cost = 0.0;
-        const int16_t kind = (int16_t)(n <= kMfmaTokCols ? 1 | kItemOnce : 1);
+        const int16_t kind = (int16_t)((n <= kMfmaTokCols ? 1 | kItemOnce : 1) | contig);
         // a remainder of at most cols_max_group tokens goes as column-split items of one token tile
         for (int32_t t0 = b0; t0 < b1;) {
           const int32_t left = b1 - t0;
@@ -821,7 +831,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     }
     // Vector-ALU items.
     if (!mf_s || !mf_e) {
-      token_groups(rank, a.scale, pt_off, start, n);
+      token_groups(rank, a.scale, pt_off, contig, start, n);
       if (!mf_e) {
         double cost = 0.0;
         for (const ItemRec& it : tg) { wl[1][0].items.push_back(it); cost += a.rank + 2 * it.ntok; }
@@ -871,8 +881,9 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
       size_t pt_run = 0;
       for (int32_t u = 0; u < n_seg; ++u) {
         const Adapter& a = p->ad[touched[u]];
-        token_groups((int16_t)a.rank, a.scale, (int32_t)pt_run, b->seg_start[u], p->count[touched[u]]);
-        pt_run += a.pt.size();
+        token_groups((int16_t)a.rank, a.scale, a.contig ? a.pt[0] : (int32_t)pt_run, (int16_t)(a.contig ? kItemContig : 0),
+                     b->seg_start[u], p->count[touched[u]]);
+        if (!a.contig) pt_run += a.pt.size();
         if (op == 1) all.insert(all.end(), tg.begin(), tg.end());
         else
           for (int32_t j0 = 0; j0 < a.rank; j0 += kShrinkRows)
@@ -918,6 +929,7 @@ int plora_batch_begin(plora_pool* p, const int32_t* t2a, int32_t T, plora_stream
     int32_t* dst = (int32_t*)(b->h_img + b->off_pt);
     for (int32_t u = 0; u < n_seg; ++u) {
       const Adapter& a = p->ad[touched[u]];
+      if (a.contig) continue;  // its records carry the first page
       std::memcpy(dst, a.pt.data(), a.pt.size() * 4);
       dst += a.pt.size();
     }

@@ -43,14 +43,14 @@ void kernel_body(const plora::LaunchArgs a, std::shared_ptr<std::set<uint64_t>> 
       if (it.kind != -1) { violation("work record is not one the host wrote (image not there?)", i, it.kind); return; }
       continue;
     }
-    if ((it.kind & 0xff) > 1 || it.rank < 0 || it.rank > 512 || it.ntok < 1 || it.pt_off < 0) {
+    if ((it.kind & 0xff) > 1 || (it.kind & ~0x3ff) || it.rank < 0 || it.rank > 512 || it.ntok < 1 || it.pt_off < 0) {
       violation("work record is not one the host wrote (image not there?)", i, it.kind);
       return;
     }
     if (it.rank == 0) continue;
     const uint64_t pages = ((uint64_t)it.rank * g_elt * a.elems_per_rank + P - 1) / P;
     for (uint64_t k = 0; k < pages; ++k) {
-      const int32_t page = a.pt[it.pt_off + k];
+      const int32_t page = (it.kind & plora::kItemContig) ? it.pt_off + (int32_t)k : a.pt[it.pt_off + k];
       uint64_t w;
       std::memcpy(&w, a.slab + (uint64_t)page * P, 8);
       ++g_pages_checked;
