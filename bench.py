@@ -27,13 +27,16 @@ from workload import (CONFIGS, RAW_DTYPE, config_layout, draw_ranks, draw_tok2ad
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # HBM bytes per launch of the (shrink, expand) kernels measured with rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE on the default draw of each workload, all slots per call (the profile named holds the
-# commands and the scaling factors found on a copy kernel of known size).  Each entry carries the
+# commands and the counter units found on the probe kernel, whose bytes are known).  Each entry carries the
 # digest of the kernel and host sources it was measured on (kernel_sources_digest below): the
 # figure is reported only while the sources are still those, and null as soon as they change.
 MEASURED_TRAFFIC = {
-    "cfg1": dict(shrink=1.813e9, expand=2.100e9, profile="profiles/decode_7b_cfg1_kernels_and_hbm_traffic.md", sources=None),
-    "cfg4": dict(shrink=2.318e9, expand=2.452e9, profile="profiles/decode_13b_layer_cfg4_kernels_and_hbm_traffic.md", sources=None),
-    "cfg2": dict(shrink=0.274e9, expand=0.400e9, profile="profiles/prefill_cfg2_kernels_traffic_and_mfma_activity.md", sources=None),
+    "cfg1": dict(shrink=1.8136e9, expand=2.0987e9, profile="profiles/decode_7b_cfg1_kernels_and_hbm_traffic.md",
+                 sources="7473f23ccbaecd95"),
+    "cfg4": dict(shrink=2.3184e9, expand=2.4507e9, profile="profiles/decode_13b_layer_cfg4_kernels_and_hbm_traffic.md",
+                 sources="7473f23ccbaecd95"),
+    "cfg2": dict(shrink=0.2779e9, expand=0.4000e9, profile="profiles/prefill_cfg2_kernels_traffic_and_mfma_activity.md",
+                 sources="7473f23ccbaecd95"),
 }
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
 KCLASS = ["shrink", "expand", "delta"]
@@ -671,6 +674,8 @@ def main():
         "tokens_per_s": round(tokens_total / elapsed, 1),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2),
         "algorithmic_bytes_per_step": int(bytes_total / args.steps),
+        "algorithmic_bytes_per_step_by_kernel": {"shrink": int(sum(a["shrink"] for a in ab) / args.steps),
+                                                 "expand": int(sum(a["expand"] for a in ab) / args.steps)},
         "gflop_per_step": round(sum(a["flops"] for a in ab) / args.steps / 1e9, 2),
         "h2d_prefetch_gbs": round(w.stats_after_load["h2d_bytes"] / 1e9 / w.t_load, 2),
         "pool_page_util": round(w.stats_after_load["used_pages"] / w.stats_after_load["n_pages"], 4),
@@ -699,7 +704,7 @@ def main():
         if probes.get("read_gbs"):
             out["pct_of_streaming_roof"] = round(100.0 * gbs / probes["read_gbs"], 2)
         if roof is not None and probes.get("read_plus_rmw_gbs"):
-            roof["frac_of_probe"] = round(roof["achieved"] / (probes["read_plus_rmw_gbs"] if roof["kernel"] == "expand" else probes["read_gbs"]), 4)
+            roof["vs_probe_of_same_mix"] = round(roof["achieved"] / (probes["read_plus_rmw_gbs"] if roof["kernel"] == "expand" else probes["read_gbs"]), 4)
         if probes.get("h2d_single_pinned_copy_gbs"):
             out["h2d_pct_of_single_pinned_copy"] = round(100.0 * out["h2d_prefetch_gbs"] / probes["h2d_single_pinned_copy_gbs"], 1)
     if not args.no_cpu_baseline:
