@@ -559,7 +559,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=500)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg3", "cfg3p", "cfg4", "cfg5", "load_study"])
+    ap.add_argument("--workload", default="cfg1", choices=["cfg0", "cfg1", "cfg2", "cfg2x8", "cfg3", "cfg3p", "cfg4", "cfg5", "load_study"])
     ap.add_argument("--slots-per-call", type=int, default=0, help="slots per plora_shrink/plora_expand call (0 = all)")
     ap.add_argument("--mfma-min-tokens", type=int, default=-1, help="plain token threshold of the matrix-core items in shrink (default: the library's work-based rule)")
     ap.add_argument("--mfma-min-tokens-expand", type=int, default=-1, help="the same for expand")
