@@ -26,7 +26,8 @@
 // Pins (tests/test_oracle_*.py): page-count closed form and the paper's printed adapter
 // sizes, allocator invariants and a brute-force rescan allocator, byte-exact virtual view,
 // numpy stable argsort for the batch translation, fp64 dense x (A^T B) for the delta, and
-// the invariances listed in the tests.  The eviction *policy* is not part of this file.
+// the invariances listed in the tests; hand-worked examples and invariants for the compaction
+// (tests/test_oracle_compact.py).  The eviction *policy* is not part of this file.
 
 #include <cstdint>
 #include <cstdlib>
@@ -253,6 +254,49 @@ int oracle_evict(void* h, int32_t id) {
   p->resident_bytes -= uint64_t(a.rank) * p->elt * uint64_t(p->C);
   a.pt.clear(); a.present = false; a.rank = 0; a.scale = 0.f;
   p->evictions++;
+  return O_OK;
+}
+
+// Compaction (Sec. III-C "Defragmentation": background compaction coalesces free pages).  The paper
+// gives no procedure.  Reading: the resident adapters are taken in ascending order of their first
+// page; each is placed anew as a load would place it if its own pages were free as well - on the m
+// lowest-numbered pages among the free ones and its own, ascending - and its bytes move with it.
+// Adapters named in skip[] stay where they are (the library leaves out adapters that an open batch
+// uses or whose load has not completed).  max_pages > 0 bounds the pages whose content moves in one
+// call: an adapter moves whole or not at all, and the first one that does not fit ends the call.
+// moved_out[0] = pages moved, moved_out[1] = adapters moved.
+int oracle_compact(void* h, uint32_t max_pages, const int32_t* skip, int32_t n_skip, uint32_t* moved_out) {
+  OPool* p = (OPool*)h;
+  if (!p || n_skip < 0 || (n_skip > 0 && !skip)) return O_INVAL;
+  std::vector<int32_t> order;
+  for (int32_t id = 0; id < p->max_adapters; ++id)
+    if (p->ad[id].present && std::find(skip, skip + n_skip, id) == skip + n_skip) order.push_back(id);
+  std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return p->ad[x].pt[0] < p->ad[y].pt[0]; });
+  uint32_t pages = 0, adapters = 0;
+  for (int32_t id : order) {
+    OAdapter& a = p->ad[id];
+    const size_t m = a.pt.size();
+    for (int32_t q : a.pt) p->is_free[q] = 1;
+    std::vector<int32_t> to;
+    for (uint32_t q = 0; q < p->n_pages && to.size() < m; ++q)
+      if (p->is_free[q]) to.push_back(int32_t(q));
+    uint32_t changed = 0;
+    for (size_t l = 0; l < m; ++l) changed += to[l] != a.pt[l];
+    if (max_pages > 0 && pages + changed > max_pages) {  // does not fit: it stays, and the call ends
+      for (int32_t q : a.pt) p->is_free[q] = 0;
+      break;
+    }
+    if (changed) {
+      std::vector<uint8_t> bytes(m * p->P);  // the adapter's pages in logical order, then into their new places
+      for (size_t l = 0; l < m; ++l) std::memcpy(bytes.data() + l * p->P, p->mem + uint64_t(a.pt[l]) * p->P, p->P);
+      for (size_t l = 0; l < m; ++l) std::memcpy(p->mem + uint64_t(to[l]) * p->P, bytes.data() + l * p->P, p->P);
+      a.pt = to;
+      pages += changed;
+      adapters++;
+    }
+    for (int32_t q : a.pt) p->is_free[q] = 0;
+  }
+  if (moved_out) { moved_out[0] = pages; moved_out[1] = adapters; }
   return O_OK;
 }
 

@@ -45,6 +45,7 @@ def _load():
     L.oracle_load.argtypes = [vp, i32, i32, f32, vp, vp, C.POINTER(u32)]
     L.oracle_evict.argtypes = [vp, i32]
     L.oracle_page_table.argtypes = [vp, i32, vp, u32, C.POINTER(u32)]
+    L.oracle_compact.argtypes = [vp, u32, vp, i32, vp]
     L.oracle_stats.argtypes = [vp, vp]
     L.oracle_free_map.argtypes = [vp, vp]
     L.oracle_read_virtual.argtypes = [vp, i32, u64, u64, vp]
@@ -127,6 +128,15 @@ class OraclePool:
         rc = self._L.oracle_evict(self._h, aid)
         if rc:
             raise OracleError(rc)
+
+    def compact(self, max_pages=0, skip=()):
+        """-> (pages moved, adapters moved)."""
+        sk = np.ascontiguousarray(list(skip), dtype=np.int32)
+        moved = np.zeros(2, dtype=np.uint32)
+        rc = self._L.oracle_compact(self._h, int(max_pages), _ptr(sk) if len(sk) else None, len(sk), _ptr(moved))
+        if rc:
+            raise OracleError(rc)
+        return int(moved[0]), int(moved[1])
 
     def page_table(self, aid):
         n = C.c_uint32(0)
