@@ -455,8 +455,9 @@ def _churn_pass(cfg, lay, ranks, scales, pool, pinned, trace, quality, stop_on="
 
 def run_load_study(args):
     """H2D rate of plora_load_adapter into fragmented pools, direct (one copy per run of consecutive
-    pages) against staged (one copy + scatter kernel): cfg3's one-layer slots and 64 KiB pages, free
-    space made of holes of h pages, 32 rank-64 adapters (4 MiB = 64 pages each) loaded back to back."""
+    pages) against staged (one copy + scatter kernel), and direct again after plora_compact has made the
+    free pages one range: cfg3's one-layer slots and 64 KiB pages, free space made of holes of h pages,
+    32 rank-64 adapters (4 MiB = 64 pages each) loaded back to back."""
     import torch
     import paper_2512_20210_amd as P
     from workload import make_adapter
@@ -503,9 +504,29 @@ def run_load_study(args):
             for k in range(n_big):
                 pool.evict(n_fill + k)
         row["staged_loads"] = pool.stats()["staged_loads"]
+        if hole:
+            # the same pool after plora_compact: the fillers slide down, the free pages become one range
+            pool.set_option("staging_bytes", 0)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            pages, adapters = pool.compact(copy_stream.cuda_stream)
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            row["compaction"] = {"pages_moved": pages, "adapters_moved": adapters, "ms": round(dt * 1e3, 2),
+                                 "moved_gbs": round(pages * page_bytes / dt / 1e9, 2)}
+            for rep in range(2):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for k in range(n_big):
+                    pool.load(n_fill + k, big_rank, 0.25, big[k % len(big)], copy_stream.cuda_stream)
+                torch.cuda.synchronize()
+                dt = time.perf_counter() - t0
+                row["direct_after_compaction_gbs"] = round(n_big * lay.adapter_elems(big_rank) * 2 / dt / 1e9, 2)
+                for k in range(n_big):
+                    pool.evict(n_fill + k)
         rows.append(row)
         pool.close()
-    print(json.dumps({"metric": "H2D GB/s of adapter loads into fragmented pools, direct vs staged", "workload": "load_study",
+    print(json.dumps({"metric": "H2D GB/s of adapter loads into fragmented pools: direct, staged, direct after compaction", "workload": "load_study",
                       "adapter_bytes": lay.adapter_elems(big_rank) * 2, "adapters": n_big, "page_bytes": page_bytes, "rows": rows}))
 
 

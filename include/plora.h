@@ -76,6 +76,8 @@ typedef struct {
   uint64_t fused_launches; /* plora_delta calls that ran as one launch */
   uint64_t fused_timeouts; /* expand tasks of such launches that gave up waiting for their slot's shrink tasks (their
                               part of y was left as it was); stays 0 unless "fused_spin_limit" is set very low */
+  uint64_t compacted_adapters, compacted_pages; /* moved by plora_compact so far */
+  double compact_ms;       /* summed first-copy-start -> last-copy-end time of completed moves */
 } plora_stats;
 
 /* Pool of n_pages pages of page_bytes each (Sec. III-C "Page Structure"; the paper's default page is
@@ -119,6 +121,30 @@ int plora_sync_adapter(plora_pool* pool, int32_t id);
  * pages are allocatable at once.  NOTFOUND; BUSY if the load has not completed or an open batch
  * names the adapter. */
 int plora_evict(plora_pool* pool, int32_t id);
+
+/* The adapter's current page table (Sec. III-C "Page Table"): the same pool-owned array that
+ * plora_load_adapter handed out, n_pages entries, valid until plora_evict(id); plora_compact rewrites it
+ * in place.  NOTFOUND. */
+int plora_adapter_pages(plora_pool* pool, int32_t id, const int32_t** page_table_out, uint32_t* n_pages_out);
+
+/* Compaction (Sec. III-C "Defragmentation": background compaction coalesces free pages).  With pages of
+ * one size no allocation can fail for lack of a contiguous range; what scattered free pages cost is one
+ * copy per run of consecutive pages when an adapter is loaded, and a table read at the head of every
+ * work item of an adapter that is not on consecutive pages.  The call takes the resident adapters in
+ * ascending order of their first page and places each anew where a load would put it if its own pages
+ * were free as well - on the lowest-numbered pages among the free ones and its own, ascending -
+ * moving its pages there with device-to-device copies on `stream`.  Adapters that an open batch names
+ * or whose load has not completed stay where they are.  max_pages > 0 bounds the pages moved by one
+ * call (a background step): an adapter moves whole or not at all, and the first that does not fit ends
+ * the call.  pages_moved_out / adapters_moved_out (host, may be NULL).
+ * Ordering: the copies wait (device side) for every batch still in flight that reads pages they write,
+ * on whatever stream it ran; batches begun afterwards wait for the moved adapter like for a load in
+ * flight (plora_adapter_ready / plora_wait_adapter apply); whoever writes the vacated pages next waits
+ * for the copies and for the batches that still read them.  Results of batches do not change.
+ * PLORA_ERR_HIP: the adapter whose move failed has left the pool (its pages may have been overwritten
+ * half way) and has to be loaded again; adapters moved before it stay moved. */
+int plora_compact(plora_pool* pool, plora_stream stream, uint32_t max_pages, uint32_t* pages_moved_out,
+                  uint32_t* adapters_moved_out);
 
 /* Once-per-batch translation (Sec. III-C "Page Table").  tok2adapter_host: host, n_tokens entries;
  * -1 = token without adapter (its y row is left untouched).  Groups tokens by adapter with a stable

@@ -13,7 +13,7 @@ import numpy as np
 __all__ = ["PLORA_OK", "PLORA_ERR_INVAL", "PLORA_ERR_NOMEM", "PLORA_ERR_EXISTS", "PLORA_ERR_NOTFOUND",
            "PLORA_ERR_BUSY", "PLORA_ERR_HIP", "PLORA_ERR_LIMIT", "PLORA_F16", "PLORA_BF16", "PLORA_F32", "PLORA_POOL_PLACEMENT_ONLY",
            "plora_pool_create", "plora_pool_destroy", "plora_adapter_bytes", "plora_load_adapter",
-           "plora_adapter_ready", "plora_wait_adapter", "plora_sync_adapter", "plora_evict", "plora_batch_begin", "plora_batch_info",
+           "plora_adapter_ready", "plora_wait_adapter", "plora_sync_adapter", "plora_evict", "plora_adapter_pages", "plora_compact", "plora_batch_begin", "plora_batch_info",
            "plora_shrink", "plora_expand", "plora_delta", "plora_delta_static", "plora_batch_end", "plora_pool_stats", "plora_pool_set_option",
            "plora_profile", "plora_profile_read", "plora_probe_stream", "plora_probe_h2d", "plora_last_hip", "plora_version", "PloraError", "PagedLoraPool", "lib", "LIB_PATH",
            "plora_predictor_create", "plora_predictor_destroy", "plora_predictor_observe", "plora_predictor_observed",
@@ -47,7 +47,8 @@ class _Stats(C.Structure):
     _fields_ = [(k, C.c_uint64) for k in ("page_bytes", "n_pages", "used_pages", "free_pages", "resident_adapters",
                                           "resident_bytes", "internal_frag_bytes", "loads", "evictions",
                                           "nomem_failures", "h2d_bytes", "h2d_copies")] + [("h2d_ms", C.c_double), ("staged_loads", C.c_uint64), ("fused_launches", C.c_uint64),
-                                                                                        ("fused_timeouts", C.c_uint64)]
+                                                                                        ("fused_timeouts", C.c_uint64), ("compacted_adapters", C.c_uint64),
+                                                                                        ("compacted_pages", C.c_uint64), ("compact_ms", C.c_double)]
 
 
 _vp, _i32, _u32, _u64, _f32 = C.c_void_p, C.c_int32, C.c_uint32, C.c_uint64, C.c_float
@@ -59,6 +60,8 @@ lib.plora_load_adapter.argtypes = [_vp, _i32, _i32, _f32, _vp, _vp, C.POINTER(C.
 lib.plora_adapter_ready.argtypes = [_vp, _i32]
 lib.plora_wait_adapter.argtypes = [_vp, _i32, _vp]
 lib.plora_evict.argtypes = [_vp, _i32]
+lib.plora_compact.argtypes = [_vp, _vp, _u32, C.POINTER(_u32), C.POINTER(_u32)]
+lib.plora_adapter_pages.argtypes = [_vp, _i32, C.POINTER(C.POINTER(_i32)), C.POINTER(_u32)]
 lib.plora_sync_adapter.argtypes = [_vp, _i32]
 lib.plora_batch_begin.argtypes = [_vp, _vp, _i32, _vp, C.POINTER(_vp)]
 lib.plora_batch_info.argtypes = [_vp, C.POINTER(_i32), C.POINTER(_i32), C.POINTER(C.POINTER(_i32)),
@@ -174,6 +177,22 @@ def plora_sync_adapter(pool, aid):
 
 def plora_evict(pool, aid):
     return lib.plora_evict(pool, aid)
+
+
+def plora_adapter_pages(pool, aid):
+    """-> (status, copy of the adapter's page table as an int32 array)."""
+    pt, n = C.POINTER(_i32)(), _u32(0)
+    rc = lib.plora_adapter_pages(pool, aid, C.byref(pt), C.byref(n))
+    if rc != PLORA_OK:
+        return rc, None
+    return rc, np.ctypeslib.as_array(pt, shape=(n.value,)).copy() if n.value else np.empty(0, np.int32)
+
+
+def plora_compact(pool, stream=None, max_pages=0):
+    """-> (status, pages moved, adapters moved)."""
+    pages, adapters = _u32(0), _u32(0)
+    rc = lib.plora_compact(pool, stream, max_pages, C.byref(pages), C.byref(adapters))
+    return rc, pages.value, adapters.value
 
 
 def plora_batch_begin(pool, tok2adapter, stream=None):
@@ -315,6 +334,16 @@ class PagedLoraPool:
     def evict(self, aid):
         _check("plora_evict", plora_evict(self.h, aid))
         self._blobs.pop(aid, None)
+
+    def page_table(self, aid):
+        rc, pt = plora_adapter_pages(self.h, aid)
+        _check("plora_adapter_pages", rc)
+        return pt
+
+    def compact(self, stream=None, max_pages=0):
+        rc, pages, adapters = plora_compact(self.h, stream, max_pages)
+        _check("plora_compact", rc)
+        return pages, adapters
 
     def batch_begin(self, tok2adapter, stream=None):
         rc, b = plora_batch_begin(self.h, tok2adapter, stream)

@@ -47,6 +47,7 @@ struct Adapter {
   bool contig = false;  // the pages are physically consecutive: kernels derive the table from pt[0]
   hipEvent_t ev_start = nullptr, ev_ready = nullptr;  // created on first use, reused
   bool copy_pending = false;                          // ready event not yet observed complete
+  bool moved = false;                                 // the pending copies are a compaction's page moves, not a load
   int pins = 0;
   std::vector<std::shared_ptr<Event>> last_use;  // completion markers of the last batches that read it: one per stream
 };
@@ -183,6 +184,9 @@ struct plora_pool {
   uint64_t resident_adapters = 0, resident_bytes = 0, loads = 0, evictions = 0, nomem = 0;
   uint64_t h2d_bytes = 0, h2d_copies = 0;
   double h2d_ms = 0.0;
+  uint64_t compactions = 0, compacted_pages = 0;  // adapters / pages moved by plora_compact
+  double compact_ms = 0.0;
+  std::vector<int32_t> compact_order, compact_to;  // scratch of plora_compact
 };
 
 namespace {
@@ -194,9 +198,10 @@ int poll_ready(plora_pool* p, Adapter& a) {
   if (e == hipErrorNotReady) { (void)hipGetLastError(); return 0; }
   if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); return PLORA_ERR_HIP; }
   float ms = 0.f;
-  if (hipEventElapsedTime(&ms, a.ev_start, a.ev_ready) == hipSuccess) p->h2d_ms += ms;
+  if (hipEventElapsedTime(&ms, a.ev_start, a.ev_ready) == hipSuccess) (a.moved ? p->compact_ms : p->h2d_ms) += ms;
   else (void)hipGetLastError();
   a.copy_pending = false;
+  a.moved = false;
   return 1;
 }
 
@@ -573,6 +578,139 @@ int plora_evict(plora_pool* p, int32_t id) {
   return PLORA_OK;
 }
 
+int plora_adapter_pages(plora_pool* p, int32_t id, const int32_t** pt_out, uint32_t* n_out) {
+  if (!p || id < 0 || id >= p->max_adapters) return PLORA_ERR_INVAL;
+  Adapter& a = p->ad[id];
+  if (!a.present) return PLORA_ERR_NOTFOUND;
+  if (pt_out) *pt_out = a.pt.data();
+  if (n_out) *n_out = (uint32_t)a.pt.size();
+  return PLORA_OK;
+}
+
+int plora_compact(plora_pool* p, plora_stream cs, uint32_t max_pages, uint32_t* pages_out, uint32_t* adapters_out) {
+  if (!p) return PLORA_ERR_INVAL;
+  if (pages_out) *pages_out = 0;
+  if (adapters_out) *adapters_out = 0;
+  hipStream_t st = (hipStream_t)cs;
+  // candidates in ascending order of their first page; adapters that an open batch names (its image
+  // carries their tables) or whose pages are still being written stay where they are
+  std::vector<int32_t>& order = p->compact_order;
+  order.clear();
+  for (int32_t id = 0; id < p->max_adapters; ++id) {
+    Adapter& a = p->ad[id];
+    if (!a.present || a.pins > 0) continue;
+    if (!p->placement_only) {
+      const int rdy = poll_ready(p, a);
+      if (rdy < 0) return rdy;
+      if (rdy == 0) continue;
+    }
+    order.push_back(id);
+  }
+  std::sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return p->ad[x].pt[0] < p->ad[y].pt[0]; });
+  uint32_t pages = 0, adapters = 0;
+  std::vector<int32_t>& to = p->compact_to;
+  for (int32_t id : order) {
+    Adapter& a = p->ad[id];
+    const size_t m = a.pt.size();
+    // where a load would put it if its own pages were free as well: the m lowest of both
+    for (int32_t q : a.pt) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
+    to.clear();
+    for (uint32_t w = std::min<uint32_t>(p->hint_word, (uint32_t)a.pt[0] >> 6); to.size() < m; ++w) {
+      uint64_t bits = p->free_bits[w];
+      while (bits && to.size() < m) {
+        to.push_back((int32_t)(w * 64 + __builtin_ctzll(bits)));
+        bits &= bits - 1;
+      }
+    }
+    uint32_t changed = 0;
+    for (size_t l = 0; l < m; ++l) changed += to[l] != a.pt[l];
+    if (changed == 0 || (max_pages > 0 && pages + changed > max_pages)) {
+      for (int32_t q : a.pt) p->free_bits[q >> 6] &= ~((uint64_t)1 << (q & 63));
+      if (changed) break;  // does not fit the bound: it stays, and the call ends
+      continue;
+    }
+    if (!p->placement_only) {
+      // The moves write free pages (which batches still in flight may be reading through evicted
+      // adapters' tables) and pages of this adapter itself (which batches in flight read through its
+      // old table): the stream waits for all of those readers first.
+      int rc = wait_for_earlier_readers(p, st);
+      hipError_t e = hipSuccess;
+      for (auto& mk : a.last_use) {
+        if (rc != PLORA_OK || e != hipSuccess) break;
+        const int passed = marker_passed(*mk);
+        if (passed < 0) rc = passed;
+        else if (passed == 0) e = hipStreamWaitEvent(st, mk->ev, 0);
+      }
+      if (rc == PLORA_OK && e == hipSuccess && !a.ev_start) {
+        e = hipEventCreate(&a.ev_start);
+        if (e == hipSuccess) e = hipEventCreate(&a.ev_ready);
+      }
+      if (rc == PLORA_OK && e == hipSuccess) e = hipEventRecord(a.ev_start, st);
+      // Page l goes from pt[l] down to to[l] <= pt[l], in ascending l: a page is overwritten only after it
+      // has been copied (to[l] <= pt[l] < pt[l + 1]).  Runs of consecutive pages go in one copy, cut so
+      // that a copy's source and destination do not overlap.
+      size_t l = 0;
+      while (rc == PLORA_OK && e == hipSuccess && l < m) {
+        if (to[l] == a.pt[l]) { ++l; continue; }
+        const size_t gap = (size_t)(a.pt[l] - to[l]);
+        size_t h = l + 1;
+        while (h < m && h - l < gap && to[h] == to[h - 1] + 1 && a.pt[h] == a.pt[h - 1] + 1) ++h;
+        e = hipMemcpyAsync(p->slab + (uint64_t)to[l] * p->P, p->slab + (uint64_t)a.pt[l] * p->P, (h - l) * p->P,
+                           hipMemcpyDeviceToDevice, st);
+        l = h;
+      }
+      if (rc == PLORA_OK && e == hipSuccess) e = hipEventRecord(a.ev_ready, st);
+      // The pages it leaves are free from now on, but whoever writes them next has to wait for these
+      // copies (they read them) and for the batches in flight that read them through the old table.
+      std::shared_ptr<Event> done;
+      if (rc == PLORA_OK && e == hipSuccess) {
+        done = std::make_shared<Event>();
+        done->stream = st;
+        rc = record_now(*done);
+      }
+      if (rc != PLORA_OK || e != hipSuccess) {
+        // Some pages may already have been overwritten on the way: the adapter is in neither place as a
+        // whole.  It leaves the pool (the caller loads it again); both sets of pages become free once the
+        // stream has drained.  A failing copy call is not expected outside a broken runtime.
+        if (e != hipSuccess) { g_last_hip = (int)e; (void)hipGetLastError(); rc = PLORA_ERR_HIP; }
+        (void)hipStreamSynchronize(st);
+        (void)hipGetLastError();
+        for (int32_t q : to) p->free_bits[q >> 6] |= (uint64_t)1 << (q & 63);
+        p->n_free += (uint32_t)m;
+        p->hint_word = std::min<uint32_t>(p->hint_word, (uint32_t)to[0] >> 6);
+        p->resident_adapters--; p->resident_bytes -= a.bytes; p->evictions++;
+        a.pt.clear();
+        a.present = false; a.rank = 0; a.scale = 0.f; a.bytes = 0; a.last_use.clear();
+        if (pages_out) *pages_out = pages;
+        if (adapters_out) *adapters_out = adapters;
+        return rc;
+      }
+      for (auto& mk : a.last_use)
+        if (!mk->recorded || hipEventQuery(mk->ev) != hipSuccess) {
+          (void)hipGetLastError();
+          if (std::none_of(p->reuse_wait.begin(), p->reuse_wait.end(), [&](const plora_pool::ReuseWait& w) { return w.m == mk; }))
+            p->reuse_wait.push_back({mk, {st}});
+        }
+      p->reuse_wait.push_back({done, {st}});
+      a.last_use.clear();  // readers of the old pages; whatever reads the new ones comes after ev_ready
+      a.copy_pending = true;
+      a.moved = true;
+    }
+    for (int32_t q : to) p->free_bits[q >> 6] &= ~((uint64_t)1 << (q & 63));
+    a.pt.assign(to.begin(), to.end());
+    a.contig = p->contig_fast_path && a.pt.back() - a.pt.front() + 1 == (int32_t)a.pt.size();
+    p->hint_word = 0;
+    while (p->hint_word < p->free_bits.size() && p->free_bits[p->hint_word] == 0) p->hint_word++;
+    pages += changed;
+    adapters++;
+  }
+  p->compactions += adapters;
+  p->compacted_pages += pages;
+  if (pages_out) *pages_out = pages;
+  if (adapters_out) *adapters_out = adapters;
+  return PLORA_OK;
+}
+
 int plora_pool_stats(plora_pool* p, plora_stats* o) {
   if (!p || !o) return PLORA_ERR_INVAL;
   if (!p->placement_only)
@@ -584,6 +722,7 @@ int plora_pool_stats(plora_pool* p, plora_stats* o) {
   o->loads = p->loads; o->evictions = p->evictions; o->nomem_failures = p->nomem;
   o->h2d_bytes = p->h2d_bytes; o->h2d_copies = p->h2d_copies; o->h2d_ms = p->h2d_ms; o->staged_loads = p->staged_loads;
   o->fused_launches = p->fused_launches;
+  o->compacted_adapters = p->compactions; o->compacted_pages = p->compacted_pages; o->compact_ms = p->compact_ms;
   o->fused_timeouts = p->h_timeouts ? *(volatile uint32_t*)p->h_timeouts : 0;
   return PLORA_OK;
 }

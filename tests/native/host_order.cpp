@@ -1,7 +1,8 @@
 // Ordering of the library's copies and kernels, checked on the CPU against a stand-in HIP runtime
 // (fake_hip.*) whose streams run only when pumped, in random orders that stream and event semantics
-// allow.  Random histories of loads, evictions and batches on two compute and two copy streams (a
-// batch's kernels sometimes on the compute stream it was not begun on); the
+// allow.  Random histories of loads, evictions, compactions and batches on two compute and two copy
+// streams (a batch's kernels sometimes on the compute stream it was not begun on; a compaction on any
+// of the four, now and then with one of its copies failing); the
 // stubbed kernels, when they finally run, look at what they would read:
 //   * the batch image must have landed (sane work records),
 //   * every page that a record's page table names must hold the blob of an adapter (and of the very
@@ -22,7 +23,7 @@
 #include "plora_internal.h"
 
 namespace {
-long g_violations = 0, g_kernels_run = 0, g_pages_checked = 0, g_staged_loads = 0, g_failed_loads = 0;
+long g_violations = 0, g_kernels_run = 0, g_pages_checked = 0, g_staged_loads = 0, g_failed_loads = 0, g_moved_adapters = 0, g_failed_moves = 0;
 bool g_verbose = true;
 std::shared_ptr<std::set<uint64_t>> g_expect;  // (adapter + 1) << 24 | load generation, of the batch being queued
 int g_elt = 2;
@@ -148,7 +149,7 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits, int stagin
   hipEvent_t cross = nullptr;
   CHECK(hipEventCreateWithFlags(&cross, hipEventDisableTiming) == hipSuccess);
   for (int step = 0; step < 600; ++step) {
-    const int what = rnd(rng) % 20;
+    const int what = rnd(rng) % 22;
     const int id = rnd(rng) % max_ad;
     if (what < 5) {
       if (!rank_of[id]) {
@@ -213,6 +214,26 @@ static long history(uint64_t seed, int per_marker, bool ignore_waits, int stagin
       }
       CHECK(plora_batch_end(p, b) == PLORA_OK);
       ++batches;
+    } else if (what < 21) {
+      // compaction on any stream: its page moves must wait for the kernels in flight that read the pages
+      // they overwrite (through old tables), and later loads into the vacated pages for the moves
+      hipStream_t st = (rnd(rng) % 2 ? compute : copy)[rnd(rng) % 2];
+      const uint32_t bound[4] = {0, 1, 3, 8};
+      const bool fault = rnd(rng) % 10 == 0;
+      if (fault) fakehip::fail_copy_in(1 + (int)(rnd(rng) % 2));
+      uint32_t pages = 0, moved = 0;
+      const int rc = plora_compact(p, st, bound[rnd(rng) % 4], &pages, &moved);
+      fakehip::fail_copy_in(0);
+      CHECK(rc == PLORA_OK || (fault && rc == PLORA_ERR_HIP));
+      CHECK((pages == 0) == (moved == 0));
+      g_moved_adapters += moved;
+      if (rc == PLORA_ERR_HIP) {  // the adapter whose move failed has left the pool
+        int gone = 0;
+        for (int a = 0; a < max_ad; ++a)
+          if (rank_of[a] && plora_adapter_ready(p, a) == PLORA_ERR_NOTFOUND) { rank_of[a] = 0; ++gone; }
+        CHECK(gone == 1);
+        ++g_failed_moves;
+      }
     } else if (rnd(rng) % 4 == 0) {
       fakehip::drain();
     }
@@ -248,11 +269,12 @@ int main() {
     }
   total_kernels = g_kernels_run;
   CHECK(total_kernels > 10000 && g_pages_checked > 10000 && g_staged_loads > 1000 && g_failed_loads > 100);
+  CHECK(g_moved_adapters > 1000 && g_failed_moves > 20);
   // the same histories without the runtime honouring waits: the kernels must notice
   g_verbose = false;
   int caught = 0;
   for (uint64_t seed = 1; seed <= 10; ++seed) caught += history(seed, 4, true, (int)(seed % 3)) > 0;
   CHECK(caught == 10);
-  std::printf("host order run OK (%ld kernels, %ld pages checked, %ld staged loads)\n", total_kernels, g_pages_checked, g_staged_loads);
+  std::printf("host order run OK (%ld kernels, %ld pages checked, %ld staged loads, %ld adapters moved by compaction)\n", total_kernels, g_pages_checked, g_staged_loads, g_moved_adapters);
   return 0;
 }
