@@ -702,6 +702,19 @@ def main():
         "pool_page_util": round(w.stats_after_load["used_pages"] / w.stats_after_load["n_pages"], 4),
         "roofline": roof,
     }
+    if not args.no_kernel_events:
+        # The timed steps above carry a pair of timing events on every kernel dispatch (the roofline figures need
+        # them), and a dispatch with events costs the queue a few microseconds: the same steps without them.
+        n = min(args.steps, 200)
+        t0 = time.perf_counter()
+        for i in range(n):
+            w.step(timed[i], spc, args.api)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        bn = sum(a["total"] for a in ab[:n])
+        out["without_kernel_events"] = {"steps": n, "ms_per_step": round(dt / n * 1e3, 4), "value": round(bn / dt / 1e9, 1),
+                                        "unit": "GB/s", "pct_of_hbm_peak": round(100.0 * bn / dt / 1e9 / HBM_PEAK_GBS, 2),
+                                        "tokens_per_s": round(sum(len(t) for t in timed[:n]) / dt, 1)}
     if not args.no_per_layer:
         # the same steps as a layer-by-layer decoder has to issue them: one call per layer (4 slots)
         if lay.n_slots > 4 and lay.n_slots % 4 == 0 and spc == lay.n_slots:
