@@ -741,6 +741,18 @@ def main():
             roof["vs_probe_of_same_mix"] = round(roof["achieved"] / (probes["read_plus_rmw_gbs"] if roof["kernel"] == "expand" else probes["read_gbs"]), 4)
         if probes.get("h2d_single_pinned_copy_gbs"):
             out["h2d_pct_of_single_pinned_copy"] = round(100.0 * out["h2d_prefetch_gbs"] / probes["h2d_single_pinned_copy_gbs"], 1)
+    # The loads above were the first use of the slab and of the pinned blobs.  What a pool that has been running
+    # for a while sees: every adapter evicted and loaded again, same stream, same placement.
+    torch.cuda.synchronize()
+    for i in range(w.n_ad):
+        w.pool.evict(i)
+    t0 = time.perf_counter()
+    for i in range(w.n_ad):
+        w.pool.load(i, int(w.ranks[i]), w.scales[i], w.pinned[i], w.copy_stream.cuda_stream)
+    w.copy_stream.synchronize()
+    out["h2d_reload_gbs"] = round(w.stats_after_load["h2d_bytes"] / 1e9 / (time.perf_counter() - t0), 2)
+    if out.get("streaming_roof", {}).get("h2d_single_pinned_copy_gbs"):
+        out["h2d_reload_pct_of_single_pinned_copy"] = round(100.0 * out["h2d_reload_gbs"] / out["streaming_roof"]["h2d_single_pinned_copy_gbs"], 1)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, timed[0])
     w.close()
