@@ -240,6 +240,10 @@ int plora_pool_stats(plora_pool* pool, plora_stats* out);
  * many such blocks (prefill); other batches (decode: a hot adapter or two) cut them into items of 16
  * tokens for the ordinary kernel instead (0 = always).  "mfma_cols_max_group" (default 32): in a
  * batch of the first kind, a group's last <= this many tokens still go as 16-token items.
+ * "panel_half_max_workgroups" (>= 0, default 8192): a launch of that kernel with at most this many
+ * workgroups of 512 columns is issued with one workgroup per 256 columns instead (twice as many, each
+ * half as long; v is then read twice as often), which is faster while the launch is too short to hide
+ * a workgroup's chain of loads behind other workgroups; 0 = never.  Results do not depend on it.
  * "mfma_shrink_depth" (0, 1 or 2; default 0): runs of 64 values of the contraction that a matrix-core
  * shrink item keeps in flight per wavefront; 0 lets the library choose per launch (2 when the batch's
  * matrix-core token tiles are at least half full on average, as in prefill, when a slot of the launch

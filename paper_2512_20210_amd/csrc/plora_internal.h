@@ -112,14 +112,15 @@ struct ScatterRuns {
   int32_t phys_page[kScatterRuns];
 };
 
-enum LaunchMode { kModeBlocks = 0, kModeCoop = 1, kModeDeep = 2, kModePanel = 2 };
+enum LaunchMode { kModeBlocks = 0, kModeCoop = 1, kModeDeep = 2, kModePanel = 2, kModePanelHalf = 3 };
 
 // Launchers (plora_kernels.hip).  Both take a list of blocks of 4 records (one matrix-core item +
 // 3 padding records, or up to 4 vector-ALU items) and run one 256-thread workgroup per block, slot
 // and (expand) 512-column chunk.  kModeCoop: the list holds vector-ALU records only and every record
 // gets a 256-thread workgroup whose four wavefronts share the record's work (for calls too small to
 // fill the machine); kModeDeep (shrink): blocks, two runs in flight per matrix-core item; kModePanel
-// (expand): matrix-core blocks only, B stationary in LDS.  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
+// (expand): matrix-core blocks only, B stationary in LDS; kModePanelHalf: the same with one workgroup
+// per 256 columns instead of 512 (for launches of few workgroups).  Grid: (n_items, chunks, n_slots), or (n_slots, n_items, chunks) when
 // a.slot_fastest is set: consecutive workgroups go to consecutive XCDs, so with a slot count that
 // is a multiple of 8 every slot then lives on one XCD (its x, v and y rows meet in one L2) and all
 // slots' copies of the first (longest) items start first.  A chunk is 64 lanes x 16 bytes of a row

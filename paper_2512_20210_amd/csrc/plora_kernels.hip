@@ -49,6 +49,7 @@
 #include <hip/hip_ext.h>
 
 #include <mutex>
+#include <type_traits>
 
 namespace plora {
 namespace {
@@ -138,7 +139,8 @@ __device__ __forceinline__ void unpack(const uint4 q, float* f) {
   }
 }
 
-// fp32 -> element, round to nearest even.
+// fp32 -> element, round to nearest even.  The update of y is written as an explicit fused multiply-add
+// (y + scale * sum with one rounding in fp32) and then rounded once to the element type.
 // Two fp32 -> one register of two bf16, round to nearest even, in one instruction (v_cvt_pk_bf16_f32).
 typedef __bf16 bf16x2_cvt_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_cvt_t __attribute__((ext_vector_type(2)));
@@ -146,7 +148,12 @@ __device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
   const f32x2_cvt_t f = {lo, hi};
   return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_cvt_t));
 }
+// (The value passes through an opaque register first: left to itself the compiler folds this conversion
+// into the fused multiply-add that produced the value for some elements - one rounding, straight to fp16 -
+// and not for others, differently from one kernel to the next.  Every element is rounded the same way:
+// to fp32 by the arithmetic, then once to fp16.)
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+  asm("" : "+v"(f));
   return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
 }
 
@@ -473,7 +480,7 @@ __device__ __forceinline__ void expand_valu_body(const LaunchArgs& a, const Item
       float yf[VEC];
       unpack<DT>(yq[i], yf);
 #pragma unroll
-      for (int e = 0; e < VEC; ++e) yf[e] = yf[e] + it.scale * acc[i][e];
+      for (int e = 0; e < VEC; ++e) yf[e] = __builtin_fmaf(it.scale, acc[i][e], yf[e]);
       sty16(yp[i], pack<DT>(yf));
     }
   }
@@ -875,8 +882,8 @@ __device__ __forceinline__ void expand_mfma_cols_body(const LaunchArgs& a, const
         unpack<DT>(yq[mt][i], yf);
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) {
-          if constexpr (DT == 0) yf[cc] = yf[cc] + it.scale * (inv[mt][i] * acc[mt][cc][i]);
-          else yf[cc] = yf[cc] + it.scale * acc[mt][cc][i];
+          if constexpr (DT == 0) yf[cc] = __builtin_fmaf(it.scale, inv[mt][i] * acc[mt][cc][i], yf[cc]);
+          else yf[cc] = __builtin_fmaf(it.scale, acc[mt][cc][i], yf[cc]);
         }
         sty16(y + ((uint64_t)trow[mt][i] * d_out + n) * EB, pack<DT>(yf));
       }
@@ -927,16 +934,23 @@ __device__ __forceinline__ void expand_mfma_cols_item(const LaunchArgs& a, const
 // against all four tiles: MFMA cc of a tile yields the real columns 8 c + cc, so a lane ends with 8
 // consecutive columns of y for each of its 4 token rows and updates y with 16-byte
 // read-modify-writes.  B is read once per 64 tokens; v goes in as hi + lo 16-bit halves (two MFMAs)
-// so that fp32 v loses nothing that matters.  Per panel, the tile of B and the rows of v are
-// requested together.  (Requesting the half's rows of y up front as well costs more in registers,
+// so that fp32 v loses nothing that matters.  Order of the requests in a panel: the tile of B; once it
+// has arrived and is on its way into LDS, the rows of v (they overlap the transposition and the
+// barrier; asked for together with B they would cost 16 registers at the point where most are live);
+// and in a half's last panel, right after the barrier, the half's rows of y, which then travel while
+// the products are formed.  (Requesting the rows of y before B is staged costs more in registers,
 // hence resident workgroups, than the overlap returns; strips of 128 columns per workgroup instead of
 // 512 are slower too: v is then re-read four times as often.)
+// HALF: the workgroup does one of the two halves only (half_sel), the other one belongs to another
+// workgroup: twice the workgroups, each with half the accumulators (4 instead of 3 fit a CU) and
+// half as long a chain, at the price of reading v twice as often - for launches that are too short
+// to hide a workgroup's chain behind others.
 static_assert(kMfmaTokE == 64, "host work items must match the kernel's tiles");
 
-template <int DT>
+template <int DT, bool HALF>
 __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const ItemRec it, const SlotRec sl,
                                                   const float* __restrict__ v, uint8_t* __restrict__ y,
-                                                  uint4 (*op)[8][kWave], int2* lds_pg, int chunk) {
+                                                  uint4 (*op)[8][kWave], int2* lds_pg, int chunk, int half_sel) {
   constexpr int EB = 2;
   const int tid = threadIdx.x, wave = wave_id(), lane = tid & 63;
   const int g = lane >> 4, c = lane & 15;
@@ -964,7 +978,7 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
   __syncthreads();
 
   const int ks_w = wave >> 1, ct_w = wave & 1;  // the tile this wavefront stages: K-step in panel, column tile
-  for (int half = 0; half < 2; ++half) {
+  for (int half = HALF ? half_sel : 0; half < (HALF ? half_sel + 1 : 2); ++half) {
     const int nh0 = n0i + half * 256;
     if (nh0 >= d_out) break;
     uint4 yq[2][4];
@@ -974,8 +988,10 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
 #pragma unroll
       for (int cc = 0; cc < 8; ++cc) acc[ct][cc] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int j0 = 0; j0 < r; j0 += 64) {
-      float vf[2][8];  // this wavefront's rows of v for the panel, requested together with the tile of B
+    // one panel of 64 rows of B; kLast: the half's last one, which also requests the rows of y
+    auto do_panel = [&](const int j0, auto last_tag) {
+      constexpr bool kLast = decltype(last_tag)::value;
+      float vf[2][8];  // this wavefront's rows of v for the panel
       {  // stage tile (ks_w, ct_w) of this panel
         const int ncol = nh0 + ct_w * 128 + 8 * c;
         const bool okc = ncol < d_out;
@@ -991,6 +1007,21 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
           const uint64_t pg = (uint64_t)(uint32_t)((inpage >> lp) ? pp.y : pp.x);
           wr[jj] = ldw16<false>(a.slab + (pg << lp) + (inpage & pmask));
         }
+#pragma unroll
+        for (int jj = 0; jj < 8; ++jj)
+          if (j8 + jj >= r || !okc) wr[jj] = make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+          const uint32_t r0 = (&wr[0].x)[d], r1 = (&wr[1].x)[d], r2 = (&wr[2].x)[d], r3 = (&wr[3].x)[d];
+          const uint32_t r4 = (&wr[4].x)[d], r5 = (&wr[5].x)[d], r6 = (&wr[6].x)[d], r7 = (&wr[7].x)[d];
+          op[wave][2 * d][lane] =
+              make_uint4(__builtin_amdgcn_perm(r1, r0, 0x05040100u), __builtin_amdgcn_perm(r3, r2, 0x05040100u),
+                         __builtin_amdgcn_perm(r5, r4, 0x05040100u), __builtin_amdgcn_perm(r7, r6, 0x05040100u));
+          op[wave][2 * d + 1][lane] =
+              make_uint4(__builtin_amdgcn_perm(r1, r0, 0x07060302u), __builtin_amdgcn_perm(r3, r2, 0x07060302u),
+                         __builtin_amdgcn_perm(r5, r4, 0x07060302u), __builtin_amdgcn_perm(r7, r6, 0x07060302u));
+        }
+        __builtin_amdgcn_sched_barrier(0);  // the rows of v only now: the registers of the tile are free again
         if (has_tok) {
 #pragma unroll
           for (int ks = 0; ks < 2; ++ks) {
@@ -1006,22 +1037,18 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
             }
           }
         }
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj)
-          if (j8 + jj >= r || !okc) wr[jj] = make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int d = 0; d < 4; ++d) {
-          const uint32_t r0 = (&wr[0].x)[d], r1 = (&wr[1].x)[d], r2 = (&wr[2].x)[d], r3 = (&wr[3].x)[d];
-          const uint32_t r4 = (&wr[4].x)[d], r5 = (&wr[5].x)[d], r6 = (&wr[6].x)[d], r7 = (&wr[7].x)[d];
-          op[wave][2 * d][lane] =
-              make_uint4(__builtin_amdgcn_perm(r1, r0, 0x05040100u), __builtin_amdgcn_perm(r3, r2, 0x05040100u),
-                         __builtin_amdgcn_perm(r5, r4, 0x05040100u), __builtin_amdgcn_perm(r7, r6, 0x05040100u));
-          op[wave][2 * d + 1][lane] =
-              make_uint4(__builtin_amdgcn_perm(r1, r0, 0x07060302u), __builtin_amdgcn_perm(r3, r2, 0x07060302u),
-                         __builtin_amdgcn_perm(r5, r4, 0x07060302u), __builtin_amdgcn_perm(r7, r6, 0x07060302u));
-        }
       }
       __syncthreads();
+      if (kLast && has_tok) {
+        // both column tiles' rows of y in one trip, under way while the products are formed
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct) {
+          const int n = imin(nh0 + ct * 128 + 8 * c, d_out - 8);
+#pragma unroll
+          for (int i = 0; i < 4; ++i) yq[ct][i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+      }
       if (has_tok) {
 #pragma unroll
         for (int ks = 0; ks < 2; ++ks) {
@@ -1044,15 +1071,13 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
         }
       }
       __syncthreads();
+    };
+    {
+      int j0 = 0;
+      for (; j0 + 64 < r; j0 += 64) do_panel(j0, std::false_type{});
+      do_panel(j0, std::true_type{});
     }
     if (has_tok) {
-      // both column tiles' rows of y are requested before the first is updated: one trip, not two
-#pragma unroll
-      for (int ct = 0; ct < 2; ++ct) {
-        const int n = imin(nh0 + ct * 128 + 8 * c, d_out - 8);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) yq[ct][i] = ldy16(y + ((uint64_t)trow[i] * d_out + n) * EB);
-      }
 #pragma unroll
       for (int ct = 0; ct < 2; ++ct) {
         const int n = nh0 + ct * 128 + 8 * c;
@@ -1064,8 +1089,8 @@ __device__ __forceinline__ void expand_panel_item(const LaunchArgs& a, const Ite
               unpack<DT>(yq[ct][i], yf);
 #pragma unroll
               for (int cc = 0; cc < 8; ++cc) {
-                if constexpr (DT == 0) yf[cc] = yf[cc] + it.scale * (inv[i] * acc[ct][cc][i]);
-                else yf[cc] = yf[cc] + it.scale * acc[ct][cc][i];
+                if constexpr (DT == 0) yf[cc] = __builtin_fmaf(it.scale, inv[i] * acc[ct][cc][i], yf[cc]);
+                else yf[cc] = __builtin_fmaf(it.scale, acc[ct][cc][i], yf[cc]);
               }
               sty16(y + ((uint64_t)trow[i] * d_out + n) * EB, pack<DT>(yf));
             }
@@ -1142,7 +1167,9 @@ __global__ __launch_bounds__(256, kWgPerCu) void k_expand(const LaunchArgs a, co
 
 // The matrix-core blocks of a batch with many large adapter groups (prefill): one item of up to 64
 // tokens per workgroup; the list holds matrix-core blocks only (first record of each block of 4).
-template <int DT>
+// HALF: the grid's chunk coordinate counts halves of 256 columns (2 per 512-column chunk), one per
+// workgroup; items in the column-split form are done whole by the workgroup of the first half.
+template <int DT, bool HALF>
 __global__ __launch_bounds__(256, kWgPerCu) void k_expand_panel(const LaunchArgs a, const SlotPtrs p) {
   __shared__ __align__(16) uint4 op[4][8][kWave];  // 4 staged tiles of B in MFMA operand order (32 KiB)
   __shared__ int2 lds_pg[kMaxRank];
@@ -1150,11 +1177,16 @@ __global__ __launch_bounds__(256, kWgPerCu) void k_expand_panel(const LaunchArgs
   expand_coords(a, blk, chunk, q);
   const ItemRec it = load_item(a.items + (4 * blk));
   if (item_kind(it) != 1) return;  // uniform
+  const int half_sel = HALF ? (chunk & 1) : 0;
+  if (HALF) chunk >>= 1;
   const SlotRec sl = a.slots[p.slot[q]];
   const float* v = (const float*)p.a[q];
   uint8_t* y = (uint8_t*)p.b[q];
-  if (it.ntok <= kMfmaTokCols) expand_mfma_cols_item<DT>(a, it, sl, v, y, lds_pg, chunk);
-  else expand_panel_item<DT>(a, it, sl, v, y, op, lds_pg, chunk);
+  if (it.ntok <= kMfmaTokCols) {
+    if (half_sel == 0) expand_mfma_cols_item<DT>(a, it, sl, v, y, lds_pg, chunk);
+  } else {
+    expand_panel_item<DT, HALF>(a, it, sl, v, y, op, lds_pg, chunk, half_sel);
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1349,7 +1381,7 @@ __device__ __forceinline__ void expand_coop_body(const LaunchArgs& a, const Item
     for (int e = 0; e < VEC; ++e) {
       const float s0 = red[((0 * kValuTok + wave) * 8 + e) * kWave + lane], s1 = red[((1 * kValuTok + wave) * 8 + e) * kWave + lane];
       const float s2 = red[((2 * kValuTok + wave) * 8 + e) * kWave + lane], s3 = red[((3 * kValuTok + wave) * 8 + e) * kWave + lane];
-      yf[e] = yf[e] + it.scale * (((s0 + s1) + s2) + s3);
+      yf[e] = __builtin_fmaf(it.scale, ((s0 + s1) + s2) + s3, yf[e]);
     }
     sty16(yp, pack<DT>(yf));
   }
@@ -1608,10 +1640,13 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
   const bool single = mode == kModeCoop;  // one record per workgroup
   if (a0.n_items <= 0 || n_slots <= 0 || max_chunks <= 0) return hipSuccess;
   if ((!single && a0.n_items % 4) || max_chunks > 65535) return hipErrorInvalidValue;
-  static const KernelFn table[3][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
+  static const KernelFn table[4][3] = {{k_expand<0>, k_expand<1>, k_expand<2>},
                                        {k_expand_coop<0>, k_expand_coop<1>, k_expand_coop<2>},
-                                       {k_expand_panel<0>, k_expand_panel<1>, nullptr}};
-  if (mode < 0 || mode > 2 || dtype < 0 || dtype > 2 || !table[mode][dtype]) return hipErrorInvalidValue;
+                                       {k_expand_panel<0, false>, k_expand_panel<1, false>, nullptr},
+                                       {k_expand_panel<0, true>, k_expand_panel<1, true>, nullptr}};
+  if (mode < 0 || mode > 3 || dtype < 0 || dtype > 2 || !table[mode][dtype]) return hipErrorInvalidValue;
+  const int grid_chunks = mode == kModePanelHalf ? 2 * max_chunks : max_chunks;  // halves of 256 columns
+  if (grid_chunks > 65535) return hipErrorInvalidValue;
   LaunchArgs a = a0;
   const int per = single ? 1 : 4;  // records per workgroup
   const int n_blocks = a0.n_items / per;
@@ -1620,8 +1655,8 @@ hipError_t launch_expand(int dtype, const LaunchArgs& a0, const SlotPtrs& p, int
     const int nb = n_blocks - first < step ? n_blocks - first : step;
     a.items = a0.items + per * first;
     a.n_items = per * nb;
-    const dim3 grid = a.slot_fastest == 1 ? dim3(n_slots, nb, max_chunks)
-                    : a.slot_fastest == 2 ? dim3(max_chunks, nb, n_slots) : dim3(nb, max_chunks, n_slots);
+    const dim3 grid = a.slot_fastest == 1 ? dim3(n_slots, nb, grid_chunks)
+                    : a.slot_fastest == 2 ? dim3(grid_chunks, nb, n_slots) : dim3(nb, grid_chunks, n_slots);
     launch(table[mode][dtype], grid, dim3(256), st, first == 0 ? e0 : nullptr, first + step >= n_blocks ? e1 : nullptr, a, p);
   }
   return hipGetLastError();

@@ -132,6 +132,8 @@ struct plora_pool {
   int panel_min_blocks = 8;  // expand: a batch with at least this many 64-token blocks of large groups (prefill) sends its
                              // matrix-core blocks to the panel kernel; other batches cut every large group into
                              // column-split items (0 = never)
+  int64_t panel_half_max_workgroups = 8192;  // expand: a panel launch of at most this many workgroups (of 512 columns) is
+                                             // issued with one workgroup per 256 columns instead (0 = never)
   int batches_per_marker = 4;                      // record the marker once this many batches share it
   std::vector<plora_batch*> batches;               // all batch objects ever made (recycled)
   int open_batches = 0;
@@ -773,6 +775,11 @@ int plora_pool_set_option(plora_pool* p, const char* key, int64_t value) {
     p->panel_min_blocks = (int)value;
     return PLORA_OK;
   }
+  if (k == "panel_half_max_workgroups") {
+    if (value < 0 || value > ((int64_t)1 << 40)) return PLORA_ERR_INVAL;
+    p->panel_half_max_workgroups = value;
+    return PLORA_OK;
+  }
   if (k == "mfma_cols_max_group") {
     if (value < 0 || value > (1 << 30)) return PLORA_ERR_INVAL;
     p->cols_max_group = (int)value;
@@ -1202,7 +1209,11 @@ static int run_slots(plora_pool* p, const plora_batch* b, int32_t slot0, int32_t
     // one launch over the whole block list, or (panel batches) the matrix-core blocks in the panel kernel
     // followed by the vector-ALU quads in the ordinary one
     struct Part { const ItemRec* items; int n; int mode; };
-    const Part parts[2] = {{list, panel ? b->n_heavy[op] : n_all, panel ? kModePanel : coop ? kModeCoop : deep ? kModeDeep : kModeBlocks},
+    // a short panel launch goes with one workgroup per 256 columns: twice the workgroups, half the chain each
+    const int panel_mode = panel && 2 * chunks <= 65535 &&
+                                   (int64_t)nq * (b->n_heavy[op] / 4) * chunks <= p->panel_half_max_workgroups
+                               ? kModePanelHalf : kModePanel;
+    const Part parts[2] = {{list, panel ? b->n_heavy[op] : n_all, panel ? panel_mode : coop ? kModeCoop : deep ? kModeDeep : kModeBlocks},
                            {list + b->n_heavy[op], panel ? n_all - b->n_heavy[op] : 0, kModeBlocks}};
     plora_pool::ProfRec rec{op, nullptr, nullptr};
     if (p->profiling) {

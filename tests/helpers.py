@@ -100,13 +100,16 @@ class Case:
         # plora_delta (one launch over a task queue); with the panel kernel for every large group (as in a
         # prefill batch) and two runs in flight in every matrix-core shrink item, through plora_delta
         # (block lists in the one launch when the batch has no panel blocks); and with the library's own
-        # choices last (its outputs are returned).  Each entry: (cooperative limit, panel_min_blocks,
-        # mfma_shrink_depth, entry points).
-        for coop, panel, depth, api in getattr(self, "kernel_modes", ((1 << 30, 8, 1, "pair"), (1 << 30, 8, 1, "delta"), (0, 1, 2, "delta"),
-                                                                      (0, 8, 0, "pair"))):
+        # choices last (its outputs are returned).  The panel kernel runs in both of its forms: one workgroup
+        # per 512 columns, and one per 256.  Each entry: (cooperative limit, panel_min_blocks,
+        # mfma_shrink_depth, entry points[, panel_half_max_workgroups; default: the library's 8192]).
+        for mode in getattr(self, "kernel_modes", ((1 << 30, 8, 1, "pair"), (1 << 30, 8, 1, "delta"), (0, 1, 2, "delta", 0),
+                                                   (0, 1, 1, "pair", 1 << 40), (0, 8, 0, "pair"))):
+            coop, panel, depth, api = mode[:4]
             self.gpool.set_option("coop_max_workgroups_shrink", coop)
             self.gpool.set_option("coop_max_workgroups_expand", coop)
             self.gpool.set_option("panel_min_blocks", panel)
+            self.gpool.set_option("panel_half_max_workgroups", mode[4] if len(mode) > 4 else 8192)
             self.gpool.set_option("mfma_shrink_depth", depth)
             self.gpool.set_option("fused_max_tasks", 1 << 20 if api == "delta" else 0)  # plora_delta as one launch where it applies
             out = self._run_gpu(t2a, slots, xs, y0, check, api)

@@ -16,11 +16,13 @@ from helpers import TOL_V, TOL_Y, rel_err, torch_to_raw
 pytestmark = pytest.mark.gpu
 
 
-def _run(oracle_mod, name, slots_per_call=0):
+def _run(oracle_mod, name, slots_per_call=0, options=()):
     import torch
     import bench
     t0 = time.time()
     w = bench.GpuWorkload(name, verbose=True)
+    for key, value in options:
+        w.pool.set_option(key, value)
     lay, cfg = w.lay, w.cfg
     rng = np.random.default_rng(cfg["seed"] + 7)
     t2a = bench.draw_batch(cfg, rng, w.n_ad)
@@ -84,6 +86,11 @@ def test_cfg1_decode_7b_one_layer_per_call(oracle_mod):
 
 def test_cfg2_prefill_full_size(oracle_mod):
     _run(oracle_mod, "cfg2")
+
+
+def test_cfg2_prefill_full_size_panel_workgroups_of_512_columns(oracle_mod):
+    """The form of the panel kernel that launches of more than 8192 workgroups take (a 4-slot call has fewer)."""
+    _run(oracle_mod, "cfg2", options=(("panel_half_max_workgroups", 0),))
 
 
 def test_cfg4_decode_13b_layer_full_size(oracle_mod):

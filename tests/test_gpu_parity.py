@@ -142,6 +142,26 @@ def test_large_groups_panels_and_odd_strides(oracle_mod, dtype):
     case.close()
 
 
+@pytest.mark.parametrize("dtype", [DT_BF16, DT_F16])
+def test_panel_kernel_forms_agree_bit_for_bit(oracle_mod, dtype):
+    """The panel kernel with one workgroup per 512 columns and with one per 256 (option
+    panel_half_max_workgroups) forms every element of y by the same sequence of operations: same bits.
+    Widths that end inside the first half, inside the second, and on their boundaries."""
+    lay = Layout((264, 520, 128, 256), (200, 776, 256, 512), dtype)
+    ranks = [64, 24, 130, 7]
+    case = Case(oracle_mod, lay, ranks, [16.0 / r for r in ranks], 64 << 10, 48, seed=77, max_rank=130, mfma_min_tokens=5)
+    t2a = np.concatenate([np.full(n, a, np.int32) for a, n in zip(range(4), (200, 150, 90, 64))])
+    np.random.default_rng(9).shuffle(t2a)
+    got = []
+    for half in (0, 1 << 40):
+        case.kernel_modes = ((0, 1, 0, "pair", half),)
+        out = case.run(t2a, seed=4)
+        got.append([o["y_got"].copy() for o in out])
+    for s, (y_full, y_half) in enumerate(zip(*got)):
+        assert (y_full.view(np.uint16) == y_half.view(np.uint16)).all(), "slot %d: the two forms differ" % s
+    case.close()
+
+
 def test_many_small_adapters_64k_pages(oracle_mod):
     """200 adapters of ranks 1..16 on 64 KiB pages, most tokens alone with their adapter."""
     lay = Layout((512,), (1024,), DT_BF16)

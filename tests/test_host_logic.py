@@ -218,7 +218,7 @@ def test_pool_create_rejects_bad_arguments():
 def test_options_validate():
     import paper_2512_20210_amd as B
     g = B.PagedLoraPool(4096, 4, [64], [64], B.PLORA_BF16, 4, 16, placement_only=True)
-    for key, good, bad in (("mfma_min_tokens", 3, -1), ("mfma_min_tokens_expand", 0, -2), ("mfma_min_work", 1, 0), ("coop_max_workgroups_shrink", 0, -1), ("batches_per_marker", 1, 0), ("staging_min_runs", 1, 0), ("panel_min_blocks", 0, -1), ("mfma_cols_max_group", 64, -1), ("mfma_shrink_depth", 2, 3), ("mfma_shrink_depth", 0, -1), ("batches_per_marker", 64, 65), ("coop_max_workgroups_expand", 5000, -1),
+    for key, good, bad in (("mfma_min_tokens", 3, -1), ("mfma_min_tokens_expand", 0, -2), ("mfma_min_work", 1, 0), ("coop_max_workgroups_shrink", 0, -1), ("batches_per_marker", 1, 0), ("staging_min_runs", 1, 0), ("panel_min_blocks", 0, -1), ("panel_half_max_workgroups", 0, -1), ("mfma_cols_max_group", 64, -1), ("mfma_shrink_depth", 2, 3), ("mfma_shrink_depth", 0, -1), ("batches_per_marker", 64, 65), ("coop_max_workgroups_expand", 5000, -1),
                            ("mfma_min_work_expand", 1000, -5), ("xcd_remap", 1, 5), ("slot_major", -1, 2), ("slot_major_expand", 2, 3), ("slot_major_shrink", 1, 2), ("xcd_remap_expand", 0, 2)):
         assert B.plora_pool_set_option(g.h, key, good) == B.PLORA_OK
         assert B.plora_pool_set_option(g.h, key, bad) == B.PLORA_ERR_INVAL
