@@ -31,12 +31,12 @@ HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 # digest of the kernel and host sources it was measured on (kernel_sources_digest below): the
 # figure is reported only while the sources are still those, and null as soon as they change.
 MEASURED_TRAFFIC = {
-    "cfg1": dict(shrink=1.8132e9, expand=2.0987e9, profile="profiles/decode_7b_cfg1_kernels_and_hbm_traffic.md",
-                 sources="bbb4c8617d0d5574"),
-    "cfg4": dict(shrink=2.3184e9, expand=2.4507e9, profile="profiles/decode_13b_layer_cfg4_kernels_and_hbm_traffic.md",
-                 sources="bbb4c8617d0d5574"),
-    "cfg2": dict(shrink=0.2770e9, expand=0.4000e9, profile="profiles/prefill_cfg2_kernels_traffic_and_mfma_activity.md",
-                 sources="bbb4c8617d0d5574"),
+    "cfg1": dict(shrink=1.8127e9, expand=2.0986e9, profile="profiles/decode_7b_cfg1_kernels_and_hbm_traffic.md",
+                 sources="6fbd2d03f7d51c49"),
+    "cfg4": dict(shrink=2.3184e9, expand=2.4506e9, profile="profiles/decode_13b_layer_cfg4_kernels_and_hbm_traffic.md",
+                 sources="6fbd2d03f7d51c49"),
+    "cfg2": dict(shrink=0.2768e9, expand=0.4052e9, profile="profiles/prefill_cfg2_kernels_traffic_and_mfma_activity.md",
+                 sources="6fbd2d03f7d51c49"),
 }
 METRIC = "paged LoRA shrink+expand HBM GB/s (% of peak) + tokens/s, 256-token decode"
 KCLASS = ["shrink", "expand", "delta"]
